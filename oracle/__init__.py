@@ -1,0 +1,6 @@
+"""CPU oracle for the Write-Gated KV hot path -- TEST INFRASTRUCTURE ONLY.
+
+Nothing in the product package may import this.  See wgkv_oracle.c for what it
+computes and which passages of the paper each part follows.
+"""
+from .wgkv_oracle import Oracle, OracleConfig, attend_definition, attend_soft, linear_gate  # noqa: F401

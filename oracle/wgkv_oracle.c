@@ -1,0 +1,549 @@
+/*
+ * wgkv_oracle.c -- TEST INFRASTRUCTURE, not product code.
+ *
+ * A plain, slow, single-purpose CPU reference for the Write-Gated KV hot path
+ * ("KV Admission: Learning What to Write for Efficient Long-Context LLM
+ * Inference").  It exists so that the GPU library can be checked against
+ * something written straight from the paper.  It shares no code, header, table
+ * or helper with the GPU library, and only tests, the smoke check and the
+ * benchmark's cpu_baseline leg may call it.
+ *
+ * Two halves that must agree with each other:
+ *
+ *  (1) the DEFINITION of the result: attention of a query at position i over
+ *      the keys j <= i that the vertical-slash mask leaves visible,
+ *        M_ij = (1(i-j < W_local) or 1(g_j >= tau)) and 1(i >= j)
+ *      (Sec. 4.2 "Vertical-slash sparse attention", mask equation) applied to
+ *      scaled-dot-product attention (Sec. 2.1 equation; Sec. 3.2 first
+ *      equation of "Write-Gated Attention").  This half keeps the whole,
+ *      undropped K/V/g history and never looks at rings, pages or pointers.
+ *
+ *  (2) the MECHANISM that the system section describes, simulated one token
+ *      at a time with ordinary arrays: a ring-buffer local cache of W_local
+ *      slots, a growing global cache, per-head page tables onto one physical
+ *      pool (Sec. 4.1), initial cache population (Sec. 4.2) and lazy promotion
+ *      (Sec. 4.3, steps (1)-(3)).
+ *
+ * All floating-point work is done in double; inputs arrive as float (the
+ * exact widening of bf16 or fp32 data).  Threshold tests are done on the
+ * stored fp32 score with the C `>=` operator, so a NaN score never admits.
+ *
+ * Readings where the paper is silent (the same list is in the design notes):
+ *  - ring slot of position p is p mod W_local; the local pointer is t mod W.
+ *  - the window contains the token itself (i-j < W with j <= i).
+ *  - the global cache is ordered by position (victims leave in order).
+ *  - the ring stores the fp32 score; the tau of the evicting call decides.
+ *  - attention in decode is taken after the write of the new token.
+ *  - pages: a LIFO free stack, free_stack[i] = n_pages-1-i, pop takes
+ *    free_stack[--free_top].  Within one call page demands are served unit by
+ *    unit, units ordered by (position of the sequence in the call, kv head);
+ *    a unit's ceil(W/P) local pages are taken at its first use, before any of
+ *    its global pages.  This rule is this project's own: the paper fixes no
+ *    allocation order, so physical page ids are "parity unpinned" with
+ *    respect to the paper; everything else below is pinned by the tests.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_OK 0
+#define ORC_ERR_ARG (-1)
+#define ORC_ERR_OUT_OF_PAGES (-2)
+#define ORC_ERR_PT_OVERFLOW (-3)
+#define ORC_ERR_NOMEM (-4)
+
+typedef struct {
+    int32_t n_layers, n_q_heads, n_kv_heads, head_dim;
+    int32_t page_size, w_local, max_seqs, max_global_pages;
+    int64_t n_pages;
+    int32_t keep_payload; /* 0: integer state only (scores, positions, pages) */
+} orc_config;
+
+typedef struct {
+    int64_t glen, gcap;
+    int64_t *gpos;        /* position of every global entry, ascending */
+    float *gk, *gv;       /* [gcap][d] when payload is kept            */
+    float *ring_g;        /* [W] stored score of the slot's token      */
+    int64_t *ring_pos;    /* [W] position held by the slot, -1 = empty */
+    float *ring_k, *ring_v; /* [W][d] when payload is kept            */
+    int32_t *local_pt;    /* [ceil(W/P)]                               */
+    int32_t *global_pt;   /* [max_global_pages], -1 = unused           */
+} orc_head;
+
+typedef struct {
+    int64_t t;     /* tokens seen so far by this (sequence, layer) */
+    int touched;   /* local pages handed out                        */
+    orc_head *h;   /* [n_kv_heads]                                  */
+} orc_sl;
+
+typedef struct {
+    orc_config c;
+    int n_local_pages;
+    orc_sl *sl; /* [max_seqs][n_layers] */
+    int32_t *free_stack;
+    int64_t free_top;
+} orc_state;
+
+static orc_sl *get_sl(orc_state *S, int seq, int layer) {
+    return &S->sl[(size_t)seq * S->c.n_layers + layer];
+}
+
+int orc_n_local_pages(const orc_state *S) { return S->n_local_pages; }
+
+void orc_destroy(orc_state *S) {
+    if (!S) return;
+    if (S->sl) {
+        size_t n = (size_t)S->c.max_seqs * S->c.n_layers;
+        for (size_t i = 0; i < n; i++) {
+            if (!S->sl[i].h) continue;
+            for (int h = 0; h < S->c.n_kv_heads; h++) {
+                orc_head *H = &S->sl[i].h[h];
+                free(H->gpos); free(H->gk); free(H->gv);
+                free(H->ring_g); free(H->ring_pos);
+                free(H->ring_k); free(H->ring_v);
+                free(H->local_pt); free(H->global_pt);
+            }
+            free(S->sl[i].h);
+        }
+        free(S->sl);
+    }
+    free(S->free_stack);
+    free(S);
+}
+
+static void reset_head(orc_state *S, orc_head *H) {
+    const int W = S->c.w_local;
+    H->glen = 0;
+    for (int s = 0; s < W; s++) { H->ring_g[s] = 0.0f; H->ring_pos[s] = -1; }
+    for (int i = 0; i < S->n_local_pages; i++) H->local_pt[i] = -1;
+    for (int i = 0; i < S->c.max_global_pages; i++) H->global_pt[i] = -1;
+}
+
+orc_state *orc_create(const orc_config *c) {
+    if (!c || c->n_layers < 1 || c->n_kv_heads < 1 || c->n_q_heads < c->n_kv_heads ||
+        c->n_q_heads % c->n_kv_heads || c->head_dim < 1 || c->page_size < 1 ||
+        c->w_local < 1 || c->max_seqs < 1 || c->max_global_pages < 0 || c->n_pages < 0)
+        return NULL;
+    orc_state *S = (orc_state *)calloc(1, sizeof(orc_state));
+    if (!S) return NULL;
+    S->c = *c;
+    S->n_local_pages = (c->w_local + c->page_size - 1) / c->page_size;
+    size_t n = (size_t)c->max_seqs * c->n_layers;
+    S->sl = (orc_sl *)calloc(n, sizeof(orc_sl));
+    S->free_stack = (int32_t *)malloc(sizeof(int32_t) * (size_t)(c->n_pages > 0 ? c->n_pages : 1));
+    if (!S->sl || !S->free_stack) { orc_destroy(S); return NULL; }
+    for (int64_t i = 0; i < c->n_pages; i++) S->free_stack[i] = (int32_t)(c->n_pages - 1 - i);
+    S->free_top = c->n_pages;
+    const int W = c->w_local, d = c->head_dim;
+    for (size_t i = 0; i < n; i++) {
+        S->sl[i].h = (orc_head *)calloc((size_t)c->n_kv_heads, sizeof(orc_head));
+        if (!S->sl[i].h) { orc_destroy(S); return NULL; }
+        for (int h = 0; h < c->n_kv_heads; h++) {
+            orc_head *H = &S->sl[i].h[h];
+            H->ring_g = (float *)malloc(sizeof(float) * W);
+            H->ring_pos = (int64_t *)malloc(sizeof(int64_t) * W);
+            H->local_pt = (int32_t *)malloc(sizeof(int32_t) * S->n_local_pages);
+            H->global_pt = (int32_t *)malloc(sizeof(int32_t) * (size_t)(c->max_global_pages > 0 ? c->max_global_pages : 1));
+            if (c->keep_payload) {
+                H->ring_k = (float *)calloc((size_t)W * d, sizeof(float));
+                H->ring_v = (float *)calloc((size_t)W * d, sizeof(float));
+            }
+            if (!H->ring_g || !H->ring_pos || !H->local_pt || !H->global_pt ||
+                (c->keep_payload && (!H->ring_k || !H->ring_v))) { orc_destroy(S); return NULL; }
+            reset_head(S, H);
+        }
+    }
+    return S;
+}
+
+static int pop_page(orc_state *S, int32_t *page) {
+    if (S->free_top <= 0) return ORC_ERR_OUT_OF_PAGES;
+    *page = S->free_stack[--S->free_top];
+    return ORC_OK;
+}
+
+/* Sec. 4.3 steps (1)-(3) for one head: look at the victim under the local
+ * pointer, promote it when its stored score passes the threshold, then let the
+ * new token take the slot.  Position p is the new token's; the victim, if the
+ * ring is already full, is position p - W. */
+static int push_one(orc_state *S, orc_head *H, int64_t p, const float *k, const float *v,
+                    float g, float tau, int *promoted) {
+    const int W = S->c.w_local, P = S->c.page_size, d = S->c.head_dim;
+    const int s = (int)(p % W); /* local pointer */
+    *promoted = 0;
+    if (p >= W) {
+        if (H->ring_g[s] >= tau) { /* victim passes the gate */
+            if (H->glen % P == 0) { /* the global pointer enters a new page */
+                int64_t lp = H->glen / P;
+                if (lp >= S->c.max_global_pages) return ORC_ERR_PT_OVERFLOW;
+                int32_t page;
+                int rc = pop_page(S, &page);
+                if (rc) return rc;
+                H->global_pt[lp] = page;
+            }
+            if (H->glen == H->gcap) {
+                int64_t nc = H->gcap ? H->gcap * 2 : 64;
+                int64_t *np_ = (int64_t *)realloc(H->gpos, sizeof(int64_t) * nc);
+                if (!np_) return ORC_ERR_NOMEM;
+                H->gpos = np_;
+                if (S->c.keep_payload) {
+                    float *nk = (float *)realloc(H->gk, sizeof(float) * nc * d);
+                    if (!nk) return ORC_ERR_NOMEM;
+                    H->gk = nk;
+                    float *nv = (float *)realloc(H->gv, sizeof(float) * nc * d);
+                    if (!nv) return ORC_ERR_NOMEM;
+                    H->gv = nv;
+                }
+                H->gcap = nc;
+            }
+            H->gpos[H->glen] = H->ring_pos[s];
+            if (S->c.keep_payload) {
+                memcpy(H->gk + H->glen * d, H->ring_k + (size_t)s * d, sizeof(float) * d);
+                memcpy(H->gv + H->glen * d, H->ring_v + (size_t)s * d, sizeof(float) * d);
+            }
+            H->glen += 1; /* global pointer advances */
+            *promoted = 1;
+        }
+        /* else: the victim leaves the window unadmitted and is gone */
+    }
+    H->ring_g[s] = g;
+    H->ring_pos[s] = p;
+    if (S->c.keep_payload) {
+        memcpy(H->ring_k + (size_t)s * d, k, sizeof(float) * d);
+        memcpy(H->ring_v + (size_t)s * d, v, sizeof(float) * d);
+    }
+    return ORC_OK;
+}
+
+/*
+ * Feed tokens to one layer of several sequences.  Prefill (Sec. 4.2 "Initial
+ * cache population"), a prefill chunk and a decode step (Sec. 4.3) are all the
+ * same thing here: n_tokens[b] pushes for sequence seq_ids[b].
+ *   k, v : [sum n_tokens][n_kv_heads][d] floats (NULL allowed without payload)
+ *   g    : [sum n_tokens][n_kv_heads] scores
+ *   admit_out    (optional) [sum n_tokens][n_kv_heads]: 1(g >= tau)  (Sec. 3.3, last sentence)
+ *   promoted_out (optional) same shape: 1 when the push of that token moved
+ *                its victim into the global cache.
+ */
+int orc_push_tokens(orc_state *S, int layer, int n_seqs, const int32_t *seq_ids,
+                    const int32_t *n_tokens, const float *k, const float *v, const float *g,
+                    float tau, uint8_t *admit_out, uint8_t *promoted_out) {
+    if (!S || layer < 0 || layer >= S->c.n_layers || n_seqs < 0) return ORC_ERR_ARG;
+    const int Hk = S->c.n_kv_heads, d = S->c.head_dim;
+    if (S->c.keep_payload && (!k || !v)) return ORC_ERR_ARG;
+    int64_t base = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        int seq = seq_ids[b];
+        if (seq < 0 || seq >= S->c.max_seqs || n_tokens[b] < 0) return ORC_ERR_ARG;
+        for (int b2 = 0; b2 < b; b2++) if (seq_ids[b2] == seq) return ORC_ERR_ARG;
+        base += n_tokens[b];
+    }
+    base = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        orc_sl *sl = get_sl(S, seq_ids[b], layer);
+        const int T = n_tokens[b];
+        for (int h = 0; h < Hk; h++) {
+            orc_head *H = &sl->h[h];
+            if (!sl->touched && T > 0) {
+                for (int i = 0; i < S->n_local_pages; i++) {
+                    int rc = pop_page(S, &H->local_pt[i]);
+                    if (rc) return rc;
+                }
+            }
+            for (int i = 0; i < T; i++) {
+                size_t row = (size_t)(base + i) * Hk + h;
+                int promoted = 0;
+                int rc = push_one(S, H, sl->t + i, k ? k + row * d : NULL, v ? v + row * d : NULL,
+                                  g[row], tau, &promoted);
+                if (rc) return rc;
+                if (admit_out) admit_out[row] = (uint8_t)(g[row] >= tau);
+                if (promoted_out) promoted_out[row] = (uint8_t)promoted;
+            }
+        }
+        if (T > 0) sl->touched = 1;
+        sl->t += T;
+        base += T;
+    }
+    return ORC_OK;
+}
+
+/* Give every page of a sequence slot back: layers ascending, kv heads
+ * ascending, a unit's local pages then its global pages, each ascending. */
+int orc_free_seq(orc_state *S, int seq) {
+    if (!S || seq < 0 || seq >= S->c.max_seqs) return ORC_ERR_ARG;
+    const int P = S->c.page_size;
+    for (int l = 0; l < S->c.n_layers; l++) {
+        orc_sl *sl = get_sl(S, seq, l);
+        for (int h = 0; h < S->c.n_kv_heads; h++) {
+            orc_head *H = &sl->h[h];
+            if (sl->touched) {
+                for (int i = 0; i < S->n_local_pages; i++) S->free_stack[S->free_top++] = H->local_pt[i];
+                int64_t ngp = (H->glen + P - 1) / P;
+                for (int64_t i = 0; i < ngp; i++) S->free_stack[S->free_top++] = H->global_pt[i];
+            }
+            reset_head(S, H);
+        }
+        sl->t = 0;
+        sl->touched = 0;
+    }
+    return ORC_OK;
+}
+
+/* ---- state read-out (for bit-exact comparison) ---- */
+
+int64_t orc_seq_len(const orc_state *S, int seq, int layer) {
+    return S->sl[(size_t)seq * S->c.n_layers + layer].t;
+}
+int64_t orc_global_len(const orc_state *S, int seq, int layer, int h) {
+    return S->sl[(size_t)seq * S->c.n_layers + layer].h[h].glen;
+}
+int64_t orc_free_top(const orc_state *S) { return S->free_top; }
+void orc_get_free_stack(const orc_state *S, int32_t *out) {
+    memcpy(out, S->free_stack, sizeof(int32_t) * (size_t)S->c.n_pages);
+}
+void orc_get_head_tables(const orc_state *S, int seq, int layer, int h, int32_t *local_pt,
+                         int32_t *global_pt, float *ring_g, int64_t *ring_pos) {
+    const orc_head *H = &S->sl[(size_t)seq * S->c.n_layers + layer].h[h];
+    if (local_pt) memcpy(local_pt, H->local_pt, sizeof(int32_t) * S->n_local_pages);
+    if (global_pt) memcpy(global_pt, H->global_pt, sizeof(int32_t) * (size_t)S->c.max_global_pages);
+    if (ring_g) memcpy(ring_g, H->ring_g, sizeof(float) * S->c.w_local);
+    if (ring_pos) memcpy(ring_pos, H->ring_pos, sizeof(int64_t) * S->c.w_local);
+}
+void orc_get_global_pos(const orc_state *S, int seq, int layer, int h, int64_t *out) {
+    const orc_head *H = &S->sl[(size_t)seq * S->c.n_layers + layer].h[h];
+    memcpy(out, H->gpos, sizeof(int64_t) * (size_t)H->glen);
+}
+/* cached rows: global entries in order, then ring slots 0..W-1 */
+int orc_get_payload(const orc_state *S, int seq, int layer, int h, float *gk, float *gv,
+                    float *ring_k, float *ring_v) {
+    if (!S->c.keep_payload) return ORC_ERR_ARG;
+    const orc_head *H = &S->sl[(size_t)seq * S->c.n_layers + layer].h[h];
+    const size_t d = S->c.head_dim;
+    if (gk) memcpy(gk, H->gk, sizeof(float) * H->glen * d);
+    if (gv) memcpy(gv, H->gv, sizeof(float) * H->glen * d);
+    if (ring_k) memcpy(ring_k, H->ring_k, sizeof(float) * S->c.w_local * d);
+    if (ring_v) memcpy(ring_v, H->ring_v, sizeof(float) * S->c.w_local * d);
+    return ORC_OK;
+}
+
+/* ---- attention ---- */
+
+/* softmax(scores) . V for one query head, everything in double, max-subtracted
+ * (Sec. 2.1 equation).  rows[n] point at the K and V vectors of the keys.  */
+static void softmax_av(const float *q, const float *const *krows, const float *const *vrows,
+                       int64_t n, int d, double scale, double *scores, double *out) {
+    double mx = -INFINITY;
+    for (int64_t j = 0; j < n; j++) {
+        double s = 0.0;
+        for (int e = 0; e < d; e++) s += (double)q[e] * (double)krows[j][e];
+        s *= scale;
+        scores[j] = s;
+        if (s > mx) mx = s;
+    }
+    double den = 0.0;
+    for (int64_t j = 0; j < n; j++) { scores[j] = exp(scores[j] - mx); den += scores[j]; }
+    for (int e = 0; e < d; e++) out[e] = 0.0;
+    for (int64_t j = 0; j < n; j++) {
+        double w = scores[j] / den;
+        for (int e = 0; e < d; e++) out[e] += w * (double)vrows[j][e];
+    }
+}
+
+/* Mechanism attention for one sequence/layer after the pushes so far: every
+ * query head of a group reads its kv head's global entries and valid ring
+ * slots (Sec. 4.3, last sentence).  q: [n_q_heads][d], out: [n_q_heads][d]. */
+int orc_attend_cached(const orc_state *S, int seq, int layer, const float *q, double scale,
+                      double *out) {
+    if (!S || !S->c.keep_payload) return ORC_ERR_ARG;
+    const int Hq = S->c.n_q_heads, Hk = S->c.n_kv_heads, d = S->c.head_dim, W = S->c.w_local;
+    const int G = Hq / Hk;
+    const orc_sl *sl = &S->sl[(size_t)seq * S->c.n_layers + layer];
+    for (int h = 0; h < Hk; h++) {
+        const orc_head *H = &sl->h[h];
+        int64_t n = H->glen;
+        for (int s = 0; s < W; s++) if (H->ring_pos[s] >= 0) n++;
+        if (n == 0) { /* nothing cached: define the output as zero */
+            for (int qh = h * G; qh < (h + 1) * G; qh++)
+                for (int e = 0; e < d; e++) out[(size_t)qh * d + e] = 0.0;
+            continue;
+        }
+        const float **kr = (const float **)malloc(sizeof(float *) * n);
+        const float **vr = (const float **)malloc(sizeof(float *) * n);
+        double *sc = (double *)malloc(sizeof(double) * n);
+        if (!kr || !vr || !sc) { free(kr); free(vr); free(sc); return ORC_ERR_NOMEM; }
+        int64_t c = 0;
+        for (int64_t i = 0; i < H->glen; i++, c++) { kr[c] = H->gk + i * d; vr[c] = H->gv + i * d; }
+        for (int s = 0; s < W; s++)
+            if (H->ring_pos[s] >= 0) { kr[c] = H->ring_k + (size_t)s * d; vr[c] = H->ring_v + (size_t)s * d; c++; }
+        for (int qh = h * G; qh < (h + 1) * G; qh++)
+            softmax_av(q + (size_t)qh * d, kr, vr, n, d, scale, sc, out + (size_t)qh * d);
+        free(kr); free(vr); free(sc);
+    }
+    return ORC_OK;
+}
+
+/* The same for several sequences at once (one decode step of one layer);
+ * independent (sequence, kv head) units run on separate host threads and
+ * nothing else is parallel.  q/out: [n_seqs][n_q_heads][d]. */
+int orc_attend_cached_batch(const orc_state *S, int layer, int n_seqs, const int32_t *seq_ids,
+                            const float *q, double scale, double *out, int *threads_used) {
+    if (!S || !S->c.keep_payload) return ORC_ERR_ARG;
+    const int Hq = S->c.n_q_heads, Hk = S->c.n_kv_heads, d = S->c.head_dim, W = S->c.w_local;
+    const int G = Hq / Hk;
+    int rc_all = ORC_OK, nthr = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp single
+        nthr = omp_get_num_threads();
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int u = 0; u < n_seqs * Hk; u++) {
+        const int b = u / Hk, h = u % Hk;
+        const orc_head *H = &S->sl[(size_t)seq_ids[b] * S->c.n_layers + layer].h[h];
+        int64_t n = H->glen;
+        for (int s = 0; s < W; s++) if (H->ring_pos[s] >= 0) n++;
+        double *o = out + ((size_t)b * Hq + (size_t)h * G) * d;
+        if (n == 0) { for (int e = 0; e < G * d; e++) o[e] = 0.0; continue; }
+        const float **kr = (const float **)malloc(sizeof(float *) * n);
+        const float **vr = (const float **)malloc(sizeof(float *) * n);
+        double *sc = (double *)malloc(sizeof(double) * n);
+        if (!kr || !vr || !sc) { free(kr); free(vr); free(sc); rc_all = ORC_ERR_NOMEM; continue; }
+        int64_t c = 0;
+        for (int64_t i = 0; i < H->glen; i++, c++) { kr[c] = H->gk + i * d; vr[c] = H->gv + i * d; }
+        for (int s = 0; s < W; s++)
+            if (H->ring_pos[s] >= 0) { kr[c] = H->ring_k + (size_t)s * d; vr[c] = H->ring_v + (size_t)s * d; c++; }
+        for (int j = 0; j < G; j++)
+            softmax_av(q + ((size_t)b * Hq + (size_t)h * G + j) * d, kr, vr, n, d, scale, sc, o + (size_t)j * d);
+        free(kr); free(vr); free(sc);
+    }
+    if (threads_used) *threads_used = nthr;
+    return rc_all;
+}
+
+/*
+ * Definition attention (Sec. 4.2 mask equation on Sec. 2.1 attention) from the
+ * full history of ONE sequence/layer:
+ *   K, V : [n_hist][n_kv_heads][d]     g : [n_hist][n_kv_heads]
+ *   q    : [n_q][n_q_heads][d]         q_pos[n_q] : position i of each query
+ * Key j is visible to query i iff j <= i and (i - j < W  or  g_j >= tau).
+ * out: [n_q][n_q_heads][d] doubles.
+ */
+int orc_attend_definition(int n_q_heads, int n_kv_heads, int d, int w_local, float tau,
+                          double scale, int64_t n_hist, const float *K, const float *V,
+                          const float *g, int64_t n_q, const float *q, const int64_t *q_pos,
+                          double *out) {
+    if (n_q_heads % n_kv_heads) return ORC_ERR_ARG;
+    const int G = n_q_heads / n_kv_heads;
+    int rc_all = ORC_OK;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int64_t r = 0; r < n_q; r++) {
+        const int64_t i = q_pos[r];
+        if (i < 0 || i >= n_hist) { rc_all = ORC_ERR_ARG; continue; }
+        const float **kr = (const float **)malloc(sizeof(float *) * (size_t)(i + 1));
+        const float **vr = (const float **)malloc(sizeof(float *) * (size_t)(i + 1));
+        double *sc = (double *)malloc(sizeof(double) * (size_t)(i + 1));
+        if (!kr || !vr || !sc) { free(kr); free(vr); free(sc); rc_all = ORC_ERR_NOMEM; continue; }
+        for (int h = 0; h < n_kv_heads; h++) {
+            int64_t n = 0;
+            for (int64_t j = 0; j <= i; j++) {
+                size_t row = (size_t)j * n_kv_heads + h;
+                if ((i - j < w_local) || (g[row] >= tau)) {
+                    kr[n] = K + row * d; vr[n] = V + row * d; n++;
+                }
+            }
+            for (int jq = 0; jq < G; jq++) {
+                size_t qh = (size_t)h * G + jq;
+                softmax_av(q + ((size_t)r * n_q_heads + qh) * d, kr, vr, n, d, scale, sc,
+                           out + ((size_t)r * n_q_heads + qh) * d);
+            }
+        }
+        free(kr); free(vr); free(sc);
+    }
+    return rc_all;
+}
+
+/*
+ * Training-time soft form of the same attention (Sec. 3.2, "Write-Gated
+ * Attention" equation): weights exp(s_ij) * m_ij with
+ * m_ij = max(1(i-j < W), g_j); with eps >= 0 the log-space form
+ * exp(s_ij + log(m_ij + eps)) is used instead when use_log != 0.
+ * With binary g it must reproduce orc_attend_definition; kept only as a
+ * cross-check of the mask code.
+ */
+int orc_attend_soft(int n_q_heads, int n_kv_heads, int d, int w_local, double scale,
+                    int64_t n_hist, const float *K, const float *V, const float *g,
+                    int64_t n_q, const float *q, const int64_t *q_pos, int use_log, double eps,
+                    double *out) {
+    if (n_q_heads % n_kv_heads) return ORC_ERR_ARG;
+    const int G = n_q_heads / n_kv_heads;
+    for (int64_t r = 0; r < n_q; r++) {
+        const int64_t i = q_pos[r];
+        if (i < 0 || i >= n_hist) return ORC_ERR_ARG;
+        double *sc = (double *)malloc(sizeof(double) * (size_t)(i + 1));
+        if (!sc) return ORC_ERR_NOMEM;
+        for (int qh = 0; qh < n_q_heads; qh++) {
+            const int h = qh / G;
+            const float *qv = q + ((size_t)r * n_q_heads + qh) * d;
+            double mx = -INFINITY;
+            for (int64_t j = 0; j <= i; j++) {
+                size_t row = (size_t)j * n_kv_heads + h;
+                double s = 0.0;
+                for (int e = 0; e < d; e++) s += (double)qv[e] * (double)K[row * d + e];
+                s *= scale;
+                double m = (i - j < w_local) ? 1.0 : 0.0;
+                if ((double)g[row] > m) m = (double)g[row];
+                if (use_log) { s += log(m + eps); sc[j] = s; }
+                else sc[j] = s; /* weight applied below */
+                if (s > mx && (use_log || m > 0.0)) mx = s;
+            }
+            double den = 0.0;
+            double *o = out + ((size_t)r * n_q_heads + qh) * d;
+            for (int e = 0; e < d; e++) o[e] = 0.0;
+            for (int64_t j = 0; j <= i; j++) {
+                size_t row = (size_t)j * n_kv_heads + h;
+                double w = exp(sc[j] - mx);
+                if (!use_log) {
+                    double m = (i - j < w_local) ? 1.0 : 0.0;
+                    if ((double)g[row] > m) m = (double)g[row];
+                    w *= m;
+                }
+                sc[j] = w;
+                den += w;
+            }
+            for (int64_t j = 0; j <= i; j++) {
+                size_t row = (size_t)j * n_kv_heads + h;
+                double w = sc[j] / den;
+                for (int e = 0; e < d; e++) o[e] += w * (double)V[row * d + e];
+            }
+        }
+        free(sc);
+    }
+    return ORC_OK;
+}
+
+/*
+ * Linear write gate used by the chunked-prefill workload: one weight vector
+ * per kv head on the layer's hidden state, g = sigmoid(w_h . x_t), i.e. the
+ * Sec. 3.2 gate equation with the hidden layer removed.
+ *   hidden: [T][dim], w: [n_kv_heads][dim]; logit_out, g_out: [T][n_kv_heads].
+ */
+int orc_linear_gate(int64_t T, int dim, int n_kv_heads, const float *hidden, const float *w,
+                    double *logit_out, double *g_out) {
+    for (int64_t t = 0; t < T; t++)
+        for (int h = 0; h < n_kv_heads; h++) {
+            double s = 0.0;
+            for (int e = 0; e < dim; e++) s += (double)hidden[t * dim + e] * (double)w[(size_t)h * dim + e];
+            if (logit_out) logit_out[t * n_kv_heads + h] = s;
+            if (g_out) g_out[t * n_kv_heads + h] = 1.0 / (1.0 + exp(-s));
+        }
+    return ORC_OK;
+}
