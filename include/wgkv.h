@@ -1,0 +1,191 @@
+/*
+ * wgkv.h -- C ABI of the Write-Gated KV hot path for AMD MI355X (gfx950).
+ *
+ * What the library does ("KV Admission: Learning What to Write for Efficient
+ * Long-Context LLM Inference"):
+ *   - a per-token, per-KV-head write gate decides admission before any write:
+ *     admit <=> g >= tau (Sec. 3.3, last sentence);
+ *   - every head keeps a dual cache: a ring-buffer local window of W_local slots
+ *     and a growing global cache, both mapped through per-head page tables onto
+ *     one physical pool of fixed-size pages (Sec. 4.1);
+ *   - prefill writes the final W_local tokens to the local cache and earlier
+ *     tokens to the global cache only if admitted (Sec. 4.2, "Initial cache
+ *     population"); decode promotes lazily: the token leaving the window is
+ *     inspected and, if its stored score passes tau, moved to the global cache
+ *     before the new token takes its slot (Sec. 4.3, steps (1)-(3));
+ *   - attention reads local window + global cache of the query's KV head,
+ *     ragged across heads (Sec. 4.3 last sentence; App. A; App. E "Decode
+ *     phase": split the ragged work into uniform pieces, then reduce), which is
+ *     attention under the vertical-slash mask of Sec. 4.2.
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses.  The library never allocates, frees or owns device memory: the
+ *     caller provides the pool, the metadata block and a workspace and keeps
+ *     them alive until wgkv_destroy.  The handle itself is host heap memory.
+ *   - All path calls (prefill_admit, decode_step, attend, gate_scores, free_seq)
+ *     only enqueue kernels on the given stream (a hipStream_t passed as void*)
+ *     and return; calls on one pool must be issued in stream order.  Small host
+ *     arrays are read before the call returns.  Only wgkv_status synchronises.
+ *   - Return value: 0 = WGKV_OK, negative = error.  Argument errors and page
+ *     exhaustion are detected on the host before anything is enqueued and leave
+ *     all state untouched.
+ *   - Positions are 0-based; a (sequence, layer) that has seen t tokens holds
+ *     positions [max(0,t-W), t) in its ring (position p in slot p mod W) and the
+ *     admitted positions below t-W, ascending, in its global cache.
+ *   - Page allocation order (the paper fixes none; this rule makes page tables
+ *     reproducible): free_stack[i] = n_pages-1-i at init, pop takes
+ *     free_stack[--free_top]; within a call, demands are served unit by unit in
+ *     (position of the sequence in the call, kv head) order, a unit's
+ *     ceil(W/P) local pages (taken at its first use) before its global pages.
+ */
+#ifndef WGKV_H
+#define WGKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct wgkv_pool wgkv_pool; /* opaque host-side handle */
+typedef void *wgkv_stream;          /* hipStream_t */
+
+enum { WGKV_F32 = 0, WGKV_BF16 = 1 };
+
+enum {
+    WGKV_OK = 0,
+    WGKV_ERR_INVALID_ARG = -1,
+    WGKV_ERR_OUT_OF_PAGES = -2, /* host-side bound on free pages would go negative */
+    WGKV_ERR_PT_OVERFLOW = -3,  /* a page-table row could exceed max_global_pages_per_head */
+    WGKV_ERR_HIP = -4,          /* a HIP runtime call failed */
+    WGKV_ERR_DEVICE_FLAG = -5,  /* the device-side sticky error flag is set */
+    WGKV_ERR_WORKSPACE = -6     /* workspace too small for this call */
+};
+
+#define WGKV_MAX_CALL_SEQS 128  /* sequences per call */
+#define WGKV_MAX_CALL_UNITS 1024 /* sequences per call x kv heads */
+
+typedef struct {
+    int32_t n_layers, n_q_heads, n_kv_heads; /* n_q_heads % n_kv_heads == 0, group size 1,2,4 or 8 */
+    int32_t head_dim;                         /* 64 or 128 */
+    int32_t dtype;                            /* element type of K, V, Q and the pool */
+    int32_t page_size;                        /* tokens per page P, a power of two (paper: 16) */
+    int32_t w_local;                          /* local window W_local >= 1 (paper: 256) */
+    int32_t max_seqs;                         /* sequence slots */
+    int32_t max_global_pages_per_head;        /* width of a global page-table row */
+    int64_t n_pages;                          /* physical pages in the pool, < 2^31 */
+} wgkv_config;
+
+/* Byte offsets of the arrays inside the metadata block (S = max_seqs, L =
+ * n_layers, H = n_kv_heads, NLP = ceil(W/P), MGP = max_global_pages_per_head):
+ *   seq_len    int32 [S][L]          tokens seen
+ *   global_len int32 [S][L][H]       global-cache length G_h
+ *   local_pt   int32 [S][L][H][NLP]  physical page of each ring page, -1 = none yet
+ *   global_pt  int32 [S][L][H][MGP]  physical page of each global page, -1 = unused
+ *   ring_g     float [S][L][H][W]    stored score of each ring slot
+ *   free_stack int32 [n_pages]       LIFO of free pages
+ *   free_top   int32                 number of free pages
+ *   err_flag   int32                 sticky: 0 ok, else first WGKV_ERR_* seen on device
+ * Pool: element [page][0=K,1=V][slot 0..P-1][head_dim]. */
+typedef struct {
+    size_t seq_len, global_len, local_pt, global_pt, ring_g, free_stack, free_top, err_flag;
+    size_t total_bytes;
+    int32_t n_local_pages;
+} wgkv_meta_layout;
+
+/* Sizes of the caller-provided device buffers.  workspace_bytes is enough for
+ * any call with at most max_call_seqs sequences and max_call_tokens tokens in
+ * total (a decode call has one token per sequence).  Any output may be NULL. */
+int wgkv_query_sizes(const wgkv_config *cfg, int32_t max_call_seqs, int64_t max_call_tokens,
+                     size_t *pool_bytes, size_t *meta_bytes, size_t *workspace_bytes);
+
+/* Where each metadata array lives (so that a caller can snapshot or inspect state). */
+int wgkv_get_meta_layout(const wgkv_config *cfg, wgkv_meta_layout *out);
+
+/* Sec. 4.1.  Validates cfg, adopts pool_dev (>= pool_bytes, 256-byte aligned)
+ * and meta_dev (>= meta_bytes), enqueues one kernel that builds the free stack
+ * and clears lengths and tables, and returns a handle in *out. */
+int wgkv_init_pool(const wgkv_config *cfg, void *pool_dev, size_t pool_bytes, void *meta_dev,
+                   size_t meta_bytes, wgkv_stream stream, wgkv_pool **out);
+
+/* Sec. 3.2 gate equation without the hidden layer (the linear write gate of the
+ * chunked-prefill workload): g[t][h] = sigmoid(w[h] . hidden[t]).
+ *   hidden_dev [n_tokens][hidden_dim], gate_w_dev [n_kv_heads][hidden_dim], both of
+ *   `dtype`; g_out_dev float [n_tokens][n_kv_heads]; fp32 accumulation.
+ * hidden_dim must be a multiple of 8. */
+int wgkv_gate_scores(int32_t dtype, int64_t n_tokens, int32_t hidden_dim, int32_t n_kv_heads,
+                     const void *hidden_dev, const void *gate_w_dev, float *g_out_dev,
+                     wgkv_stream stream);
+
+/* Sec. 4.2 "Initial cache population", also for one chunk of a chunked prefill:
+ * feeds n_tokens_host[b] new tokens of layer `layer` to sequence seq_ids_host[b]
+ * (distinct ids, n_seqs <= WGKV_MAX_CALL_SEQS).  Tokens that leave the window in
+ * this call (from the old ring or from the chunk) are appended to the global
+ * cache in position order iff their score >= tau, with new pages popped as
+ * needed; the last min(W, t) tokens end up in the ring with their scores.
+ *   k_dev, v_dev : [sum T][n_kv_heads][head_dim] of cfg.dtype, sequences packed
+ *   g_dev        : float [sum T][n_kv_heads] scores, or NULL to compute them from
+ *                  hidden_dev [sum T][hidden_dim] and gate_w_dev (see wgkv_gate_scores)
+ *   admit_mask_out_dev : optional uint8 [sum T][n_kv_heads], 1(g >= tau)
+ * Errors: INVALID_ARG, OUT_OF_PAGES / PT_OVERFLOW (from host-side worst-case
+ * bounds: every leaving token counted as admitted; wgkv_status tightens them),
+ * WORKSPACE, HIP. */
+int wgkv_prefill_admit(wgkv_pool *pool, int32_t layer, int32_t n_seqs,
+                       const int32_t *seq_ids_host, const int32_t *n_tokens_host,
+                       const void *k_dev, const void *v_dev, const float *g_dev,
+                       const void *hidden_dev, const void *gate_w_dev, int32_t hidden_dim,
+                       float tau, uint8_t *admit_mask_out_dev, void *workspace_dev,
+                       size_t workspace_bytes, wgkv_stream stream);
+
+/* Sec. 4.3 lazy promotion, one new token per sequence: the victim in slot
+ * t mod W (if t >= W) is appended to the global cache iff its stored score
+ * >= tau, then (k_new, v_new, g_new) take the slot and t advances.
+ *   k_new_dev, v_new_dev : [n_seqs][n_kv_heads][head_dim];  g_new_dev : float [n_seqs][n_kv_heads]
+ *   promoted_out_dev     : optional uint8 [n_seqs][n_kv_heads] */
+int wgkv_decode_step(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                     const void *k_new_dev, const void *v_new_dev, const float *g_new_dev,
+                     float tau, uint8_t *promoted_out_dev, wgkv_stream stream);
+
+/* Attention of the queries of layer `layer` over what the cache holds.
+ * Decode (every n_q_host[b] == 1, k_chunk_dev == NULL): call after
+ * wgkv_decode_step; query head hq reads the valid ring slots and the global
+ * cache of kv head hq / (n_q_heads / n_kv_heads) (Sec. 4.3; Sec. 2.1 equation).
+ * Prefill chunk (k_chunk_dev, v_chunk_dev, g_chunk_dev given; n_q_host[b] = chunk
+ * length T_b): call BEFORE wgkv_prefill_admit of the same chunk; query i of the
+ * chunk (position t+i) sees the global cache, ring positions j with
+ * (pos_i - j < W or stored g_j >= tau) and chunk keys j <= i with
+ * (i - j < W or g_j >= tau)  (Sec. 4.2 mask equation).
+ *   q_dev   : [sum n_q][n_q_heads][head_dim] of cfg.dtype
+ *   out_dev : float [sum n_q][n_q_heads][head_dim]
+ *   scale   : multiplies q.k before the softmax (1/sqrt(head_dim) in the paper) */
+int wgkv_attend(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                const int32_t *n_q_host, const void *q_dev, const void *k_chunk_dev,
+                const void *v_chunk_dev, const float *g_chunk_dev, float tau, float scale,
+                float *out_dev, void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
+
+/* Returns every page of a sequence slot to the free stack (layers ascending, kv
+ * heads ascending, a unit's local pages then its global pages) and clears it. */
+int wgkv_free_seq(wgkv_pool *pool, int32_t seq_id, wgkv_stream stream);
+
+/* Synchronises the stream, reads free_top, the error flag and all lengths back,
+ * and replaces the host-side worst-case bounds by the exact values. */
+int wgkv_status(wgkv_pool *pool, wgkv_stream stream, int64_t *pages_free,
+                int32_t *device_error_flag);
+
+/* Measurement aid: when both are non-NULL hipEvent_t handles, every later
+ * wgkv_attend records ev_begin right before and ev_end right after its main
+ * attention kernel on the call's stream.  Pass NULLs to switch it off. */
+int wgkv_set_profile_events(wgkv_pool *pool, void *ev_begin, void *ev_end);
+
+/* Frees the host handle only. */
+void wgkv_destroy(wgkv_pool *pool);
+
+/* Library version string (static storage). */
+const char *wgkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WGKV_H */

@@ -1,0 +1,226 @@
+"""ctypes binding with the same names as the C ABI (include/wgkv.h).
+
+Argument marshalling only.  Tensors are torch CUDA tensors; small per-call
+arrays are Python sequences.  Every call enqueues on torch's current stream.
+"""
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+F32, BF16 = 0, 1
+
+EXPORTED_SYMBOLS = [
+    "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
+    "wgkv_gate_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_free_seq",
+    "wgkv_status", "wgkv_set_profile_events", "wgkv_destroy",
+]
+
+_ERR = {-1: "invalid argument", -2: "out of pages", -3: "page-table overflow", -4: "HIP error",
+        -5: "device error flag set", -6: "workspace too small"}
+
+
+class WgkvError(RuntimeError):
+    def __init__(self, code, what=""):
+        super().__init__(f"{what}: wgkv error {code} ({_ERR.get(code, '?')})")
+        self.code = code
+
+
+class _CConfig(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("dtype", C.c_int32), ("page_size", C.c_int32),
+                ("w_local", C.c_int32), ("max_seqs", C.c_int32),
+                ("max_global_pages_per_head", C.c_int32), ("n_pages", C.c_int64)]
+
+
+class _CLayout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("seq_len", "global_len", "local_pt", "global_pt", "ring_g",
+                                          "free_stack", "free_top", "err_flag", "total_bytes")] + \
+               [("n_local_pages", C.c_int32)]
+
+
+@dataclass
+class Config:
+    n_layers: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    dtype: int
+    page_size: int
+    w_local: int
+    max_seqs: int
+    max_global_pages_per_head: int
+    n_pages: int
+
+    def c(self):
+        return _CConfig(self.n_layers, self.n_q_heads, self.n_kv_heads, self.head_dim, self.dtype,
+                        self.page_size, self.w_local, self.max_seqs,
+                        self.max_global_pages_per_head, self.n_pages)
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libwgkv.so")
+
+
+_lib = None
+
+
+def load_library():
+    """Load the built C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2512_17452_amd.build` "
+                           "(there is no fallback path)")
+    L = C.CDLL(path)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    pi32 = C.POINTER(C.c_int32)
+    L.wgkv_version.restype = C.c_char_p
+    L.wgkv_get_meta_layout.argtypes = [C.POINTER(_CConfig), C.POINTER(_CLayout)]
+    L.wgkv_query_sizes.argtypes = [C.POINTER(_CConfig), i32, i64, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+    L.wgkv_init_pool.argtypes = [C.POINTER(_CConfig), vp, sz, vp, sz, vp, C.POINTER(vp)]
+    L.wgkv_gate_scores.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp]
+    L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+    L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
+    L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
+    L.wgkv_free_seq.argtypes = [vp, i32, vp]
+    L.wgkv_status.argtypes = [vp, vp, C.POINTER(i64), C.POINTER(i32)]
+    L.wgkv_set_profile_events.argtypes = [vp, vp, vp]
+    L.wgkv_destroy.argtypes = [vp]
+    L.wgkv_destroy.restype = None
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _ids(xs):
+    arr = (C.c_int32 * len(xs))(*[int(x) for x in xs])
+    return arr
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise WgkvError(rc, what)
+
+
+def gate_scores(hidden, gate_w, out=None):
+    """wgkv_gate_scores: g[t][h] = sigmoid(gate_w[h] . hidden[t]) as float32 [T, Hkv]."""
+    import torch
+    L = load_library()
+    assert hidden.is_cuda and gate_w.is_cuda and hidden.is_contiguous() and gate_w.is_contiguous()
+    assert hidden.dtype == gate_w.dtype and hidden.dtype in (torch.float32, torch.bfloat16)
+    T, dim = hidden.shape
+    Hk = gate_w.shape[0]
+    if out is None:
+        out = torch.empty((T, Hk), dtype=torch.float32, device=hidden.device)
+    dt = F32 if hidden.dtype == torch.float32 else BF16
+    _check(L.wgkv_gate_scores(dt, T, dim, Hk, _ptr(hidden), _ptr(gate_w), _ptr(out), _stream()), "wgkv_gate_scores")
+    return out
+
+
+class Pool:
+    """Owns the torch buffers (pool, metadata, workspace) and the library handle."""
+
+    def __init__(self, cfg: Config, max_call_seqs: int, max_call_tokens: int, device="cuda:0"):
+        import torch
+        self.L = load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("wgkv needs a GPU: there is no CPU path")
+        self.cfg = cfg
+        self.device = torch.device(device)
+        cc = cfg.c()
+        pb, mb, wb = C.c_size_t(), C.c_size_t(), C.c_size_t()
+        _check(self.L.wgkv_query_sizes(C.byref(cc), max_call_seqs, max_call_tokens, C.byref(pb),
+                                       C.byref(mb), C.byref(wb)), "wgkv_query_sizes")
+        self.layout = _CLayout()
+        _check(self.L.wgkv_get_meta_layout(C.byref(cc), C.byref(self.layout)), "wgkv_get_meta_layout")
+        self.pool_buf = torch.empty(pb.value, dtype=torch.uint8, device=self.device)
+        self.meta_buf = torch.empty(mb.value, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(wb.value, dtype=torch.uint8, device=self.device)
+        self.torch_dtype = torch.float32 if cfg.dtype == F32 else torch.bfloat16
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(self.L.wgkv_init_pool(C.byref(cc), _ptr(self.pool_buf), pb.value, _ptr(self.meta_buf),
+                                         mb.value, _stream(), C.byref(h)), "wgkv_init_pool")
+        self.h = h
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            self.L.wgkv_destroy(self.h)
+            self.h = None
+
+    # ---- the path ----
+    def prefill_admit(self, layer, seq_ids, n_tokens, k, v, g=None, hidden=None, gate_w=None,
+                      tau=0.5, admit_mask_out=None):
+        hd = 0 if hidden is None else hidden.shape[-1]
+        _check(self.L.wgkv_prefill_admit(self.h, layer, len(seq_ids), _ids(seq_ids), _ids(n_tokens),
+                                         _ptr(k), _ptr(v), _ptr(g), _ptr(hidden), _ptr(gate_w), hd,
+                                         tau, _ptr(admit_mask_out), _ptr(self.workspace),
+                                         self.workspace.numel(), _stream()), "wgkv_prefill_admit")
+
+    def decode_step(self, layer, seq_ids, k_new, v_new, g_new, tau=0.5, promoted_out=None):
+        _check(self.L.wgkv_decode_step(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(k_new),
+                                       _ptr(v_new), _ptr(g_new), tau, _ptr(promoted_out), _stream()),
+               "wgkv_decode_step")
+
+    def attend(self, layer, seq_ids, q, out, scale, n_q=None, k_chunk=None, v_chunk=None,
+               g_chunk=None, tau=0.5):
+        if n_q is None:
+            n_q = [1] * len(seq_ids)
+        _check(self.L.wgkv_attend(self.h, layer, len(seq_ids), _ids(seq_ids), _ids(n_q), _ptr(q),
+                                  _ptr(k_chunk), _ptr(v_chunk), _ptr(g_chunk), tau, scale, _ptr(out),
+                                  _ptr(self.workspace), self.workspace.numel(), _stream()), "wgkv_attend")
+        return out
+
+    def free_seq(self, seq_id):
+        _check(self.L.wgkv_free_seq(self.h, seq_id, _stream()), "wgkv_free_seq")
+
+    def status(self):
+        free, flag = C.c_int64(), C.c_int32()
+        rc = self.L.wgkv_status(self.h, _stream(), C.byref(free), C.byref(flag))
+        if rc not in (0, -5):
+            raise WgkvError(rc, "wgkv_status")
+        return free.value, flag.value
+
+    def set_profile_events(self, ev_begin, ev_end):
+        """ev_begin/ev_end: raw hipEvent_t handles (ints) or None."""
+        _check(self.L.wgkv_set_profile_events(self.h, C.c_void_p(ev_begin) if ev_begin else None,
+                                              C.c_void_p(ev_end) if ev_end else None),
+               "wgkv_set_profile_events")
+
+    # ---- views of the documented metadata layout (inspection / snapshots) ----
+    def _view(self, off, count, dtype):
+        import torch
+        es = 4
+        return self.meta_buf[off: off + count * es].view(dtype)
+
+    def meta(self):
+        import torch
+        c, lay = self.cfg, self.layout
+        S, Lr, H, W = c.max_seqs, c.n_layers, c.n_kv_heads, c.w_local
+        nlp, mgp = lay.n_local_pages, c.max_global_pages_per_head
+        i32, f32 = torch.int32, torch.float32
+        return {
+            "seq_len": self._view(lay.seq_len, S * Lr, i32).view(S, Lr),
+            "global_len": self._view(lay.global_len, S * Lr * H, i32).view(S, Lr, H),
+            "local_pt": self._view(lay.local_pt, S * Lr * H * nlp, i32).view(S, Lr, H, nlp),
+            "global_pt": self._view(lay.global_pt, S * Lr * H * mgp, i32).view(S, Lr, H, mgp),
+            "ring_g": self._view(lay.ring_g, S * Lr * H * W, f32).view(S, Lr, H, W),
+            "free_stack": self._view(lay.free_stack, c.n_pages, i32),
+            "free_top": self._view(lay.free_top, 1, i32),
+            "err_flag": self._view(lay.err_flag, 1, i32),
+        }
+
+    def pool_pages(self):
+        """The pool as [n_pages, 2 (K,V), P, head_dim] in the pool dtype."""
+        c = self.cfg
+        return self.pool_buf.view(self.torch_dtype).view(c.n_pages, 2, c.page_size, c.head_dim)

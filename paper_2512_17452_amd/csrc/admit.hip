@@ -1,0 +1,407 @@
+// Admission, paging and promotion kernels for gfx950 (wave64).
+//
+//  init_kernel            free stack + cleared tables                       (Sec. 4.1)
+//  prefill_count_kernel   gate score -> admit mask, per-block admitted counts (Sec. 3.3 last sentence)
+//  prefill_plan_kernel    prefix sums over blocks and units, page hand-out    (Sec. 4.1, 4.2)
+//  prefill_scatter_kernel stable compaction of admitted K/V rows into global pages (Sec. 4.2)
+//  prefill_ring_kernel    last min(W,T) tokens into the ring                  (Sec. 4.2)
+//  decode_step_kernel     lazy promotion of the victim, then overwrite        (Sec. 4.3 (1)-(3))
+//  free_seq_kernel        pages of a sequence slot back to the free stack
+//
+// Page hand-out never races: demands are prefix-summed in (sequence position in
+// the call, kv head) order and unit u takes free_stack[top-1-base_u-i].
+#include "wgkv_dev.h"
+
+namespace wgkv {
+
+constexpr int kPrefillBlk = 1024;  // leaving tokens per block (256 threads x 4)
+
+struct PrefillArgs {
+    int layer;
+    int nblk_max;         // grid.x
+    float tau;
+    const char *k, *v;    // [sumT][Hkv][d]
+    const float *g;       // [sumT][Hkv]
+    uint8_t *admit_out;   // optional
+    int32_t *cnt;         // [n_units][nblk_max] admitted per block -> exclusive offsets
+    int32_t *plan;        // [0]=abort flag, [1+u]=G_old of unit u
+};
+
+struct DecodeArgs {
+    int layer;
+    float tau;
+    const char *k, *v;    // [n_seqs][Hkv][d]
+    const float *g;       // [n_seqs][Hkv]
+    uint8_t *promoted_out;
+};
+
+__global__ void init_kernel(View pv) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t n_sl = (size_t)pv.S * pv.L, n_u = n_sl * pv.Hkv;
+    for (size_t i = i0; i < (size_t)pv.n_pages; i += stride) pv.free_stack[i] = pv.n_pages - 1 - (int32_t)i;
+    for (size_t i = i0; i < n_sl; i += stride) pv.seq_len[i] = 0;
+    for (size_t i = i0; i < n_u; i += stride) pv.global_len[i] = 0;
+    for (size_t i = i0; i < n_u * pv.nlp; i += stride) pv.local_pt[i] = -1;
+    for (size_t i = i0; i < n_u * pv.maxgp; i += stride) pv.global_pt[i] = -1;
+    for (size_t i = i0; i < n_u * pv.W; i += stride) pv.ring_g[i] = 0.0f;
+    if (i0 == 0) { *pv.free_top = pv.n_pages; *pv.err_flag = 0; }
+}
+
+// Score of leaving position p of a unit: from the ring if the token was fed by
+// an earlier call, else from this call's scores.
+__device__ __forceinline__ float leaving_score(const View &pv, const PrefillArgs &a, int um, int h,
+                                               int p, int t0, int base) {
+    if (p < t0) return pv.ring_g[(size_t)um * pv.W + (p % pv.W)];
+    return a.g[(size_t)(base + p - t0) * pv.Hkv + h];
+}
+
+__global__ __launch_bounds__(256) void prefill_count_kernel(View pv, CallSeqs cs, PrefillArgs a) {
+    __shared__ int s_w[4];
+    const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
+    const int t0 = cs.t0[b], T = cs.ntok[b], base = cs.base[b];
+    const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+    const int lo = max(0, t0 - pv.W), hi = max(0, t0 + T - pv.W), n_leave = hi - lo;
+    const int i0 = blockIdx.x * kPrefillBlk + threadIdx.x * 4;
+    if (a.admit_out) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            int i = i0 + j;
+            if (i < T) {
+                size_t row = (size_t)(base + i) * pv.Hkv + h;
+                a.admit_out[row] = (uint8_t)(a.g[row] >= a.tau);
+            }
+        }
+    }
+    if (blockIdx.x * kPrefillBlk >= n_leave) return;  // block-uniform
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        int i = i0 + j;
+        if (i < n_leave) c += (int)(leaving_score(pv, a, um, h, lo + i, t0, base) >= a.tau);
+    }
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    c = wave_incl_scan(c, lane);
+    if (lane == 63) s_w[w] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) a.cnt[(size_t)u * a.nblk_max + blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+}
+
+__global__ __launch_bounds__(256) void prefill_plan_kernel(View pv, CallSeqs cs, PrefillArgs a) {
+    __shared__ int s_adm[kMaxCallUnits];
+    __shared__ int s_gold[kMaxCallUnits];
+    __shared__ int s_base[kMaxCallUnits];
+    __shared__ int s_dl[kMaxCallUnits];
+    __shared__ int s_tmp[20];
+    __shared__ int s_err;
+    const int n_units = cs.n * pv.Hkv;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (threadIdx.x == 0) s_err = 0;
+    __syncthreads();
+    // A: one wave per unit turns block counts into exclusive offsets
+    for (int u = w; u < n_units; u += 4) {
+        const int b = u / pv.Hkv;
+        const int t0 = cs.t0[b], T = cs.ntok[b];
+        const int n_leave = max(0, t0 + T - pv.W) - max(0, t0 - pv.W);
+        const int nblk = (n_leave + kPrefillBlk - 1) / kPrefillBlk;
+        int32_t *c = a.cnt + (size_t)u * a.nblk_max;
+        int run = 0;
+        for (int i0 = 0; i0 < nblk; i0 += 64) {
+            int i = i0 + lane;
+            int v = i < nblk ? c[i] : 0;
+            int inc = wave_incl_scan(v, lane);
+            if (i < nblk) c[i] = run + inc - v;
+            run += __shfl(inc, 63);
+        }
+        if (lane == 0) s_adm[u] = run;
+    }
+    __syncthreads();
+    // B: page demand of every unit, prefix over units in call order
+    const int top = *pv.free_top;
+    int carry = 0;
+    for (int u0 = 0; u0 < n_units; u0 += 256) {
+        const int u = u0 + threadIdx.x;
+        int demand = 0;
+        if (u < n_units) {
+            const int b = u / pv.Hkv, h = u % pv.Hkv;
+            const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+            const int gold = pv.global_len[um];
+            const int gnew = gold + s_adm[u];
+            const int dl = (cs.ntok[b] > 0 && pv.local_pt[(size_t)um * pv.nlp] < 0) ? pv.nlp : 0;
+            const int pages_new = (gnew + pv.P - 1) >> pv.logP;
+            if (pages_new > pv.maxgp) s_err = WGKV_ERR_PT_OVERFLOW;
+            demand = dl + pages_new - ((gold + pv.P - 1) >> pv.logP);
+            s_gold[u] = gold;
+            s_dl[u] = dl;
+        }
+        int total;
+        int ex = block_excl_scan(demand, s_tmp, &total);
+        if (u < n_units) s_base[u] = carry + ex;
+        carry += total;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && s_err == 0 && carry > top) s_err = WGKV_ERR_OUT_OF_PAGES;
+    __syncthreads();
+    if (s_err != 0) {  // block-uniform: leave all state as it was
+        if (threadIdx.x == 0) {
+            a.plan[0] = 1;
+            atomicCAS(pv.err_flag, 0, s_err);
+        }
+        return;
+    }
+    // C: page-table entries, one wave per unit
+    for (int u = w; u < n_units; u += 4) {
+        const int b = u / pv.Hkv, h = u % pv.Hkv;
+        const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+        const int gold = s_gold[u], dl = s_dl[u], ubase = s_base[u];
+        for (int i = lane; i < dl; i += 64) pv.local_pt[(size_t)um * pv.nlp + i] = pv.free_stack[top - 1 - (ubase + i)];
+        const int first = (gold + pv.P - 1) >> pv.logP;
+        const int n_new = ((gold + s_adm[u] + pv.P - 1) >> pv.logP) - first;
+        for (int j = lane; j < n_new; j += 64)
+            pv.global_pt[(size_t)um * pv.maxgp + first + j] = pv.free_stack[top - 1 - (ubase + dl + j)];
+    }
+    // D: lengths
+    for (int u = threadIdx.x; u < n_units; u += 256) {
+        const int b = u / pv.Hkv, h = u % pv.Hkv;
+        const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+        pv.global_len[um] = s_gold[u] + s_adm[u];
+        a.plan[1 + u] = s_gold[u];
+    }
+    for (int b = threadIdx.x; b < cs.n; b += 256) pv.seq_len[cs.sid[b] * pv.L + a.layer] = cs.t0[b] + cs.ntok[b];
+    if (threadIdx.x == 0) {
+        *pv.free_top = top - carry;
+        a.plan[0] = 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs cs, PrefillArgs a) {
+    __shared__ int s_src[kPrefillBlk];
+    __shared__ int s_tmp[20];
+    if (a.plan[0] != 0) return;
+    const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
+    const int t0 = cs.t0[b], T = cs.ntok[b], base = cs.base[b];
+    const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+    const int lo = max(0, t0 - pv.W), hi = max(0, t0 + T - pv.W), n_leave = hi - lo;
+    if (blockIdx.x * kPrefillBlk >= n_leave) return;
+    const int i0 = blockIdx.x * kPrefillBlk + threadIdx.x * 4;
+    int f[4], c = 0;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        int i = i0 + j;
+        f[j] = (i < n_leave) ? (int)(leaving_score(pv, a, um, h, lo + i, t0, base) >= a.tau) : 0;
+        c += f[j];
+    }
+    int n_adm;
+    int rank = block_excl_scan(c, s_tmp, &n_adm);
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+        if (f[j]) s_src[rank++] = i0 + j;
+    __syncthreads();
+    // copy the admitted rows: lpr lanes of 16 bytes per row, K and V
+    const int lpr = pv.row_bytes >> 4;
+    const int rows_per_pass = 256 / lpr;
+    const int sub = threadIdx.x % lpr;
+    const int dst0 = a.plan[1 + u] + a.cnt[(size_t)u * a.nblk_max + blockIdx.x];
+    for (int r = threadIdx.x / lpr; r < n_adm; r += rows_per_pass) {
+        const int p = lo + s_src[r];
+        const char *ks, *vs;
+        if (p < t0) {
+            const int slot = p % pv.W;
+            const char *pg = page_ptr(pv, pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)]);
+            ks = pg + (size_t)(slot & (pv.P - 1)) * pv.row_bytes;
+            vs = ks + pv.v_off;
+        } else {
+            const size_t row = ((size_t)(base + p - t0) * pv.Hkv + h) * pv.row_bytes;
+            ks = a.k + row;
+            vs = a.v + row;
+        }
+        const int dst = dst0 + r;
+        char *dp = page_ptr(pv, pv.global_pt[(size_t)um * pv.maxgp + (dst >> pv.logP)]) +
+                   (size_t)(dst & (pv.P - 1)) * pv.row_bytes;
+        const uint4 kk = *reinterpret_cast<const uint4 *>(ks + sub * 16);
+        const uint4 vv = *reinterpret_cast<const uint4 *>(vs + sub * 16);
+        *reinterpret_cast<uint4 *>(dp + sub * 16) = kk;
+        *reinterpret_cast<uint4 *>(dp + pv.v_off + sub * 16) = vv;
+    }
+}
+
+__global__ __launch_bounds__(256) void prefill_ring_kernel(View pv, CallSeqs cs, PrefillArgs a) {
+    if (a.plan[0] != 0) return;
+    const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
+    const int t0 = cs.t0[b], T = cs.ntok[b], base = cs.base[b];
+    const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+    const int nr = min(T, pv.W);
+    const int lpr = pv.row_bytes >> 4;
+    const int r = (blockIdx.x * 256 + threadIdx.x) / lpr, sub = threadIdx.x % lpr;
+    if (r >= nr) return;
+    const int i = T - nr + r;  // index in the chunk
+    const int slot = (t0 + i) % pv.W;
+    const size_t row = (size_t)(base + i) * pv.Hkv + h;
+    char *dp = page_ptr(pv, pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)]) +
+               (size_t)(slot & (pv.P - 1)) * pv.row_bytes;
+    *reinterpret_cast<uint4 *>(dp + sub * 16) = *reinterpret_cast<const uint4 *>(a.k + row * pv.row_bytes + sub * 16);
+    *reinterpret_cast<uint4 *>(dp + pv.v_off + sub * 16) =
+        *reinterpret_cast<const uint4 *>(a.v + row * pv.row_bytes + sub * 16);
+    if (sub == 0) pv.ring_g[(size_t)um * pv.W + slot] = a.g[row];
+}
+
+// One block does the whole step: decisions and page hand-out first (they need a
+// prefix over units), then the row moves.
+__global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs, DecodeArgs a) {
+    __shared__ int s_gold[kMaxCallUnits];   // G before the step, bit 31 = promote
+    __shared__ int s_tmp[20];
+    __shared__ int s_err;
+    const int n_units = cs.n * pv.Hkv;
+    if (threadIdx.x == 0) s_err = 0;
+    __syncthreads();
+    const int top = *pv.free_top;
+    const int u = threadIdx.x;  // n_units <= 1024 = blockDim.x
+    int demand = 0, dl = 0, promote = 0, gold = 0, um = 0, slot = 0;
+    if (u < n_units) {
+        const int b = u / pv.Hkv, h = u % pv.Hkv, t = cs.t0[b];
+        um = unit_meta(pv, cs.sid[b], a.layer, h);
+        slot = t % pv.W;
+        gold = pv.global_len[um];
+        promote = (t >= pv.W) && (pv.ring_g[(size_t)um * pv.W + slot] >= a.tau);
+        dl = (pv.local_pt[(size_t)um * pv.nlp] < 0) ? pv.nlp : 0;
+        const int need = promote && ((gold & (pv.P - 1)) == 0);
+        if (need && (gold >> pv.logP) >= pv.maxgp) s_err = WGKV_ERR_PT_OVERFLOW;
+        demand = dl + need;
+    }
+    int total;
+    const int ubase = block_excl_scan(demand, s_tmp, &total);
+    if (total > top && threadIdx.x == 0 && s_err == 0) s_err = WGKV_ERR_OUT_OF_PAGES;
+    __syncthreads();
+    if (s_err != 0) {
+        if (threadIdx.x == 0) atomicCAS(pv.err_flag, 0, s_err);
+        return;
+    }
+    if (u < n_units) {
+        for (int i = 0; i < dl; i++) pv.local_pt[(size_t)um * pv.nlp + i] = pv.free_stack[top - 1 - (ubase + i)];
+        if (demand > dl) pv.global_pt[(size_t)um * pv.maxgp + (gold >> pv.logP)] = pv.free_stack[top - 1 - (ubase + dl)];
+        if (promote) pv.global_len[um] = gold + 1;
+        if (a.promoted_out) a.promoted_out[u] = (uint8_t)promote;
+        s_gold[u] = (int)((unsigned)gold | ((unsigned)promote << 31));
+    }
+    if (threadIdx.x < cs.n) pv.seq_len[cs.sid[threadIdx.x] * pv.L + a.layer] = cs.t0[threadIdx.x] + 1;
+    if (threadIdx.x == 0) *pv.free_top = top - total;
+    __syncthreads();  // tables written above are read below by other threads
+    const int lpr = pv.row_bytes >> 4;
+    for (int c = threadIdx.x; c < n_units * lpr; c += blockDim.x) {
+        const int uu = c / lpr, sub = c % lpr;
+        const int b = uu / pv.Hkv, h = uu % pv.Hkv;
+        const int m = unit_meta(pv, cs.sid[b], a.layer, h);
+        const int sl = cs.t0[b] % pv.W;
+        char *rp = page_ptr(pv, pv.local_pt[(size_t)m * pv.nlp + (sl >> pv.logP)]) +
+                   (size_t)(sl & (pv.P - 1)) * pv.row_bytes + sub * 16;
+        const int gi = s_gold[uu];
+        if (gi < 0) {  // promote: ring row -> global slot G_old
+            const int g0 = gi & 0x7fffffff;
+            char *dp = page_ptr(pv, pv.global_pt[(size_t)m * pv.maxgp + (g0 >> pv.logP)]) +
+                       (size_t)(g0 & (pv.P - 1)) * pv.row_bytes + sub * 16;
+            const uint4 kk = *reinterpret_cast<const uint4 *>(rp);
+            const uint4 vv = *reinterpret_cast<const uint4 *>(rp + pv.v_off);
+            *reinterpret_cast<uint4 *>(dp) = kk;
+            *reinterpret_cast<uint4 *>(dp + pv.v_off) = vv;
+        }
+        const size_t row = (size_t)uu * pv.row_bytes + sub * 16;
+        *reinterpret_cast<uint4 *>(rp) = *reinterpret_cast<const uint4 *>(a.k + row);
+        *reinterpret_cast<uint4 *>(rp + pv.v_off) = *reinterpret_cast<const uint4 *>(a.v + row);
+        if (sub == 0) pv.ring_g[(size_t)m * pv.W + sl] = a.g[uu];
+    }
+}
+
+__global__ __launch_bounds__(256) void free_seq_kernel(View pv, int sid) {
+    __shared__ int s_tmp[20];
+    const int n_units = pv.L * pv.Hkv;
+    const int top = *pv.free_top;
+    int carry = 0;
+    for (int u0 = 0; u0 < n_units; u0 += 256) {
+        const int u = u0 + threadIdx.x;
+        int n = 0, um = 0, ngp = 0, touched = 0;
+        if (u < n_units) {
+            um = sid * n_units + u;  // (sid*L + layer)*Hkv + h with u = layer*Hkv + h
+            touched = pv.local_pt[(size_t)um * pv.nlp] >= 0;
+            ngp = (pv.global_len[um] + pv.P - 1) >> pv.logP;
+            n = touched ? pv.nlp + ngp : 0;
+        }
+        int total;
+        const int ex = block_excl_scan(n, s_tmp, &total);
+        if (u < n_units) {
+            int o = top + carry + ex;
+            if (touched) {
+                for (int i = 0; i < pv.nlp; i++) {
+                    pv.free_stack[o++] = pv.local_pt[(size_t)um * pv.nlp + i];
+                    pv.local_pt[(size_t)um * pv.nlp + i] = -1;
+                }
+                for (int i = 0; i < ngp; i++) {
+                    pv.free_stack[o++] = pv.global_pt[(size_t)um * pv.maxgp + i];
+                    pv.global_pt[(size_t)um * pv.maxgp + i] = -1;
+                }
+            }
+            pv.global_len[um] = 0;
+            for (int s = 0; s < pv.W; s++) pv.ring_g[(size_t)um * pv.W + s] = 0.0f;
+        }
+        carry += total;
+    }
+    for (int l = threadIdx.x; l < pv.L; l += 256) pv.seq_len[sid * pv.L + l] = 0;
+    __syncthreads();
+    if (threadIdx.x == 0) *pv.free_top = top + carry;
+}
+
+// ---- host-side launchers (called from the C ABI layer) ----
+
+hipError_t launch_init(const View &pv, hipStream_t st) {
+    hipLaunchKernelGGL(init_kernel, dim3(1024), dim3(256), 0, st, pv);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill(const View &pv, const CallSeqs &cs, int layer, float tau, const void *k,
+                          const void *v, const float *g, uint8_t *admit_out, int32_t *cnt,
+                          int32_t *plan, int nblk_leave_max, int max_T, int max_ring_rows,
+                          hipStream_t st) {
+    PrefillArgs a;
+    a.layer = layer;
+    a.tau = tau;
+    a.k = (const char *)k;
+    a.v = (const char *)v;
+    a.g = g;
+    a.admit_out = admit_out;
+    a.cnt = cnt;
+    a.plan = plan;
+    a.nblk_max = nblk_leave_max > 0 ? nblk_leave_max : 1;
+    const int n_units = cs.n * pv.Hkv;
+    int gx = a.nblk_max;
+    if (admit_out) gx = max(gx, (max_T + kPrefillBlk - 1) / kPrefillBlk);
+    hipLaunchKernelGGL(prefill_count_kernel, dim3(gx, n_units), dim3(256), 0, st, pv, cs, a);
+    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(256), 0, st, pv, cs, a);
+    if (nblk_leave_max > 0)
+        hipLaunchKernelGGL(prefill_scatter_kernel, dim3(a.nblk_max, n_units), dim3(256), 0, st, pv, cs, a);
+    if (max_ring_rows > 0) {
+        const int lpr = pv.row_bytes >> 4;
+        const int gxr = (max_ring_rows * lpr + 255) / 256;
+        hipLaunchKernelGGL(prefill_ring_kernel, dim3(gxr, n_units), dim3(256), 0, st, pv, cs, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_step(const View &pv, const CallSeqs &cs, int layer, float tau,
+                              const void *k, const void *v, const float *g, uint8_t *promoted_out,
+                              hipStream_t st) {
+    DecodeArgs a;
+    a.layer = layer;
+    a.tau = tau;
+    a.k = (const char *)k;
+    a.v = (const char *)v;
+    a.g = g;
+    a.promoted_out = promoted_out;
+    hipLaunchKernelGGL(decode_step_kernel, dim3(1), dim3(1024), 0, st, pv, cs, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_free_seq(const View &pv, int sid, hipStream_t st) {
+    hipLaunchKernelGGL(free_seq_kernel, dim3(1), dim3(256), 0, st, pv, sid);
+    return hipGetLastError();
+}
+
+}  // namespace wgkv

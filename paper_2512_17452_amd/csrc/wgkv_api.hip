@@ -1,0 +1,455 @@
+// C ABI of the library: argument checks, host-side bookkeeping, kernel launches.
+// Every entry point is documented in include/wgkv.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "wgkv_dev.h"
+
+namespace wgkv {
+hipError_t launch_init(const View &pv, hipStream_t st);
+hipError_t launch_prefill(const View &pv, const CallSeqs &cs, int layer, float tau, const void *k,
+                          const void *v, const float *g, uint8_t *admit_out, int32_t *cnt,
+                          int32_t *plan, int nblk_leave_max, int max_T, int max_ring_rows,
+                          hipStream_t st);
+hipError_t launch_decode_step(const View &pv, const CallSeqs &cs, int layer, float tau,
+                              const void *k, const void *v, const float *g, uint8_t *promoted_out,
+                              hipStream_t st);
+hipError_t launch_free_seq(const View &pv, int sid, hipStream_t st);
+size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid);
+hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int32_t *sids,
+                                const void *q, float scale, float *out, void *ws, int grid,
+                                int min_tpb, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
+hipError_t launch_gate_linear(int dtype, int64_t n_tokens, int hidden_dim, int n_kv_heads,
+                              const void *hidden, const void *w, float *g_out, hipStream_t st);
+size_t attend_prefill_ws_bytes(const View &pv, int n_seqs, int64_t total_q);
+hipError_t launch_attend_prefill(const View &pv, const CallSeqs &cs, int layer, const void *q,
+                                 const void *k, const void *v, const float *g, float tau,
+                                 float scale, float *out, void *ws, hipStream_t st);
+}  // namespace wgkv
+
+using namespace wgkv;
+
+namespace {
+
+constexpr int kPrefillBlkHost = 1024;   // must match kPrefillBlk in admit.hip
+constexpr int kAttnGridMax = 4096;      // upper bound on the decode-attention grid
+constexpr int kAttnBlocksPerCu = 4;
+constexpr int kAttnMinTilesPerBlock = 8;
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int check_config(const wgkv_config *c) {
+    if (!c) return WGKV_ERR_INVALID_ARG;
+    if (c->n_layers < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1) return WGKV_ERR_INVALID_ARG;
+    if (c->n_q_heads % c->n_kv_heads) return WGKV_ERR_INVALID_ARG;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return WGKV_ERR_INVALID_ARG;
+    if (c->head_dim != 64 && c->head_dim != 128) return WGKV_ERR_INVALID_ARG;
+    if (c->dtype != WGKV_F32 && c->dtype != WGKV_BF16) return WGKV_ERR_INVALID_ARG;
+    if (c->page_size < 1 || (c->page_size & (c->page_size - 1)) || c->page_size > 1024) return WGKV_ERR_INVALID_ARG;
+    if (c->w_local < 1 || c->w_local > (1 << 20)) return WGKV_ERR_INVALID_ARG;
+    if (c->max_seqs < 1 || c->max_global_pages_per_head < 1) return WGKV_ERR_INVALID_ARG;
+    if (c->n_pages < 1 || c->n_pages >= ((int64_t)1 << 31)) return WGKV_ERR_INVALID_ARG;
+    const int64_t units = (int64_t)c->max_seqs * c->n_layers * c->n_kv_heads;
+    if (units * (int64_t)c->max_global_pages_per_head >= ((int64_t)1 << 40)) return WGKV_ERR_INVALID_ARG;
+    return WGKV_OK;
+}
+
+void make_layout(const wgkv_config *c, wgkv_meta_layout *o) {
+    const size_t S = c->max_seqs, L = c->n_layers, H = c->n_kv_heads;
+    const size_t nlp = (c->w_local + c->page_size - 1) / c->page_size;
+    size_t off = 0;
+    o->seq_len = off;    off = align256(off + S * L * 4);
+    o->global_len = off; off = align256(off + S * L * H * 4);
+    o->local_pt = off;   off = align256(off + S * L * H * nlp * 4);
+    o->global_pt = off;  off = align256(off + S * L * H * (size_t)c->max_global_pages_per_head * 4);
+    o->ring_g = off;     off = align256(off + S * L * H * (size_t)c->w_local * 4);
+    o->free_stack = off; off = align256(off + (size_t)c->n_pages * 4);
+    o->free_top = off;   off = align256(off + 4);
+    o->err_flag = off;   off = align256(off + 4);
+    o->total_bytes = off;
+    o->n_local_pages = (int32_t)nlp;
+}
+
+View make_view(const wgkv_config *c, void *pool, void *meta) {
+    wgkv_meta_layout lay;
+    make_layout(c, &lay);
+    View v;
+    memset(&v, 0, sizeof(v));
+    v.L = c->n_layers; v.Hq = c->n_q_heads; v.Hkv = c->n_kv_heads; v.d = c->head_dim;
+    v.dtype = c->dtype; v.es = c->dtype == WGKV_F32 ? 4 : 2;
+    v.P = c->page_size; v.logP = 0;
+    while ((1 << v.logP) < v.P) v.logP++;
+    v.W = c->w_local; v.S = c->max_seqs; v.maxgp = c->max_global_pages_per_head;
+    v.nlp = lay.n_local_pages; v.G = c->n_q_heads / c->n_kv_heads;
+    v.n_pages = (int32_t)c->n_pages;
+    v.row_bytes = (uint32_t)(v.d * v.es);
+    v.v_off = (uint32_t)(v.P * v.d * v.es);
+    v.page_bytes = (uint64_t)2 * v.P * v.d * v.es;
+    v.pool = (char *)pool;
+    char *m = (char *)meta;
+    v.seq_len = (int32_t *)(m + lay.seq_len);
+    v.global_len = (int32_t *)(m + lay.global_len);
+    v.local_pt = (int32_t *)(m + lay.local_pt);
+    v.global_pt = (int32_t *)(m + lay.global_pt);
+    v.ring_g = (float *)(m + lay.ring_g);
+    v.free_stack = (int32_t *)(m + lay.free_stack);
+    v.free_top = (int32_t *)(m + lay.free_top);
+    v.err_flag = (int32_t *)(m + lay.err_flag);
+    return v;
+}
+
+struct PrefillWs { size_t g_off, cnt_off, plan_off, total; };
+
+// scratch of a prefill call: scores computed from the gate, block counts, plan
+PrefillWs prefill_ws(const wgkv_config *c, int n_seqs, int64_t total_tokens, int64_t max_T) {
+    PrefillWs w;
+    size_t off = 0;
+    w.g_off = off;   off = align256(off + (size_t)total_tokens * c->n_kv_heads * 4);
+    const size_t n_units = (size_t)n_seqs * c->n_kv_heads;
+    const size_t nblk = (size_t)((max_T + kPrefillBlkHost - 1) / kPrefillBlkHost) + 1;
+    w.cnt_off = off; off = align256(off + n_units * nblk * 4);
+    w.plan_off = off; off = align256(off + (1 + n_units) * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+struct wgkv_pool {
+    wgkv_config cfg;
+    View view;
+    wgkv_meta_layout lay;
+    std::vector<int32_t> seq_len_h;  // [S][L] exact mirror (deterministic)
+    std::vector<uint8_t> touched_h;  // [S][L] local pages handed out
+    std::vector<int32_t> g_ub;       // [S][L][H] upper bound of the global length
+    int64_t pages_ub;                // upper bound of pages in use
+    int attn_grid;
+    hipEvent_t ev0, ev1;
+};
+
+extern "C" {
+
+const char *wgkv_version(void) { return "wgkv-gfx950 0.1"; }
+
+int wgkv_get_meta_layout(const wgkv_config *cfg, wgkv_meta_layout *out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!out) return WGKV_ERR_INVALID_ARG;
+    make_layout(cfg, out);
+    return WGKV_OK;
+}
+
+int wgkv_query_sizes(const wgkv_config *cfg, int32_t max_call_seqs, int64_t max_call_tokens,
+                     size_t *pool_bytes, size_t *meta_bytes, size_t *workspace_bytes) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (max_call_seqs < 1 || max_call_seqs > WGKV_MAX_CALL_SEQS || max_call_tokens < 1 ||
+        max_call_tokens >= ((int64_t)1 << 31) ||
+        (int64_t)max_call_seqs * cfg->n_kv_heads > WGKV_MAX_CALL_UNITS)
+        return WGKV_ERR_INVALID_ARG;
+    wgkv_meta_layout lay;
+    make_layout(cfg, &lay);
+    View v = make_view(cfg, nullptr, nullptr);
+    if (pool_bytes) *pool_bytes = (size_t)cfg->n_pages * v.page_bytes;
+    if (meta_bytes) *meta_bytes = lay.total_bytes;
+    if (workspace_bytes) {
+        size_t a = prefill_ws(cfg, max_call_seqs, max_call_tokens, max_call_tokens).total;
+        size_t b = attend_decode_ws_bytes(v, max_call_seqs, kAttnGridMax);
+        size_t c = attend_prefill_ws_bytes(v, max_call_seqs, max_call_tokens);
+        size_t m = a > b ? a : b;
+        *workspace_bytes = align256(m > c ? m : c);
+    }
+    return WGKV_OK;
+}
+
+int wgkv_init_pool(const wgkv_config *cfg, void *pool_dev, size_t pool_bytes, void *meta_dev,
+                   size_t meta_bytes, wgkv_stream stream, wgkv_pool **out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!pool_dev || !meta_dev || !out) return WGKV_ERR_INVALID_ARG;
+    if (((uintptr_t)pool_dev & 255) || ((uintptr_t)meta_dev & 255)) return WGKV_ERR_INVALID_ARG;
+    wgkv_meta_layout lay;
+    make_layout(cfg, &lay);
+    View v = make_view(cfg, pool_dev, meta_dev);
+    if (pool_bytes < (size_t)cfg->n_pages * v.page_bytes || meta_bytes < lay.total_bytes)
+        return WGKV_ERR_INVALID_ARG;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+        return WGKV_ERR_HIP;
+    wgkv_pool *p = new (std::nothrow) wgkv_pool();
+    if (!p) return WGKV_ERR_INVALID_ARG;
+    p->cfg = *cfg;
+    p->view = v;
+    p->lay = lay;
+    const size_t n_sl = (size_t)cfg->max_seqs * cfg->n_layers;
+    p->seq_len_h.assign(n_sl, 0);
+    p->touched_h.assign(n_sl, 0);
+    p->g_ub.assign(n_sl * cfg->n_kv_heads, 0);
+    p->pages_ub = 0;
+    p->attn_grid = prop.multiProcessorCount * kAttnBlocksPerCu;
+    if (p->attn_grid > kAttnGridMax) p->attn_grid = kAttnGridMax;
+    if (p->attn_grid < 1) p->attn_grid = 1;
+    p->ev0 = p->ev1 = nullptr;
+    if (launch_init(v, (hipStream_t)stream) != hipSuccess) {
+        delete p;
+        return WGKV_ERR_HIP;
+    }
+    *out = p;
+    return WGKV_OK;
+}
+
+void wgkv_destroy(wgkv_pool *pool) { delete pool; }
+
+int wgkv_set_profile_events(wgkv_pool *pool, void *ev_begin, void *ev_end) {
+    if (!pool || ((ev_begin == nullptr) != (ev_end == nullptr))) return WGKV_ERR_INVALID_ARG;
+    pool->ev0 = (hipEvent_t)ev_begin;
+    pool->ev1 = (hipEvent_t)ev_end;
+    return WGKV_OK;
+}
+
+static int check_seqs(const wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *ids) {
+    if (!p || !ids) return WGKV_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= p->cfg.n_layers) return WGKV_ERR_INVALID_ARG;
+    if (n_seqs < 1 || n_seqs > WGKV_MAX_CALL_SEQS ||
+        (int64_t)n_seqs * p->cfg.n_kv_heads > WGKV_MAX_CALL_UNITS)
+        return WGKV_ERR_INVALID_ARG;
+    for (int i = 0; i < n_seqs; i++) {
+        if (ids[i] < 0 || ids[i] >= p->cfg.max_seqs) return WGKV_ERR_INVALID_ARG;
+        for (int j = 0; j < i; j++)
+            if (ids[j] == ids[i]) return WGKV_ERR_INVALID_ARG;
+    }
+    return WGKV_OK;
+}
+
+int wgkv_gate_scores(int32_t dtype, int64_t n_tokens, int32_t hidden_dim, int32_t n_kv_heads,
+                     const void *hidden_dev, const void *gate_w_dev, float *g_out_dev,
+                     wgkv_stream stream) {
+    if ((dtype != WGKV_F32 && dtype != WGKV_BF16) || n_tokens < 0 || hidden_dim < 8 ||
+        (hidden_dim % 8) || n_kv_heads < 1 || n_kv_heads > 16 || !hidden_dev || !gate_w_dev ||
+        !g_out_dev)
+        return WGKV_ERR_INVALID_ARG;
+    if (n_tokens == 0) return WGKV_OK;
+    return launch_gate_linear(dtype, n_tokens, hidden_dim, n_kv_heads, hidden_dev, gate_w_dev,
+                              g_out_dev, (hipStream_t)stream) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
+}
+
+int wgkv_prefill_admit(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                       const int32_t *n_tokens_host, const void *k_dev, const void *v_dev,
+                       const float *g_dev, const void *hidden_dev, const void *gate_w_dev,
+                       int32_t hidden_dim, float tau, uint8_t *admit_mask_out_dev,
+                       void *workspace_dev, size_t workspace_bytes, wgkv_stream stream) {
+    int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    if (!n_tokens_host || !workspace_dev) return WGKV_ERR_INVALID_ARG;
+    const wgkv_config &c = p->cfg;
+    const int W = c.w_local, P = c.page_size, H = c.n_kv_heads;
+    CallSeqs cs;
+    memset(&cs, 0, sizeof(cs));
+    cs.n = n_seqs;
+    int64_t total = 0, max_T = 0, max_leave = 0, max_ring = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        const int T = n_tokens_host[b];
+        if (T < 0) return WGKV_ERR_INVALID_ARG;
+        const int64_t t0 = p->seq_len_h[(size_t)seq_ids_host[b] * c.n_layers + layer];
+        if (t0 + T >= ((int64_t)1 << 30)) return WGKV_ERR_INVALID_ARG;
+        cs.sid[b] = seq_ids_host[b];
+        cs.t0[b] = (int32_t)t0;
+        cs.ntok[b] = T;
+        cs.base[b] = (int32_t)total;
+        total += T;
+        if (total >= ((int64_t)1 << 31) / (H > 0 ? H : 1)) return WGKV_ERR_INVALID_ARG;
+        const int64_t leave = std::max<int64_t>(0, t0 + T - W) - std::max<int64_t>(0, t0 - W);
+        max_T = std::max<int64_t>(max_T, T);
+        max_leave = std::max(max_leave, leave);
+        max_ring = std::max<int64_t>(max_ring, std::min(T, W));
+    }
+    if (total == 0) return WGKV_OK;
+    if (!k_dev || !v_dev) return WGKV_ERR_INVALID_ARG;
+    if (!g_dev && (!hidden_dev || !gate_w_dev || hidden_dim < 8 || (hidden_dim % 8))) return WGKV_ERR_INVALID_ARG;
+    const PrefillWs ws = prefill_ws(&c, n_seqs, total, max_T);
+    if (workspace_bytes < ws.total) return WGKV_ERR_WORKSPACE;
+    // worst case for the page bounds: every token that leaves the window is admitted
+    int64_t new_pages = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        const int T = cs.ntok[b];
+        if (T == 0) continue;
+        const size_t sl = (size_t)cs.sid[b] * c.n_layers + layer;
+        const int64_t t0 = cs.t0[b];
+        const int64_t leave = std::max<int64_t>(0, t0 + T - W) - std::max<int64_t>(0, t0 - W);
+        if (!p->touched_h[sl]) new_pages += (int64_t)p->view.nlp * H;
+        for (int h = 0; h < H; h++) {
+            const int64_t g0 = p->g_ub[sl * H + h], g1 = g0 + leave;
+            const int64_t pg1 = (g1 + P - 1) / P;
+            if (pg1 > c.max_global_pages_per_head) return WGKV_ERR_PT_OVERFLOW;
+            new_pages += pg1 - (g0 + P - 1) / P;
+        }
+    }
+    if (p->pages_ub + new_pages > c.n_pages) return WGKV_ERR_OUT_OF_PAGES;
+    hipStream_t st = (hipStream_t)stream;
+    char *wsp = (char *)workspace_dev;
+    const float *g = g_dev;
+    if (!g) {
+        float *gw = (float *)(wsp + ws.g_off);
+        if (launch_gate_linear(c.dtype, total, hidden_dim, H, hidden_dev, gate_w_dev, gw, st) != hipSuccess)
+            return WGKV_ERR_HIP;
+        g = gw;
+    }
+    const int nblk_leave = (int)((max_leave + kPrefillBlkHost - 1) / kPrefillBlkHost);
+    if (launch_prefill(p->view, cs, layer, tau, k_dev, v_dev, g, admit_mask_out_dev,
+                       (int32_t *)(wsp + ws.cnt_off), (int32_t *)(wsp + ws.plan_off), nblk_leave,
+                       (int)max_T, (int)max_ring, st) != hipSuccess)
+        return WGKV_ERR_HIP;
+    for (int b = 0; b < n_seqs; b++) {
+        const int T = cs.ntok[b];
+        if (T == 0) continue;
+        const size_t sl = (size_t)cs.sid[b] * c.n_layers + layer;
+        const int64_t t0 = cs.t0[b];
+        const int64_t leave = std::max<int64_t>(0, t0 + T - W) - std::max<int64_t>(0, t0 - W);
+        p->touched_h[sl] = 1;
+        p->seq_len_h[sl] = (int32_t)(t0 + T);
+        for (int h = 0; h < H; h++) p->g_ub[sl * H + h] += (int32_t)leave;
+    }
+    p->pages_ub += new_pages;
+    return WGKV_OK;
+}
+
+int wgkv_decode_step(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                     const void *k_new_dev, const void *v_new_dev, const float *g_new_dev,
+                     float tau, uint8_t *promoted_out_dev, wgkv_stream stream) {
+    int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    if (!k_new_dev || !v_new_dev || !g_new_dev) return WGKV_ERR_INVALID_ARG;
+    const wgkv_config &c = p->cfg;
+    const int W = c.w_local, P = c.page_size, H = c.n_kv_heads;
+    CallSeqs cs;
+    memset(&cs, 0, sizeof(cs));
+    cs.n = n_seqs;
+    int64_t new_pages = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        const size_t sl = (size_t)seq_ids_host[b] * c.n_layers + layer;
+        const int64_t t0 = p->seq_len_h[sl];
+        if (t0 + 1 >= ((int64_t)1 << 30)) return WGKV_ERR_INVALID_ARG;
+        cs.sid[b] = seq_ids_host[b];
+        cs.t0[b] = (int32_t)t0;
+        cs.ntok[b] = 1;
+        cs.base[b] = b;
+        if (!p->touched_h[sl]) new_pages += (int64_t)p->view.nlp * H;
+        if (t0 >= W)
+            for (int h = 0; h < H; h++) {
+                const int64_t g0 = p->g_ub[sl * H + h];
+                const int64_t pg1 = (g0 + 1 + P - 1) / P;
+                if (pg1 > c.max_global_pages_per_head) return WGKV_ERR_PT_OVERFLOW;
+                new_pages += pg1 - (g0 + P - 1) / P;
+            }
+    }
+    if (p->pages_ub + new_pages > c.n_pages) return WGKV_ERR_OUT_OF_PAGES;
+    if (launch_decode_step(p->view, cs, layer, tau, k_new_dev, v_new_dev, g_new_dev,
+                           promoted_out_dev, (hipStream_t)stream) != hipSuccess)
+        return WGKV_ERR_HIP;
+    for (int b = 0; b < n_seqs; b++) {
+        const size_t sl = (size_t)cs.sid[b] * c.n_layers + layer;
+        p->touched_h[sl] = 1;
+        if (cs.t0[b] >= W)
+            for (int h = 0; h < H; h++) p->g_ub[sl * H + h] += 1;
+        p->seq_len_h[sl] = cs.t0[b] + 1;
+    }
+    p->pages_ub += new_pages;
+    return WGKV_OK;
+}
+
+int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                const int32_t *n_q_host, const void *q_dev, const void *k_chunk_dev,
+                const void *v_chunk_dev, const float *g_chunk_dev, float tau, float scale,
+                float *out_dev, void *workspace_dev, size_t workspace_bytes, wgkv_stream stream) {
+    int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    if (!n_q_host || !q_dev || !out_dev || !workspace_dev || !std::isfinite(scale)) return WGKV_ERR_INVALID_ARG;
+    const bool prefill = k_chunk_dev != nullptr;
+    if (prefill != (v_chunk_dev != nullptr) || prefill != (g_chunk_dev != nullptr)) return WGKV_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (!prefill) {
+        for (int b = 0; b < n_seqs; b++)
+            if (n_q_host[b] != 1) return WGKV_ERR_INVALID_ARG;
+        if (workspace_bytes < attend_decode_ws_bytes(p->view, n_seqs, p->attn_grid)) return WGKV_ERR_WORKSPACE;
+        return launch_attend_decode(p->view, layer, n_seqs, seq_ids_host, q_dev, scale, out_dev,
+                                    workspace_dev, p->attn_grid, kAttnMinTilesPerBlock, st, p->ev0,
+                                    p->ev1) == hipSuccess
+                   ? WGKV_OK
+                   : WGKV_ERR_HIP;
+    }
+    CallSeqs cs;
+    memset(&cs, 0, sizeof(cs));
+    cs.n = n_seqs;
+    int64_t total = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        if (n_q_host[b] < 0) return WGKV_ERR_INVALID_ARG;
+        cs.sid[b] = seq_ids_host[b];
+        cs.t0[b] = p->seq_len_h[(size_t)seq_ids_host[b] * p->cfg.n_layers + layer];
+        cs.ntok[b] = n_q_host[b];
+        cs.base[b] = (int32_t)total;
+        total += n_q_host[b];
+        if (total >= ((int64_t)1 << 31) / p->cfg.n_q_heads) return WGKV_ERR_INVALID_ARG;
+    }
+    if (total == 0) return WGKV_OK;
+    if (workspace_bytes < attend_prefill_ws_bytes(p->view, n_seqs, total)) return WGKV_ERR_WORKSPACE;
+    return launch_attend_prefill(p->view, cs, layer, q_dev, k_chunk_dev, v_chunk_dev, g_chunk_dev,
+                                 tau, scale, out_dev, workspace_dev, st) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
+}
+
+int wgkv_free_seq(wgkv_pool *p, int32_t seq_id, wgkv_stream stream) {
+    if (!p || seq_id < 0 || seq_id >= p->cfg.max_seqs) return WGKV_ERR_INVALID_ARG;
+    if (launch_free_seq(p->view, seq_id, (hipStream_t)stream) != hipSuccess) return WGKV_ERR_HIP;
+    const wgkv_config &c = p->cfg;
+    const int P = c.page_size, H = c.n_kv_heads;
+    for (int l = 0; l < c.n_layers; l++) {
+        const size_t sl = (size_t)seq_id * c.n_layers + l;
+        if (p->touched_h[sl]) p->pages_ub -= (int64_t)p->view.nlp * H;
+        for (int h = 0; h < H; h++) {
+            p->pages_ub -= (p->g_ub[sl * H + h] + P - 1) / P;
+            p->g_ub[sl * H + h] = 0;
+        }
+        p->touched_h[sl] = 0;
+        p->seq_len_h[sl] = 0;
+    }
+    return WGKV_OK;
+}
+
+int wgkv_status(wgkv_pool *p, wgkv_stream stream, int64_t *pages_free, int32_t *device_error_flag) {
+    if (!p) return WGKV_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    int32_t top = 0, flag = 0;
+    std::vector<int32_t> gl(p->g_ub.size());
+    if (hipMemcpyAsync(&top, p->view.free_top, 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipMemcpyAsync(&flag, p->view.err_flag, 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipMemcpyAsync(gl.data(), p->view.global_len, gl.size() * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return WGKV_ERR_HIP;
+    if (pages_free) *pages_free = top;
+    if (device_error_flag) *device_error_flag = flag;
+    if (flag != 0) return WGKV_ERR_DEVICE_FLAG;
+    const wgkv_config &c = p->cfg;
+    int64_t used = 0;
+    for (size_t sl = 0; sl < p->touched_h.size(); sl++) {
+        if (p->touched_h[sl]) used += (int64_t)p->view.nlp * c.n_kv_heads;
+        for (int h = 0; h < c.n_kv_heads; h++) {
+            const size_t i = sl * c.n_kv_heads + h;
+            p->g_ub[i] = gl[i];
+            used += (gl[i] + c.page_size - 1) / c.page_size;
+        }
+    }
+    p->pages_ub = used;
+    return WGKV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Device-side view of the pool and small helpers shared by the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/wgkv.h"
+
+namespace wgkv {
+
+constexpr int kMaxCallSeqs = WGKV_MAX_CALL_SEQS;
+constexpr int kMaxCallUnits = WGKV_MAX_CALL_UNITS;
+
+// Everything a kernel needs to find its way through pool and metadata.
+struct View {
+    int32_t L, Hq, Hkv, d, dtype, es;   // es: bytes per element
+    int32_t P, logP, W, S, maxgp, nlp;  // nlp = ceil(W/P) local pages per head
+    int32_t G;                           // query heads per kv head
+    int32_t n_pages;
+    uint32_t row_bytes;                  // d * es
+    uint32_t v_off;                      // byte offset of the V half of a page: P * d * es
+    uint64_t page_bytes;                 // 2 * P * d * es
+    char *pool;
+    int32_t *seq_len, *global_len, *local_pt, *global_pt;
+    float *ring_g;
+    int32_t *free_stack, *free_top, *err_flag;
+};
+
+// The sequences of one call, passed by value in the kernel arguments.
+struct CallSeqs {
+    int32_t n;
+    int32_t sid[kMaxCallSeqs];   // sequence slot
+    int32_t t0[kMaxCallSeqs];    // tokens seen before this call (host mirror of seq_len)
+    int32_t ntok[kMaxCallSeqs];  // tokens / queries of this call
+    int32_t base[kMaxCallSeqs];  // first packed row of the sequence
+};
+
+__device__ __forceinline__ int unit_meta(const View &pv, int sid, int layer, int h) {
+    return (sid * pv.L + layer) * pv.Hkv + h;
+}
+
+__device__ __forceinline__ char *page_ptr(const View &pv, int page) {
+    return pv.pool + (uint64_t)(uint32_t)page * pv.page_bytes;
+}
+
+// ---- wave64 cross-lane helpers (DPP where the pattern allows) ----
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);
+}
+
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8 lanes
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16 lanes
+
+// Sum over aligned groups of N consecutive lanes; every lane of the group gets the total.
+template <int N>
+__device__ __forceinline__ float group_sum(float x) {
+    static_assert(N == 1 || N == 2 || N == 4 || N == 8 || N == 16 || N == 32 || N == 64, "");
+    if (N >= 2) x += dpp_f<kDppXor1>(x);
+    if (N >= 4) x += dpp_f<kDppXor2>(x);
+    if (N >= 8) x += dpp_f<kDppHalfMirror>(x);
+    if (N >= 16) x += dpp_f<kDppMirror>(x);
+    if (N >= 32) x += __shfl_xor(x, 16);
+    if (N >= 64) x += __shfl_xor(x, 32);
+    return x;
+}
+
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int n = __shfl_up(v, o);
+        if (lane >= o) v += n;
+    }
+    return v;
+}
+
+// Exclusive prefix over the values of one 256- or 1024-thread block.  s_tmp: >= 17 ints.
+// Returns the exclusive prefix of v for this thread; *total gets the block sum.
+__device__ __forceinline__ int block_excl_scan(int v, int *s_tmp, int *total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    int inc = wave_incl_scan(v, lane);
+    __syncthreads();
+    if (lane == 63) s_tmp[w] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int i = 0; i < nw; i++) { int x = s_tmp[i]; s_tmp[i] = run; run += x; }
+        s_tmp[16] = run;
+    }
+    __syncthreads();
+    int res = inc - v + s_tmp[w];
+    *total = s_tmp[16];
+    return res;
+}
+
+}  // namespace wgkv
