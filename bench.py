@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the Write-Gated KV hot path on one MI355X.
+
+A step is one new token for the whole batch through every layer of the workload:
+per layer `wgkv_decode_step` (lazy promotion + ring write) then `wgkv_attend`
+(ragged paged GQA decode attention).  Inputs are synthetic, seeded and already
+resident in HBM when the timed region starts.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import ctypes as C
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E published peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """Raw HIP events (the library records them around its main attention kernel)."""
+
+    def __init__(self, n):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self.ev = []
+        for _ in range(n):
+            e = C.c_void_p()
+            assert self.hip.hipEventCreate(C.byref(e)) == 0
+            self.ev.append(e.value)
+
+    def elapsed_ms(self, a, b):
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), C.c_void_p(a), C.c_void_p(b))
+        assert rc == 0, rc
+        return ms.value
+
+    def destroy(self):
+        for e in self.ev:
+            self.hip.hipEventDestroy(C.c_void_p(e))
+
+
+def attend_algorithmic_bytes(cfg, seq_len, global_len, layers):
+    """Bytes one decode-attention launch must move: K and V rows of the valid
+    tokens, the page-table entries that locate them, q in and out out."""
+    es = 4 if cfg.dtype == "f32" else 2
+    d, P, W, G = cfg.head_dim, cfg.page_size, cfg.w_local, cfg.n_q_heads // cfg.n_kv_heads
+    nlp = -(-W // P)
+    per_layer = []
+    for l in layers:
+        t = seq_len[:, l].astype(np.int64)                     # [B]
+        gl = global_len[:, l, :].astype(np.int64)              # [B, H]
+        tok = np.minimum(t, W)[:, None] + gl
+        b = tok * 2 * d * es + 4 * (nlp + -(-gl // P)) + G * d * es + G * d * 4
+        per_layer.append(int(b.sum()))
+    return per_layer
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--workload", default="llama8b_32layer_b8_128k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="skip the per-kernel HIP events (roofline.achieved becomes null)")
+    ap.add_argument("--ctx-scale", type=float, default=1.0, help="shrink contexts (debugging only)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_17452_amd as wg
+    import wgkv_workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = wl.get_config(args.workload)
+    B, L, Hq, Hk, d, W, P = cfg.batch, cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local, cfg.page_size
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    ctx = wl.context_lengths(cfg)
+    if args.ctx_scale != 1.0:
+        ctx = np.maximum((ctx * args.ctx_scale).astype(np.int64), W + 1)
+    rates = wl.unit_rates(cfg)
+    total_steps = args.steps + args.warmup
+    max_ctx = int(ctx.max())
+
+    # pool: expected admitted tokens + 10 % + room for the host's worst-case bound of one prefill call
+    exp_tokens = sum(float(rates[l, h]) * int(c) for c in ctx for l in range(L) for h in range(Hk))
+    exp_pages = exp_tokens / P * 1.10 + B * L * Hk * (-(-W // P) + 2 + -(-total_steps // P))
+    n_pages = int(exp_pages) + Hk * (max_ctx // P + 2) + 1024
+    max_gp = (max_ctx + total_steps) // P + 2
+    wcfg = wg.Config(L, Hq, Hk, d, wg.F32 if cfg.dtype == "f32" else wg.BF16, P, W, B, max_gp, n_pages)
+    t_setup = time.time()
+    pool = wg.Pool(wcfg, max_call_seqs=B, max_call_tokens=max_ctx)
+    log(f"[bench] workload {cfg.name}: B={B} L={L} ctx={ctx.tolist()} pool {n_pages} pages "
+        f"({pool.pool_buf.numel() / 2**30:.1f} GiB)")
+
+    def gen_prefill(seq, layer):
+        n = int(ctx[seq])
+        k = wl.draw_normal(cfg, "k", (n, Hk, d), device=dev, key=(seq, layer))
+        v = wl.draw_normal(cfg, "v", (n, Hk, d), device=dev, key=(seq, layer))
+        g = torch.from_numpy(wl.draw_scores(cfg, seq, layer, n, rates)).to(dev)
+        return k, v, g
+
+    for layer in range(L):
+        for seq in range(B):
+            k, v, g = gen_prefill(seq, layer)
+            pool.prefill_admit(layer, [seq], [int(ctx[seq])], k, v, g, tau=cfg.tau)
+            free, flag = pool.status()
+            assert flag == 0, f"device error flag {flag}"
+        if layer % 8 == 7:
+            log(f"[bench] prefilled layer {layer + 1}/{L}, free pages {free}")
+    del k, v, g
+    seqs = list(range(B))
+    # decode inputs: one K/V/Q set per layer (reused every step), fresh scores every step
+    k_new = [wl.draw_normal(cfg, "dec_k", (B, Hk, d), device=dev, key=(l,)) for l in range(L)]
+    v_new = [wl.draw_normal(cfg, "dec_v", (B, Hk, d), device=dev, key=(l,)) for l in range(L)]
+    q_new = [wl.draw_normal(cfg, "q", (B, Hq, d), device=dev, key=(l,)) for l in range(L)]
+    g_steps = np.stack([np.stack([np.concatenate([wl.draw_scores(cfg, s, l, 1, rates, purpose="dec_scores", step=st)
+                                                  for s in range(B)]) for l in range(L)])
+                        for st in range(total_steps)])            # [steps, L, B, Hk]
+    g_new = torch.from_numpy(g_steps).to(dev)
+    out = torch.empty((L, B, Hq, d), dtype=torch.float32, device=dev)
+    scale = 1.0 / math.sqrt(d)
+    log(f"[bench] setup {time.time() - t_setup:.1f}s")
+
+    def one_step(st, events=None):
+        for l in range(L):
+            pool.decode_step(l, seqs, k_new[l], v_new[l], g_new[st, l], tau=cfg.tau)
+            if events is not None:
+                i = (st - args.warmup) * L + l
+                pool.set_profile_events(events.ev[2 * i], events.ev[2 * i + 1])
+            pool.attend(l, seqs, q_new[l], out[l], scale)
+
+    for st in range(args.warmup):
+        one_step(st)
+    torch.cuda.synchronize()
+    meta = pool.meta()
+    sl0, gl0 = meta["seq_len"].cpu().numpy(), meta["global_len"].cpu().numpy()
+    events = None if args.no_kernel_events else HipEvents(2 * args.steps * L)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for st in range(args.warmup, total_steps):
+        one_step(st, events)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    pool.set_profile_events(None, None)
+    free, flag = pool.status()
+    assert flag == 0
+    sl1, gl1 = meta["seq_len"].cpu().numpy(), meta["global_len"].cpu().numpy()
+
+    bytes0 = attend_algorithmic_bytes(cfg, sl0, gl0, range(L))
+    bytes1 = attend_algorithmic_bytes(cfg, sl1, gl1, range(L))
+    bytes_per_launch = 0.5 * (np.mean(bytes0) + np.mean(bytes1))
+    roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                "traffic": None, "kernel": "attend_decode_kernel",
+                "algorithmic_bytes_per_launch": bytes_per_launch}
+    if events is not None:
+        durs = np.array([events.elapsed_ms(events.ev[2 * i], events.ev[2 * i + 1]) for i in range(args.steps * L)])
+        avg_us = float(durs.mean() * 1e3)
+        roofline.update({"achieved": bytes_per_launch / (avg_us * 1e-6) / 1e9,
+                         "frac": bytes_per_launch / (avg_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                         "kernel_avg_us": avg_us, "kernel_p10_us": float(np.percentile(durs, 10) * 1e3),
+                         "kernel_p90_us": float(np.percentile(durs, 90) * 1e3), "launches": int(len(durs))})
+        events.destroy()
+    traffic_file = os.path.join(ROOT, "profiles", "attend_decode_traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            roofline["traffic"] = json.load(open(traffic_file)).get("hbm_bytes_per_launch")
+        except Exception:
+            pass
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = run_cpu_baseline(cfg, wl, ctx, rates, dev, gen_prefill, k_new[0], v_new[0], g_new[0, 0],
+                                        q_new[0], scale, pool, seqs)
+
+    res = {
+        "metric": "decode_step_latency_us (all layers: lazy promotion + ragged paged GQA decode attention)",
+        "value": ms_per_step * 1e3, "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": B, "layers": L, "q_heads": Hq, "kv_heads": Hk, "head_dim": d,
+                   "w_local": W, "page_size": P, "tau": cfg.tau, "ctx_min": int(ctx.min()), "ctx_max": int(ctx.max()),
+                   "mean_cached_tokens_per_head": float((np.minimum(sl1, W)[:, :, None] + gl1).mean()),
+                   "attend_us_per_layer": roofline.get("kernel_avg_us"),
+                   "gpu_ms_per_step": gpu_ms / args.steps, "host_wall_ms_per_step": wall_ms / args.steps},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(res), flush=True)
+
+
+def run_cpu_baseline(cfg, wl, ctx, rates, dev, gen_prefill, k1, v1, g1, q, scale, pool, seqs):
+    """Times the CPU oracle (as it stands) on layer 0 of the same workload: one
+    decode-attention call for the whole batch, (sequence, kv head) units spread
+    over the host threads.  Reported per step by multiplying with the layer count."""
+    import torch
+    from oracle import Oracle, OracleConfig
+    B, L, Hq, Hk, d, W, P = cfg.batch, cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local, cfg.page_size
+    t0 = time.time()
+    max_gp = int(ctx.max()) // P + 8
+    n_pages = B * Hk * (max_gp + W // P + 1)
+    orc = Oracle(OracleConfig(1, Hq, Hk, d, P, W, B, max_gp, n_pages, True))
+    chunk = 8192
+    for s in range(B):
+        k, v, g = gen_prefill(s, 0)
+        for a in range(0, int(ctx[s]), chunk):
+            b = min(a + chunk, int(ctx[s]))
+            orc.push_tokens(0, [s], [b - a], k[a:b].float().cpu().numpy(), v[a:b].float().cpu().numpy(),
+                            g[a:b].cpu().numpy(), cfg.tau)
+        del k, v, g
+    log(f"[bench] oracle state for layer 0 built in {time.time() - t0:.1f}s")
+    orc.push_tokens(0, seqs, [1] * B, k1.float().cpu().numpy(), v1.float().cpu().numpy(), g1.cpu().numpy(), cfg.tau)
+    qh = q.float().cpu().numpy()
+    reps, best = 3, None
+    for _ in range(reps):
+        t1 = time.perf_counter()
+        ref, threads = orc.attend_cached_batch(0, seqs, qh, scale)
+        dt = time.perf_counter() - t1
+        best = dt if best is None else min(best, dt)
+    tokens = sum(orc.global_len(s, 0, h) + min(orc.seq_len(s, 0), W) for s in range(B) for h in range(Hk))
+    return {"value": best * 1e6 * L, "unit": "us/step", "cores": int(threads), "kind": "oracle",
+            "sample": f"decode attention of layer 0 only (batch {B}, {tokens} cached tokens over {B * Hk} "
+                      f"(sequence, kv head) units), best of {reps}, {best * 1e3:.1f} ms per layer call, "
+                      f"multiplied by {L} layers (extrapolated); promotion/paging not included",
+            "layer_call_ms": best * 1e3}
+
+
+if __name__ == "__main__":
+    main()

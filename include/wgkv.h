@@ -88,9 +88,11 @@ typedef struct {
  *   free_stack int32 [n_pages]       LIFO of free pages
  *   free_top   int32                 number of free pages
  *   err_flag   int32                 sticky: 0 ok, else first WGKV_ERR_* seen on device
+ *   unit_counters int32 [WGKV_MAX_CALL_UNITS]  scratch of wgkv_attend, zero between calls
  * Pool: element [page][0=K,1=V][slot 0..P-1][head_dim]. */
 typedef struct {
     size_t seq_len, global_len, local_pt, global_pt, ring_g, free_stack, free_top, err_flag;
+    size_t unit_counters;
     size_t total_bytes;
     int32_t n_local_pages;
 } wgkv_meta_layout;

@@ -34,7 +34,8 @@ class _CConfig(C.Structure):
 
 class _CLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in ("seq_len", "global_len", "local_pt", "global_pt", "ring_g",
-                                          "free_stack", "free_top", "err_flag", "total_bytes")] + \
+                                          "free_stack", "free_top", "err_flag", "unit_counters",
+                                          "total_bytes")] + \
                [("n_local_pages", C.c_int32)]
 
 

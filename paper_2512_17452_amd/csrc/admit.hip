@@ -45,6 +45,7 @@ __global__ void init_kernel(View pv) {
     for (size_t i = i0; i < n_u * pv.nlp; i += stride) pv.local_pt[i] = -1;
     for (size_t i = i0; i < n_u * pv.maxgp; i += stride) pv.global_pt[i] = -1;
     for (size_t i = i0; i < n_u * pv.W; i += stride) pv.ring_g[i] = 0.0f;
+    for (size_t i = i0; i < (size_t)kMaxCallUnits; i += stride) pv.unit_counters[i] = 0;
     if (i0 == 0) { *pv.free_top = pv.n_pages; *pv.err_flag = 0; }
 }
 

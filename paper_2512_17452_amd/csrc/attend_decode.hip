@@ -5,16 +5,21 @@
 // G query heads of the group all read the same K/V rows (Sec. 4.3 last sentence,
 // Sec. 2.1 equation; head-to-batch folding of App. A).  The cached tokens of all
 // units, cut into 16-token tiles, form one long list that is split EVENLY over the
-// blocks of the launch -- a block's share may start in the middle of one unit and
-// end in the middle of another -- and every (block, unit) overlap leaves a partial
-// (m, l, acc) that a second kernel merges (the split-then-reduce balancing of
-// App. E "Decode phase", taken down to tile granularity).
+// waves of the launch -- a wave's share may start in the middle of one unit and end
+// in the middle of another -- and every (wave, unit) overlap leaves a partial
+// (m, l, acc); the wave that finishes a unit last folds the partials of that unit
+// (the split-then-reduce balancing of App. E "Decode phase", taken down to tile
+// granularity, without a second launch and without any wave waiting for another).
 //
 // Data path: each lane loads 16 bytes of a K row and of a V row straight into
-// registers; 64 lanes x 16 B = 1 KiB per load instruction, fully coalesced, next
-// tile in flight while the current one is reduced.  A 16-lane (256-byte row) group
-// owns one token per row, so a wave holds 64/LPT independent online-softmax
-// streams that are only combined when a unit ends.
+// registers; 64 lanes x 16 B = 1 KiB per load instruction, fully coalesced.  A wave
+// keeps several tiles in flight in separate register sets that are refilled in
+// place as soon as they have been consumed, so that few waves per SIMD are enough
+// to cover the HBM latency and no wave depends on the issue priority of another.
+// A 16-lane (256-byte row) group owns one token per row, so a wave holds 64/LPT
+// independent online-softmax streams that are only combined when a unit ends.
+#include <type_traits>
+
 #include "wgkv_dev.h"
 
 namespace wgkv {
@@ -22,18 +27,18 @@ namespace wgkv {
 constexpr int kTile = 16;        // tokens per tile
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = 4;
-constexpr int kPtStage = 1056;   // page ids staged in LDS per piece
+constexpr int kStagesFast = 4;   // tiles in flight per wave on the fast path
 
 struct AttendArgs {
     int layer;
     int n_seqs;
-    int min_tpb;              // at least this many tiles per block
+    int min_tpw;              // at least this many tiles per wave
     float scale_log2e;        // scale * log2(e)
     const char *q;            // [n_seqs][Hq][d]
     float *out;               // [n_seqs][Hq][d]
-    float *part_ml;           // [(grid + n_units)][G][2]
-    float *part_acc;          // [(grid + n_units)][G][d]
-    int32_t *tile_start;      // [n_units + 1] written by block 0 for the merge kernel
+    float *part_ml;           // [(waves + n_units)][G][2]
+    float *part_acc;          // [(waves + n_units)][G][d]
+    int32_t *counters;        // [n_units] zero between calls: waves done per unit
     int32_t sid[kMaxCallSeqs];
 };
 
@@ -71,8 +76,21 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
                                            __builtin_bit_cast(bf16x2_t, b), c, false);
 }
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {  // round to nearest even
+    bf16x2_t t = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, t);
+}
 __device__ __forceinline__ float bf16_lo(uint32_t x) { return __uint_as_float(x << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t x) { return __uint_as_float(x & 0xffff0000u); }
+
+// Partials cross compute units (and their L2 slices) inside one launch: they are
+// written and read with device-coherent accesses, so no cache-wide flush is needed.
+__device__ __forceinline__ void st_coherent(float *p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_coherent(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 template <int DT, int D, int G>
 __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, AttendArgs a) {
@@ -81,28 +99,41 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
     constexpr int LPT = D / EPL;      // lanes per token row
     constexpr int TPW = 64 / LPT;     // token rows per wave load
     constexpr int RPT = kTile / TPW;  // wave loads per tile (K and V each)
+    constexpr int ROWB = D * ES;      // bytes of a K or V row
     static_assert(LPT == 8 || LPT == 16 || LPT == 32, "row must be 128, 256 or 512 bytes");
+    // 256-byte rows with four query heads per kv head (every workload shape of the
+    // paper's two models): the 16 scores of a tile are spread over the 16 lanes of a
+    // row group, one per lane, so that max, exp and sum run once instead of 16 times.
+    // In that mode m[0] and l[0] belong to head sub%4; the other entries are unused.
+    constexpr bool FAST = (LPT == 16 && G == 4);
+    constexpr int S = FAST ? kStagesFast : 1;  // register sets = tiles in flight
 
     __shared__ int s_ts[kMaxCallUnits + 1];
     __shared__ int s_tmp[20];
-    __shared__ int s_pt[kPtStage];
-    __shared__ float s_m[kAttnWaves][G], s_l[kAttnWaves][G];
-    __shared__ float s_acc[kAttnWaves][G][D];
+    __shared__ float s_p[kAttnWaves][64];          // fp32 weights of a tile (fp32 pool)
+    __shared__ uint32_t s_pk[kAttnWaves][4][2][4]; // bf16 weight pairs of a tile: [row group][row pair][head]
 
     const int n_units = a.n_seqs * pv.Hkv;
     build_tile_prefix(pv, a, n_units, s_ts, s_tmp);
     const int total = s_ts[n_units];
-    if (blockIdx.x == 0)
-        for (int i = threadIdx.x; i <= n_units; i += kAttnThreads) a.tile_start[i] = s_ts[i];
-    const int tpb = max(a.min_tpb, (total + (int)gridDim.x - 1) / (int)gridDim.x);
-    const int T0 = blockIdx.x * tpb;
-    const int T1 = min(total, T0 + tpb);
-    if (T0 >= T1) return;  // block-uniform
-
+    if (blockIdx.x == 0) {  // units with nothing cached: the output is defined as zero
+        for (int uu = 0; uu < n_units; uu++)
+            if (s_ts[uu + 1] == s_ts[uu]) {
+                float *o = a.out + ((size_t)(uu / pv.Hkv) * pv.Hq + (size_t)(uu % pv.Hkv) * G) * D;
+                for (int i = threadIdx.x; i < G * D; i += kAttnThreads) o[i] = 0.f;
+            }
+    }
+    // From here on every wave works alone: no block-wide barrier below this line.
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPT, sub = lane % LPT;
+    const int n_waves = (int)gridDim.x * kAttnWaves;
+    const int tpw = max(a.min_tpw, (total + n_waves - 1) / n_waves);
+    const int wid = (int)blockIdx.x * kAttnWaves + wave;
+    const int T0 = wid * tpw;
+    const int T1 = min(total, T0 + tpw);
+    if (T0 >= T1) return;
 
-    // first unit of the share: largest u with s_ts[u] <= T0 and s_ts[u+1] > T0
+    // first unit of the share: the u with s_ts[u] <= T0 < s_ts[u+1]
     int u;
     {
         int lo = 0, hi = n_units - 1;
@@ -111,12 +142,12 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
             if (s_ts[mid] <= T0) lo = mid; else hi = mid - 1;
         }
         u = lo;
-        while (s_ts[u + 1] <= T0) u++;  // skip units without tiles
     }
+    const uint32_t lane_off = (uint32_t)(grp * ROWB + sub * 16);
 
     int cur = T0;
     while (cur < T1) {
-        while (s_ts[u + 1] <= cur) u++;
+        while (s_ts[u + 1] <= cur) u++;  // also skips units without tiles
         const int b = u / pv.Hkv, h = u % pv.Hkv, sid = a.sid[b];
         const int um = unit_meta(pv, sid, a.layer, h);
         const int gl = pv.global_len[um];
@@ -144,101 +175,308 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
         }
 
         while (cur < u_end) {
-            // one piece: tiles [k0, k1) of one region (global or local) of unit u
+            // one piece: at most 64 tiles [k0, k0+n) of one region (global or local) of unit u
             const int kk = cur - u_begin;
             const bool is_glob = kk < n_gt;
             const int k0 = is_glob ? kk : kk - n_gt;
             const int region_tiles = is_glob ? n_gt : ceil_tiles(nloc);
             const int count = is_glob ? gl : nloc;
-            const int piece_cap = pv.logP >= 4 ? 1024 : (64 << pv.logP);
-            const int k1 = min(min(region_tiles, k0 + piece_cap), k0 + (u_end - cur));
+            const int n = min(min(region_tiles - k0, 64), u_end - cur);
             const int32_t *pt = is_glob ? pv.global_pt + (size_t)um * pv.maxgp
                                         : pv.local_pt + (size_t)um * pv.nlp;
-            const int page0 = (k0 * kTile) >> pv.logP;
-            const int page1 = (min(k1 * kTile, count) - 1) >> pv.logP;
-            __syncthreads();  // previous piece is done with s_pt
-            for (int i = threadIdx.x; i <= page1 - page0; i += kAttnThreads) s_pt[i] = pt[page0 + i];
-            __syncthreads();
+            // A tile inside one page (P >= 16) needs one page id for the whole wave:
+            // lane i keeps the page id of tile k0+i and the base address goes through
+            // scalar registers.  Only full tiles take that pipelined path; a partial
+            // last tile, and every tile when pages are smaller than a tile, is handled
+            // one at a time afterwards with a page lookup per row.
+            const bool page_per_tile = pv.logP >= 4;
+            const int n_fast = page_per_tile ? max(0, min(n, count / kTile - k0)) : 0;
+            int ptreg = 0;
 
-            uint4 kb[RPT], vb[RPT], kn[RPT], vn[RPT];
-            auto load_tile = [&](int k, uint4 *kd, uint4 *vd) {
+            // Row addresses of full tile j (clamped to the last full tile of the piece: a
+            // tile asked for beyond the end is re-read and never used).  No memory access.
+            auto tile_rows = [&](int j, const char *(&rowp)[RPT]) {
+                j = min(j, n_fast - 1);
+                const int k = k0 + j;
+                const int page = __builtin_amdgcn_readlane(ptreg, j);
+                const char *base = page_ptr(pv, page) + (size_t)((k * kTile) & (pv.P - 1)) * ROWB;
+#pragma unroll
+                for (int r = 0; r < RPT; r++) rowp[r] = base + (lane_off + (uint32_t)(r * TPW * ROWB));
+            };
+            // Row addresses of any tile, one page lookup per row.
+            auto tile_rows_any = [&](int j, const char *(&rowp)[RPT]) {
+                const int k = k0 + j;
 #pragma unroll
                 for (int r = 0; r < RPT; r++) {
                     int tok = k * kTile + r * TPW + grp;
-                    tok = min(tok, count - 1);
-                    const int page = s_pt[(tok >> pv.logP) - page0];
-                    const char *p = page_ptr(pv, page) + (size_t)(tok & (pv.P - 1)) * pv.row_bytes + sub * 16;
-                    kd[r] = *reinterpret_cast<const uint4 *>(p);
-                    vd[r] = *reinterpret_cast<const uint4 *>(p + pv.v_off);
+                    tok = min(tok, count - 1);  // rows past the end re-read a valid row and get weight 0
+                    const int page = pt[tok >> pv.logP];
+                    rowp[r] = page_ptr(pv, page) + (size_t)(tok & (pv.P - 1)) * ROWB + sub * 16;
                 }
             };
-            int k = k0 + wave;
-            if (k < k1) load_tile(k, kb, vb);
-            while (k < k1) {
-                const int kn_i = k + kAttnWaves;
-                if (kn_i < k1) load_tile(kn_i, kn, vn);
-                // ---- scores of the tile: s[r][g] ----
-                float s[RPT][G];
+
+            uint4 kb[S][RPT], vb[S][RPT];
+
+            // One tile out of register set ST; the set is refilled with tile j+S.
+            auto process = [&](auto st_tag, auto refill_tag, int j) {
+                constexpr int ST = decltype(st_tag)::value;
+                constexpr bool REFILL = decltype(refill_tag)::value;
+                const int k = k0 + j;
+                const char *rowp[RPT];
+                if constexpr (REFILL) tile_rows(j + S, rowp);
+                if constexpr (FAST) {
+                    // ---- 16 partial dot products per lane: x[r*4+g]; a K row register is
+                    //      refilled as soon as it has been used ----
+                    float x[16];
 #pragma unroll
-                for (int r = 0; r < RPT; r++) {
-                    const uint32_t kw[4] = {kb[r].x, kb[r].y, kb[r].z, kb[r].w};
+                    for (int r = 0; r < 4; r++) {
+                        const uint32_t kw[4] = {kb[ST][r].x, kb[ST][r].y, kb[ST][r].z, kb[ST][r].w};
+#pragma unroll
+                        for (int g = 0; g < 4; g++) {
+                            float d = 0.f;
+                            if (DT == WGKV_BF16) {
+#pragma unroll
+                                for (int e = 0; e < 4; e++) d = dot2_bf16(kw[e], qreg[g][e], d);
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; e++) d = fmaf(__uint_as_float(kw[e]), __uint_as_float(qreg[g][e]), d);
+                            }
+                            x[r * 4 + g] = d;
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (REFILL) kb[ST][r] = *reinterpret_cast<const uint4 *>(rowp[r]);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    // ---- reduce-scatter over the 16 lanes of the row group: lane `sub`
+                    //      ends up with the full dot product x[sub], i.e. row sub/4, head sub%4 ----
+                    float y8[8], y4[4], y2[2];
+#pragma unroll
+                    for (int i = 0; i < 8; i++) {
+                        const float lo_ = x[i] + dpp_f<kDppRor8>(x[i]);
+                        const float hi_ = x[i + 8] + dpp_f<kDppRor8>(x[i + 8]);
+                        y8[i] = (sub & 8) ? hi_ : lo_;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        const float lo_ = y8[i] + dpp_f<kDppShl4>(y8[i]);
+                        const float hi_ = y8[i + 4] + dpp_f<kDppShr4>(y8[i + 4]);
+                        y4[i] = (sub & 4) ? hi_ : lo_;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 2; i++) {
+                        const float lo_ = y4[i] + dpp_f<kDppXor2>(y4[i]);
+                        const float hi_ = y4[i + 2] + dpp_f<kDppXor2>(y4[i + 2]);
+                        y2[i] = (sub & 2) ? hi_ : lo_;
+                    }
+                    float sc;
+                    {
+                        const float lo_ = y2[0] + dpp_f<kDppXor1>(y2[0]);
+                        const float hi_ = y2[1] + dpp_f<kDppXor1>(y2[1]);
+                        sc = (sub & 1) ? hi_ : lo_;
+                    }
+                    const int tok_l = k * kTile + (sub >> 2) * TPW + grp;
+                    sc = tok_l < count ? sc * a.scale_log2e : -INFINITY;
+                    // ---- online softmax on one (row, head) per lane; lanes sub, sub^4, sub^8,
+                    //      sub^12 hold the four rows of the same head ----
+                    float mt = fmaxf(sc, dpp_f<kDppRor8>(sc));
+                    mt = fmaxf(mt, dpp_f<kDppRor4>(mt));
+                    const float mnew = fmaxf(m[0], mt);
+                    const float msafe = mnew == -INFINITY ? 0.f : mnew;
+                    const float corr = __builtin_amdgcn_exp2f(m[0] - msafe);
+                    float pl = __builtin_amdgcn_exp2f(sc - msafe);
+                    uint32_t pb = 0;
+                    if constexpr (DT == WGKV_BF16) {
+                        // the weights enter the weighted sum as bf16 pairs (rows 2i, 2i+1);
+                        // the denominator sums the same rounded values
+                        pb = pack_bf16(pl, dpp_f<kDppShl4>(pl));
+                        pl = bf16_lo(pb);
+                    }
+                    float ps = pl + dpp_f<kDppRor8>(pl);
+                    ps += dpp_f<kDppRor4>(ps);
+                    l[0] = l[0] * corr + ps;
+                    if (__builtin_amdgcn_ballot_w64(mnew > m[0]) != 0) {  // rare once the maxima settle
+                        const float c0 = dpp_f<0x00>(corr), c1 = dpp_f<0x55>(corr);
+                        const float c2 = dpp_f<0xAA>(corr), c3 = dpp_f<0xFF>(corr);
+#pragma unroll
+                        for (int e = 0; e < EPL; e++) {
+                            acc[0][e] *= c0; acc[1][e] *= c1; acc[2][e] *= c2; acc[3][e] *= c3;
+                        }
+                    }
+                    m[0] = mnew;
+                    // ---- weights back to the row layout through the wave's LDS strip ----
+                    if constexpr (DT == WGKV_BF16) {
+                        if ((sub & 4) == 0) s_pk[wave][grp][sub >> 3][sub & 3] = pb;
+                        __builtin_amdgcn_wave_barrier();
+                        const uint4 pk0 = *reinterpret_cast<const uint4 *>(&s_pk[wave][grp][0][0]);
+                        const uint4 pk1 = *reinterpret_cast<const uint4 *>(&s_pk[wave][grp][1][0]);
+                        const uint32_t pk[2][4] = {{pk0.x, pk0.y, pk0.z, pk0.w}, {pk1.x, pk1.y, pk1.z, pk1.w}};
+#pragma unroll
+                        for (int i = 0; i < 2; i++) {
+                            const uint32_t va[4] = {vb[ST][2 * i].x, vb[ST][2 * i].y, vb[ST][2 * i].z, vb[ST][2 * i].w};
+                            const uint32_t vc[4] = {vb[ST][2 * i + 1].x, vb[ST][2 * i + 1].y, vb[ST][2 * i + 1].z,
+                                                    vb[ST][2 * i + 1].w};
+#pragma unroll
+                            for (int e = 0; e < 4; e++) {
+                                const uint32_t lo2 = __builtin_amdgcn_perm(vc[e], va[e], 0x05040100u);
+                                const uint32_t hi2 = __builtin_amdgcn_perm(vc[e], va[e], 0x07060302u);
+#pragma unroll
+                                for (int g = 0; g < 4; g++) {
+                                    acc[g][2 * e] = dot2_bf16(lo2, pk[i][g], acc[g][2 * e]);
+                                    acc[g][2 * e + 1] = dot2_bf16(hi2, pk[i][g], acc[g][2 * e + 1]);
+                                }
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                            if constexpr (REFILL) {
+                                vb[ST][2 * i] = *reinterpret_cast<const uint4 *>(rowp[2 * i] + pv.v_off);
+                                vb[ST][2 * i + 1] = *reinterpret_cast<const uint4 *>(rowp[2 * i + 1] + pv.v_off);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                    } else {
+                        s_p[wave][lane] = pl;
+                        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                        for (int r = 0; r < 4; r++) {
+                            const float4 pr = *reinterpret_cast<const float4 *>(&s_p[wave][grp * 16 + r * 4]);
+                            const float pg[4] = {pr.x, pr.y, pr.z, pr.w};
+                            const uint32_t vw[4] = {vb[ST][r].x, vb[ST][r].y, vb[ST][r].z, vb[ST][r].w};
+#pragma unroll
+                            for (int e = 0; e < 4; e++)
+#pragma unroll
+                                for (int g = 0; g < 4; g++) acc[g][e] = fmaf(pg[g], __uint_as_float(vw[e]), acc[g][e]);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if constexpr (REFILL) vb[ST][r] = *reinterpret_cast<const uint4 *>(rowp[r] + pv.v_off);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                } else {
+                    // ---- scores of the tile, every lane of a row group gets all of them ----
+                    float s[RPT][G];
+#pragma unroll
+                    for (int r = 0; r < RPT; r++) {
+                        const uint32_t kw[4] = {kb[ST][r].x, kb[ST][r].y, kb[ST][r].z, kb[ST][r].w};
+                        const int tok = k * kTile + r * TPW + grp;
+#pragma unroll
+                        for (int g = 0; g < G; g++) {
+                            float d = 0.f;
+                            if (DT == WGKV_BF16) {
+#pragma unroll
+                                for (int e = 0; e < 4; e++) d = dot2_bf16(kw[e], qreg[g][e], d);
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; e++) d = fmaf(__uint_as_float(kw[e]), __uint_as_float(qreg[g][e]), d);
+                            }
+                            d = group_sum<LPT>(d);
+                            s[r][g] = tok < count ? d * a.scale_log2e : -INFINITY;
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);  // the K registers are free from here on
+                    if constexpr (REFILL) {
+#pragma unroll
+                        for (int r = 0; r < RPT; r++) kb[ST][r] = *reinterpret_cast<const uint4 *>(rowp[r]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    // ---- online softmax per query head, one rescale per tile ----
+                    float p[RPT][G];
 #pragma unroll
                     for (int g = 0; g < G; g++) {
-                        float d = 0.f;
-                        if (DT == WGKV_BF16) {
+                        float mt = s[0][g];
 #pragma unroll
-                            for (int e = 0; e < 4; e++) d = dot2_bf16(kw[e], qreg[g][e], d);
-                        } else {
+                        for (int r = 1; r < RPT; r++) mt = fmaxf(mt, s[r][g]);
+                        const float mnew = fmaxf(m[g], mt);
+                        const float msafe = mnew == -INFINITY ? 0.f : mnew;
+                        const float corr = __builtin_amdgcn_exp2f(m[g] - msafe);
+                        m[g] = mnew;
+                        float ps = 0.f;
 #pragma unroll
-                            for (int e = 0; e < 4; e++) d = fmaf(__uint_as_float(kw[e]), __uint_as_float(qreg[g][e]), d);
+                        for (int r = 0; r < RPT; r++) {
+                            p[r][g] = __builtin_amdgcn_exp2f(s[r][g] - msafe);
+                            ps += p[r][g];
                         }
-                        d = group_sum<LPT>(d);
-                        const int tok = k * kTile + r * TPW + grp;
-                        s[r][g] = tok < count ? d * a.scale_log2e : -INFINITY;
+                        l[g] = l[g] * corr + ps;
+#pragma unroll
+                        for (int e = 0; e < EPL; e++) acc[g][e] *= corr;
                     }
-                }
-                // ---- online softmax per query head, one rescale per tile ----
-#pragma unroll
-                for (int g = 0; g < G; g++) {
-                    float mt = s[0][g];
-#pragma unroll
-                    for (int r = 1; r < RPT; r++) mt = fmaxf(mt, s[r][g]);
-                    const float mnew = fmaxf(m[g], mt);
-                    const float msafe = mnew == -INFINITY ? 0.f : mnew;
-                    const float corr = __builtin_amdgcn_exp2f(m[g] - msafe);
-                    m[g] = mnew;
-                    float p[RPT], ps = 0.f;
 #pragma unroll
                     for (int r = 0; r < RPT; r++) {
-                        p[r] = __builtin_amdgcn_exp2f(s[r][g] - msafe);
-                        ps += p[r];
-                    }
-                    l[g] = l[g] * corr + ps;
-#pragma unroll
-                    for (int e = 0; e < EPL; e++) acc[g][e] *= corr;
-#pragma unroll
-                    for (int r = 0; r < RPT; r++) {
-                        const uint32_t vw[4] = {vb[r].x, vb[r].y, vb[r].z, vb[r].w};
+                        const uint32_t vw[4] = {vb[ST][r].x, vb[ST][r].y, vb[ST][r].z, vb[ST][r].w};
                         if (DT == WGKV_BF16) {
 #pragma unroll
                             for (int e = 0; e < 4; e++) {
-                                acc[g][2 * e] = fmaf(p[r], bf16_lo(vw[e]), acc[g][2 * e]);
-                                acc[g][2 * e + 1] = fmaf(p[r], bf16_hi(vw[e]), acc[g][2 * e + 1]);
+                                const float vlo = bf16_lo(vw[e]), vhi = bf16_hi(vw[e]);
+#pragma unroll
+                                for (int g = 0; g < G; g++) {
+                                    acc[g][2 * e] = fmaf(p[r][g], vlo, acc[g][2 * e]);
+                                    acc[g][2 * e + 1] = fmaf(p[r][g], vhi, acc[g][2 * e + 1]);
+                                }
                             }
                         } else {
 #pragma unroll
-                            for (int e = 0; e < 4; e++) acc[g][e] = fmaf(p[r], __uint_as_float(vw[e]), acc[g][e]);
+                            for (int e = 0; e < 4; e++)
+#pragma unroll
+                                for (int g = 0; g < G; g++) acc[g][e] = fmaf(p[r][g], __uint_as_float(vw[e]), acc[g][e]);
                         }
                     }
-                }
+                    __builtin_amdgcn_sched_barrier(0);  // the V registers are free from here on
+                    if constexpr (REFILL) {
 #pragma unroll
-                for (int r = 0; r < RPT; r++) { kb[r] = kn[r]; vb[r] = vn[r]; }
-                k = kn_i;
+                        for (int r = 0; r < RPT; r++) vb[ST][r] = *reinterpret_cast<const uint4 *>(rowp[r] + pv.v_off);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+
+            if (n_fast > 0) {
+                ptreg = pt[((k0 + min(lane, n_fast - 1)) * kTile) >> pv.logP];
+                // prologue: fill every register set
+#pragma unroll
+                for (int st = 0; st < S; st++) {
+                    const char *rowp[RPT];
+                    tile_rows(st, rowp);
+#pragma unroll
+                    for (int r = 0; r < RPT; r++) kb[st][r] = *reinterpret_cast<const uint4 *>(rowp[r]);
+#pragma unroll
+                    for (int r = 0; r < RPT; r++) vb[st][r] = *reinterpret_cast<const uint4 *>(rowp[r] + pv.v_off);
+                }
+                // Main loop: S tiles per trip, straight-line, so that every wait is for exactly
+                // the load that is needed and the younger ones stay in flight.
+                int j = 0;
+                for (; j + S <= n_fast; j += S) {
+                    process(std::integral_constant<int, 0>{}, std::true_type{}, j);
+                    if constexpr (S > 1) process(std::integral_constant<int, 1 % S>{}, std::true_type{}, j + 1);
+                    if constexpr (S > 2) process(std::integral_constant<int, 2 % S>{}, std::true_type{}, j + 2);
+                    if constexpr (S > 3) process(std::integral_constant<int, 3 % S>{}, std::true_type{}, j + 3);
+                }
+                // the last n_fast % S full tiles are already in their register sets: no more loads
+                if constexpr (S > 1) {
+                    if (j < n_fast) process(std::integral_constant<int, 0>{}, std::false_type{}, j);
+                    if (j + 1 < n_fast) process(std::integral_constant<int, 1 % S>{}, std::false_type{}, j + 1);
+                }
+                if constexpr (S > 3) {
+                    if (j + 2 < n_fast) process(std::integral_constant<int, 2 % S>{}, std::false_type{}, j + 2);
+                }
             }
-            cur += k1 - k0;
+            // whatever is left of the piece, one tile at a time through register set 0
+            for (int j = n_fast; j < n; j++) {
+                const char *rowp[RPT];
+                tile_rows_any(j, rowp);
+#pragma unroll
+                for (int r = 0; r < RPT; r++) kb[0][r] = *reinterpret_cast<const uint4 *>(rowp[r]);
+#pragma unroll
+                for (int r = 0; r < RPT; r++) vb[0][r] = *reinterpret_cast<const uint4 *>(rowp[r] + pv.v_off);
+                process(std::integral_constant<int, 0>{}, std::false_type{}, j);
+            }
+            cur += n;
         }
 
-        // ---- unit (or share) ends: combine the streams of the block, write one partial ----
+        // ---- the unit (or the share) ends: fold the wave's row groups into one state ----
+        if constexpr (FAST) {  // back to one (m, l) per head in every lane
+            const float m1 = m[0], l1 = l[0];
+            m[0] = dpp_f<0x00>(m1); m[1] = dpp_f<0x55>(m1); m[2] = dpp_f<0xAA>(m1); m[3] = dpp_f<0xFF>(m1);
+            l[0] = dpp_f<0x00>(l1); l[1] = dpp_f<0x55>(l1); l[2] = dpp_f<0xAA>(l1); l[3] = dpp_f<0xFF>(l1);
+        }
 #pragma unroll
         for (int off = LPT; off < 64; off <<= 1) {
 #pragma unroll
@@ -253,81 +491,103 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                 m[g] = mn;
             }
         }
-        __syncthreads();  // s_acc free again
-        if (lane < LPT) {
+        // waves whose share overlaps this unit
+        const int w_first = s_ts[u] / tpw, w_last = (s_ts[u + 1] - 1) / tpw;
+        float *o = a.out + ((size_t)b * pv.Hq + (size_t)h * G) * D;
+        if (w_first == w_last) {  // the unit lies inside this wave's share
+            if (lane < LPT) {
 #pragma unroll
-            for (int g = 0; g < G; g++) {
-                if (sub == 0) { s_m[wave][g] = m[g]; s_l[wave][g] = l[g]; }
+                for (int g = 0; g < G; g++) {
+                    const float inv = 1.0f / l[g];
 #pragma unroll
-                for (int e = 0; e < EPL; e++) s_acc[wave][g][sub * EPL + e] = acc[g][e];
+                    for (int e = 0; e < EPL; e++) o[g * D + sub * EPL + e] = acc[g][e] * inv;
+                }
             }
-        }
-        __syncthreads();
-        const size_t slot = (size_t)blockIdx.x + u;
-        for (int i = threadIdx.x; i < G * D; i += kAttnThreads) {
-            const int g = i / D, e = i % D;
-            float mm = s_m[0][g];
+        } else {
+            const size_t slot = (size_t)wid + u;
+            if (lane < LPT) {
 #pragma unroll
-            for (int w = 1; w < kAttnWaves; w++) mm = fmaxf(mm, s_m[w][g]);
-            const float ms = mm == -INFINITY ? 0.f : mm;
-            float ll = 0.f, aa = 0.f;
+                for (int g = 0; g < G; g++) {
 #pragma unroll
-            for (int w = 0; w < kAttnWaves; w++) {
-                const float c = __builtin_amdgcn_exp2f(s_m[w][g] - ms);
-                ll += s_l[w][g] * c;
-                aa += s_acc[w][g][e] * c;
+                    for (int e = 0; e < EPL; e++) st_coherent(&a.part_acc[(slot * G + g) * D + sub * EPL + e], acc[g][e]);
+                    if (sub == 0) {
+                        st_coherent(&a.part_ml[(slot * G + g) * 2], m[g]);
+                        st_coherent(&a.part_ml[(slot * G + g) * 2 + 1], l[g]);
+                    }
+                }
             }
-            a.part_acc[(slot * G + g) * D + e] = aa;
-            if (e == 0) {
-                a.part_ml[(slot * G + g) * 2] = mm;
-                a.part_ml[(slot * G + g) * 2 + 1] = ll;
+            // the partial must have reached device-coherent memory before the count moves
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            int prev = 0;
+            if (lane == 0) prev = __hip_atomic_fetch_add(&a.counters[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            prev = __builtin_amdgcn_readfirstlane(prev);
+            if (prev == w_last - w_first) {  // every other wave of this unit is done: fold
+                constexpr int OPL = G * D / 64;  // outputs per lane, all of one head
+                const int g = (lane * OPL) / D, e0 = (lane * OPL) % D;
+                float Mx = -INFINITY, Ls = 0.f, A[OPL];
+#pragma unroll
+                for (int e = 0; e < OPL; e++) A[e] = 0.f;
+                // the partials sit in device-coherent memory, one round trip away: ask for
+                // several of them before folding any
+                constexpr int MB = (OPL <= 8) ? 8 : 4;
+                for (int w0 = w_first; w0 <= w_last; w0 += MB) {
+                    float mv[MB], lv[MB], av[MB][OPL];
+#pragma unroll
+                    for (int i = 0; i < MB; i++) {
+                        const size_t sl = ((size_t)min(w0 + i, w_last) + u) * G + g;
+                        mv[i] = ld_coherent(&a.part_ml[sl * 2]);
+                        lv[i] = ld_coherent(&a.part_ml[sl * 2 + 1]);
+#pragma unroll
+                        for (int e = 0; e < OPL; e++) av[i][e] = ld_coherent(&a.part_acc[sl * D + e0 + e]);
+                    }
+#pragma unroll
+                    for (int i = 0; i < MB; i++) {
+                        if (w0 + i <= w_last) {
+                            const float mn = fmaxf(Mx, mv[i]);
+                            const float ms = mn == -INFINITY ? 0.f : mn;
+                            const float ca = __builtin_amdgcn_exp2f(Mx - ms), cb = __builtin_amdgcn_exp2f(mv[i] - ms);
+                            Ls = Ls * ca + lv[i] * cb;
+#pragma unroll
+                            for (int e = 0; e < OPL; e++) A[e] = A[e] * ca + av[i][e] * cb;
+                            Mx = mn;
+                        }
+                    }
+                }
+                const float inv = 1.0f / Ls;
+#pragma unroll
+                for (int e = 0; e < OPL; e++) o[g * D + e0 + e] = A[e] * inv;
+                if (lane == 0) __hip_atomic_store(&a.counters[u], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
 }
 
-// One block per unit: fold the partials of the blocks that overlapped it.
-template <int D, int G>
-__global__ __launch_bounds__(256) void attend_merge_kernel(View pv, AttendArgs a, int grid_main) {
-    const int u = blockIdx.x;
-    const int n_units = a.n_seqs * pv.Hkv;
-    const int total = a.tile_start[n_units];
-    const int ts0 = a.tile_start[u], ts1 = a.tile_start[u + 1];
-    const int b = u / pv.Hkv, h = u % pv.Hkv;
-    float *o = a.out + ((size_t)b * pv.Hq + (size_t)h * G) * D;
-    if (ts1 <= ts0) {  // nothing cached for this unit
-        for (int i = threadIdx.x; i < G * D; i += 256) o[i] = 0.f;
-        return;
+// Blocks of one instantiation that fit on a compute unit at the same time.  The
+// launch uses exactly (compute units x that many) blocks: with an even split of the
+// tiles a second, partly filled round of blocks would double the run time.
+template <int DT, int D, int GG>
+static int resident_blocks_per_cu() {
+    static int cached = 0;
+    if (cached == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attend_decode_kernel<DT, D, GG>, kAttnThreads, 0) != hipSuccess || n < 1)
+            n = 1;
+        cached = n;
     }
-    const int tpb = max(a.min_tpb, (total + grid_main - 1) / grid_main);
-    const int b0 = ts0 / tpb, b1 = (ts1 - 1) / tpb;
-    for (int i = threadIdx.x; i < G * D; i += 256) {
-        const int g = i / D, e = i % D;
-        float mm = -INFINITY;
-        for (int bb = b0; bb <= b1; bb++) mm = fmaxf(mm, a.part_ml[((size_t)(bb + u) * G + g) * 2]);
-        const float ms = mm == -INFINITY ? 0.f : mm;
-        float ll = 0.f, aa = 0.f;
-        for (int bb = b0; bb <= b1; bb++) {
-            const size_t s = (size_t)(bb + u) * G + g;
-            const float c = __builtin_amdgcn_exp2f(a.part_ml[s * 2] - ms);
-            ll += a.part_ml[s * 2 + 1] * c;
-            aa += a.part_acc[s * D + e] * c;
-        }
-        o[i] = aa / ll;
-    }
+    return cached;
 }
 
 template <int DT, int D>
-static hipError_t launch_g(const View &pv, const AttendArgs &a, int grid, hipStream_t st,
+static hipError_t launch_g(const View &pv, const AttendArgs &a, int n_cu, int grid_max, hipStream_t st,
                            hipEvent_t ev0, hipEvent_t ev1) {
-    const int n_units = a.n_seqs * pv.Hkv;
-    if (ev0) (void)hipEventRecord(ev0, st);
+    int grid = 0;
     switch (pv.G) {
 #define WGKV_CASE(GG)                                                                              \
     case GG:                                                                                       \
+        grid = n_cu * resident_blocks_per_cu<DT, D, GG>();                                         \
+        if (grid > grid_max) grid = grid_max;                                                      \
+        if (ev0) (void)hipEventRecord(ev0, st);                                                    \
         hipLaunchKernelGGL((attend_decode_kernel<DT, D, GG>), dim3(grid), dim3(kAttnThreads), 0, st, pv, a); \
-        if (ev1) (void)hipEventRecord(ev1, st);                                                    \
-        hipLaunchKernelGGL((attend_merge_kernel<D, GG>), dim3(n_units), dim3(256), 0, st, pv, a, grid);   \
         break;
         WGKV_CASE(1)
         WGKV_CASE(2)
@@ -336,43 +596,42 @@ static hipError_t launch_g(const View &pv, const AttendArgs &a, int grid, hipStr
 #undef WGKV_CASE
         default: return hipErrorInvalidValue;
     }
+    if (ev1) (void)hipEventRecord(ev1, st);
     return hipGetLastError();
 }
 
-// workspace bytes for a decode attend with this grid
-size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid) {
-    const size_t n_units = (size_t)n_seqs * pv.Hkv, slots = grid + n_units;
-    size_t b = (n_units + 1) * sizeof(int32_t);
-    b = (b + 255) & ~(size_t)255;
-    b += slots * pv.G * 2 * sizeof(float);
+// workspace bytes for a decode attend launched with at most grid_max blocks
+size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid_max) {
+    const size_t n_units = (size_t)n_seqs * pv.Hkv, slots = (size_t)grid_max * kAttnWaves + n_units;
+    size_t b = slots * pv.G * 2 * sizeof(float);
     b = (b + 255) & ~(size_t)255;
     b += slots * pv.G * pv.d * sizeof(float);
     return b;
 }
 
 hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int32_t *sids,
-                                const void *q, float scale, float *out, void *ws, int grid,
-                                int min_tpb, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+                                const void *q, float scale, float *out, void *ws, int32_t *counters,
+                                int n_cu, int grid_max, int min_tpw, hipStream_t st, hipEvent_t ev0,
+                                hipEvent_t ev1) {
     AttendArgs a;
     a.layer = layer;
     a.n_seqs = n_seqs;
-    a.min_tpb = min_tpb;
+    a.min_tpw = min_tpw;
     a.scale_log2e = scale * 1.4426950408889634f;
     a.q = (const char *)q;
     a.out = out;
-    const size_t n_units = (size_t)n_seqs * pv.Hkv, slots = grid + n_units;
+    a.counters = counters;
+    // the partial slots are laid out for the largest grid any instantiation may use
+    const size_t n_units = (size_t)n_seqs * pv.Hkv, slots = (size_t)grid_max * kAttnWaves + n_units;
     char *w = (char *)ws;
-    a.tile_start = (int32_t *)w;
-    size_t off = ((n_units + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
-    a.part_ml = (float *)(w + off);
-    off += slots * pv.G * 2 * sizeof(float);
-    off = (off + 255) & ~(size_t)255;
+    a.part_ml = (float *)w;
+    size_t off = (slots * pv.G * 2 * sizeof(float) + 255) & ~(size_t)255;
     a.part_acc = (float *)(w + off);
     for (int i = 0; i < n_seqs; i++) a.sid[i] = sids[i];
-    if (pv.dtype == WGKV_BF16 && pv.d == 128) return launch_g<WGKV_BF16, 128>(pv, a, grid, st, ev0, ev1);
-    if (pv.dtype == WGKV_BF16 && pv.d == 64) return launch_g<WGKV_BF16, 64>(pv, a, grid, st, ev0, ev1);
-    if (pv.dtype == WGKV_F32 && pv.d == 128) return launch_g<WGKV_F32, 128>(pv, a, grid, st, ev0, ev1);
-    if (pv.dtype == WGKV_F32 && pv.d == 64) return launch_g<WGKV_F32, 64>(pv, a, grid, st, ev0, ev1);
+    if (pv.dtype == WGKV_BF16 && pv.d == 128) return launch_g<WGKV_BF16, 128>(pv, a, n_cu, grid_max, st, ev0, ev1);
+    if (pv.dtype == WGKV_BF16 && pv.d == 64) return launch_g<WGKV_BF16, 64>(pv, a, n_cu, grid_max, st, ev0, ev1);
+    if (pv.dtype == WGKV_F32 && pv.d == 128) return launch_g<WGKV_F32, 128>(pv, a, n_cu, grid_max, st, ev0, ev1);
+    if (pv.dtype == WGKV_F32 && pv.d == 64) return launch_g<WGKV_F32, 64>(pv, a, n_cu, grid_max, st, ev0, ev1);
     return hipErrorInvalidValue;
 }
 

@@ -22,8 +22,9 @@ hipError_t launch_decode_step(const View &pv, const CallSeqs &cs, int layer, flo
 hipError_t launch_free_seq(const View &pv, int sid, hipStream_t st);
 size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid);
 hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int32_t *sids,
-                                const void *q, float scale, float *out, void *ws, int grid,
-                                int min_tpb, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
+                                const void *q, float scale, float *out, void *ws, int32_t *counters,
+                                int n_cu, int grid_max, int min_tpb, hipStream_t st, hipEvent_t ev0,
+                                hipEvent_t ev1);
 hipError_t launch_gate_linear(int dtype, int64_t n_tokens, int hidden_dim, int n_kv_heads,
                               const void *hidden, const void *w, float *g_out, hipStream_t st);
 size_t attend_prefill_ws_bytes(const View &pv, int n_seqs, int64_t total_q);
@@ -37,9 +38,8 @@ using namespace wgkv;
 namespace {
 
 constexpr int kPrefillBlkHost = 1024;   // must match kPrefillBlk in admit.hip
-constexpr int kAttnGridMax = 4096;      // upper bound on the decode-attention grid
-constexpr int kAttnBlocksPerCu = 4;
-constexpr int kAttnMinTilesPerBlock = 8;
+constexpr int kAttnGridMax = 2048;      // upper bound on the decode-attention grid (blocks of 4 waves)
+constexpr int kAttnMinTilesPerWave = 4;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -72,6 +72,7 @@ void make_layout(const wgkv_config *c, wgkv_meta_layout *o) {
     o->free_stack = off; off = align256(off + (size_t)c->n_pages * 4);
     o->free_top = off;   off = align256(off + 4);
     o->err_flag = off;   off = align256(off + 4);
+    o->unit_counters = off; off = align256(off + (size_t)WGKV_MAX_CALL_UNITS * 4);
     o->total_bytes = off;
     o->n_local_pages = (int32_t)nlp;
 }
@@ -101,6 +102,7 @@ View make_view(const wgkv_config *c, void *pool, void *meta) {
     v.free_stack = (int32_t *)(m + lay.free_stack);
     v.free_top = (int32_t *)(m + lay.free_top);
     v.err_flag = (int32_t *)(m + lay.err_flag);
+    v.unit_counters = (int32_t *)(m + lay.unit_counters);
     return v;
 }
 
@@ -129,7 +131,7 @@ struct wgkv_pool {
     std::vector<uint8_t> touched_h;  // [S][L] local pages handed out
     std::vector<int32_t> g_ub;       // [S][L][H] upper bound of the global length
     int64_t pages_ub;                // upper bound of pages in use
-    int attn_grid;
+    int n_cu;                        // compute units of the device
     hipEvent_t ev0, ev1;
 };
 
@@ -193,9 +195,7 @@ int wgkv_init_pool(const wgkv_config *cfg, void *pool_dev, size_t pool_bytes, vo
     p->touched_h.assign(n_sl, 0);
     p->g_ub.assign(n_sl * cfg->n_kv_heads, 0);
     p->pages_ub = 0;
-    p->attn_grid = prop.multiProcessorCount * kAttnBlocksPerCu;
-    if (p->attn_grid > kAttnGridMax) p->attn_grid = kAttnGridMax;
-    if (p->attn_grid < 1) p->attn_grid = 1;
+    p->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
     p->ev0 = p->ev1 = nullptr;
     if (launch_init(v, (hipStream_t)stream) != hipSuccess) {
         delete p;
@@ -379,10 +379,10 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
     if (!prefill) {
         for (int b = 0; b < n_seqs; b++)
             if (n_q_host[b] != 1) return WGKV_ERR_INVALID_ARG;
-        if (workspace_bytes < attend_decode_ws_bytes(p->view, n_seqs, p->attn_grid)) return WGKV_ERR_WORKSPACE;
+        if (workspace_bytes < attend_decode_ws_bytes(p->view, n_seqs, kAttnGridMax)) return WGKV_ERR_WORKSPACE;
         return launch_attend_decode(p->view, layer, n_seqs, seq_ids_host, q_dev, scale, out_dev,
-                                    workspace_dev, p->attn_grid, kAttnMinTilesPerBlock, st, p->ev0,
-                                    p->ev1) == hipSuccess
+                                    workspace_dev, p->view.unit_counters, p->n_cu, kAttnGridMax,
+                                    kAttnMinTilesPerWave, st, p->ev0, p->ev1) == hipSuccess
                    ? WGKV_OK
                    : WGKV_ERR_HIP;
     }

@@ -23,6 +23,7 @@ struct View {
     int32_t *seq_len, *global_len, *local_pt, *global_pt;
     float *ring_g;
     int32_t *free_stack, *free_top, *err_flag;
+    int32_t *unit_counters;              // [kMaxCallUnits], zero between calls
 };
 
 // The sequences of one call, passed by value in the kernel arguments.
@@ -58,6 +59,10 @@ constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
 constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8 lanes
 constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16 lanes
+constexpr int kDppShl4 = 0x104;       // lane i reads lane i+4 of its row of 16
+constexpr int kDppShr4 = 0x114;       // lane i reads lane i-4
+constexpr int kDppRor4 = 0x124;       // rotate the row of 16 by 4
+constexpr int kDppRor8 = 0x128;       // rotate by 8: lane i <-> i^8
 
 // Sum over aligned groups of N consecutive lanes; every lane of the group gets the total.
 template <int N>
