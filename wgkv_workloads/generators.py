@@ -61,13 +61,25 @@ def score_shape_b(rate: np.ndarray, tau: float) -> np.ndarray:
 
 
 def draw_scores(cfg: WorkloadConfig, seq: int, layer: int, n_tokens: int, rates: np.ndarray,
-                purpose: str = "scores", step: int = 0) -> np.ndarray:
-    """fp32 scores [n_tokens, n_kv_heads] of one (sequence, layer)."""
-    r = _rng(cfg, purpose, seq, layer, step)
-    u = r.random(size=(n_tokens, cfg.n_kv_heads), dtype=np.float64)
-    b = score_shape_b(rates[layer], cfg.tau)[None, :]
-    g = 1.0 - np.power(1.0 - u, 1.0 / b)
-    return np.ascontiguousarray(np.clip(g, 0.0, 1.0).astype(np.float32))
+                purpose: str = "scores", step: int = 0, device=None):
+    """fp32 scores [n_tokens, n_kv_heads] of one (sequence, layer).
+
+    device=None: numpy Philox stream, returns a numpy array.  With a torch device the
+    uniforms come from a torch generator seeded with the same key and a torch tensor
+    on that device is returned (a different but equally reproducible stream; whoever
+    needs the scores on both sides copies these bytes)."""
+    b = score_shape_b(rates[layer], cfg.tau)
+    if device is None:
+        r = _rng(cfg, purpose, seq, layer, step)
+        u = r.random(size=(n_tokens, cfg.n_kv_heads), dtype=np.float64)
+        g = 1.0 - np.power(1.0 - u, 1.0 / b[None, :])
+        return np.ascontiguousarray(np.clip(g, 0.0, 1.0).astype(np.float32))
+    gen = torch.Generator(device=device)
+    gen.manual_seed(_torch_seed(cfg, purpose, seq, layer, step))
+    u = torch.rand((n_tokens, cfg.n_kv_heads), generator=gen, device=device, dtype=torch.float64)
+    inv_b = torch.as_tensor(1.0 / b, dtype=torch.float64, device=device)[None, :]
+    g = 1.0 - torch.pow(1.0 - u, inv_b)
+    return g.clamp_(0.0, 1.0).to(torch.float32).contiguous()
 
 
 def torch_dtype(cfg: WorkloadConfig):
