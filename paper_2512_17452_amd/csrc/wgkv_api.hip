@@ -386,6 +386,8 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
                    ? WGKV_OK
                    : WGKV_ERR_HIP;
     }
+    // the matrix-core path is built for the shape of the paper's models
+    if (p->cfg.dtype != WGKV_BF16 || p->cfg.head_dim != 128 || p->view.G != 4) return WGKV_ERR_INVALID_ARG;
     CallSeqs cs;
     memset(&cs, 0, sizeof(cs));
     cs.n = n_seqs;

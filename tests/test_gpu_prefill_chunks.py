@@ -1,0 +1,162 @@
+"""Chunked prefill: linear write gate, attention of chunk queries under the
+vertical-slash mask (matrix-core kernel) and admission of the chunk, against the
+definition oracle on the dense history.  Every call goes through the C ABI."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_17452_amd as wg
+import wgkv_workloads as wl
+from oracle import Oracle, OracleConfig, attend_definition, linear_gate
+
+pytestmark = pytest.mark.gpu
+SCALE = float(os.environ.get("WGKV_TEST_SCALE", "1.0"))
+MAX_ABS_TOL, MEAN_ABS_TOL = 1e-2, 1e-3
+GATE_TOL = 1e-4       # fp32 accumulation of bf16 products vs fp64
+GUARD = 1e-3          # |logit - logit(tau)| below which the fp32 and fp64 decisions may differ
+
+
+@pytest.mark.parametrize("dtype,T,dim,Hk", [(torch.bfloat16, 1000, 4096, 8), (torch.bfloat16, 7, 64, 2),
+                                            (torch.float32, 129, 512, 8), (torch.bfloat16, 4096, 4096, 8),
+                                            (torch.bfloat16, 33, 2056, 12)])
+def test_gate_scores_match_fp64(dtype, T, dim, Hk):
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cpu").manual_seed(T * 131 + dim)
+    hidden = torch.randn((T, dim), generator=gen).to(dtype)
+    w = (0.02 * torch.randn((Hk, dim), generator=gen)).to(dtype)
+    g = wg.gate_scores(hidden.to(dev), w.to(dev)).cpu().numpy()
+    logit, ref = linear_gate(hidden.float().numpy(), w.float().numpy())
+    assert np.abs(g - ref).max() <= GATE_TOL
+    # decisions at tau = 0.5 (logit 0) agree with fp64 wherever the logit is not within the guard band
+    far = np.abs(logit) > GUARD
+    assert np.array_equal((g >= 0.5)[far], (ref >= 0.5)[far])
+
+
+def _flow(B, lens, chunk, W, P, hidden_dim, seed, tau=0.5, use_gate=True, check_rows=None):
+    """Feeds B sequences chunk by chunk: gate -> attend(prefill form) -> prefill_admit."""
+    Hq, Hk, d = 32, 8, 128
+    dev = torch.device("cuda:0")
+    max_len = max(lens)
+    max_gp = max_len // P + 4
+    n_pages = B * Hk * (max_gp + W // P + 1) + 64
+    pool = wg.Pool(wg.Config(1, Hq, Hk, d, wg.BF16, P, W, B, max_gp, n_pages), B, B * chunk)
+    orc = Oracle(OracleConfig(1, Hq, Hk, d, P, W, B, max_gp, n_pages, True))
+    gen = torch.Generator(device="cpu").manual_seed(seed)
+    w = (0.02 * torch.randn((Hk, hidden_dim), generator=gen)).to(torch.bfloat16)
+    hist = {s: [np.zeros((0, Hk, d), np.float32), np.zeros((0, Hk, d), np.float32), np.zeros((0, Hk), np.float32)]
+            for s in range(B)}
+    scale = 1.0 / math.sqrt(d)
+    done = [0] * B
+    worst = [0.0, 0.0]
+    near = 0
+    while any(done[s] < lens[s] for s in range(B)):
+        seqs = [s for s in range(B) if done[s] < lens[s]]
+        nt = [min(chunk, lens[s] - done[s]) for s in seqs]
+        tot = sum(nt)
+        q = torch.randn((tot, Hq, d), generator=gen).to(torch.bfloat16)
+        k = torch.randn((tot, Hk, d), generator=gen).to(torch.bfloat16)
+        v = torch.randn((tot, Hk, d), generator=gen).to(torch.bfloat16)
+        if use_gate:
+            hidden = torch.randn((tot, hidden_dim), generator=gen).to(torch.bfloat16)
+            g_dev = wg.gate_scores(hidden.to(dev), w.to(dev))
+            logit, gref = linear_gate(hidden.float().numpy(), w.float().numpy())
+            g = g_dev.cpu().numpy()
+            assert np.abs(g - gref).max() <= GATE_TOL
+            far = np.abs(logit) > GUARD
+            near += int((~far).sum())
+            assert np.array_equal((g >= tau)[far], (gref >= tau)[far])
+        else:
+            g = torch.rand((tot, Hk), generator=gen).numpy().astype(np.float32)
+            g_dev = torch.from_numpy(g).to(dev)
+        out = torch.full((tot, Hq, d), float("nan"), dtype=torch.float32, device=dev)
+        kd, vd = k.to(dev), v.to(dev)
+        pool.attend(0, seqs, q.to(dev), out, scale, n_q=nt, k_chunk=kd, v_chunk=vd, g_chunk=g_dev, tau=tau)
+        mask = torch.zeros((tot, Hk), dtype=torch.uint8, device=dev)
+        pool.prefill_admit(0, seqs, nt, kd, vd, g_dev, tau=tau, admit_mask_out=mask)
+        # both sides decide on the same fp32 scores (the kernel's)
+        admit, _ = orc.push_tokens(0, seqs, nt, k.float().numpy(), v.float().numpy(), g, tau)
+        assert np.array_equal(mask.cpu().numpy(), admit)
+        o = out.cpu().numpy()
+        base = 0
+        for s, n in zip(seqs, nt):
+            h = hist[s]
+            h[0] = np.concatenate([h[0], k[base:base + n].float().numpy()])
+            h[1] = np.concatenate([h[1], v[base:base + n].float().numpy()])
+            h[2] = np.concatenate([h[2], g[base:base + n]])
+            rows = np.arange(n) if check_rows is None else np.unique(np.concatenate(
+                [[0, n - 1], np.random.default_rng(seed + done[s]).integers(0, n, check_rows)]))
+            ref = attend_definition(h[0], h[1], h[2], q[base:base + n].float().numpy()[rows], done[s] + rows, W, tau, scale)
+            err = np.abs(o[base:base + n][rows].astype(np.float64) - ref)
+            assert np.isfinite(o[base:base + n]).all()
+            assert err.max() <= MAX_ABS_TOL and err.mean() <= MEAN_ABS_TOL, (s, done[s], err.max(), err.mean())
+            worst = [max(worst[0], err.max()), max(worst[1], err.mean())]
+            done[s] += n
+            base += n
+    # final state against the mechanism oracle
+    free, flag = pool.status()
+    assert flag == 0 and free == orc.free_top
+    m = {kk: vv.cpu().numpy() for kk, vv in pool.meta().items()}
+    for s in range(B):
+        assert int(m["seq_len"][s, 0]) == lens[s]
+        for hh in range(Hk):
+            lp, gp, rg, _ = orc.head_tables(s, 0, hh)
+            assert int(m["global_len"][s, 0, hh]) == orc.global_len(s, 0, hh)
+            assert np.array_equal(m["global_pt"][s, 0, hh], gp) and np.array_equal(m["local_pt"][s, 0, hh], lp)
+            assert np.array_equal(m["ring_g"][s, 0, hh].view(np.uint32), rg.view(np.uint32))
+    return pool, orc, worst, near
+
+
+@pytest.mark.parametrize("chunk,W,P", [(384, 256, 16), (64, 32, 16), (100, 256, 32), (1, 16, 16), (257, 64, 16)])
+def test_chunked_prefill_every_row(chunk, W, P):
+    lens = [min(1536, 12 * chunk + 5), min(900, 7 * chunk)] if chunk > 1 else [70, 33]
+    _, _, worst, near = _flow(2, lens, chunk, W, P, hidden_dim=256, seed=1000 + chunk)
+    print(f"chunk {chunk} W {W} P {P}: max abs err {worst[0]:.2e}, mean {worst[1]:.2e}, {near} scores in the guard band", flush=True)
+
+
+def test_given_scores_admit_all_and_none():
+    for tau in (0.0, 2.0):  # dense causal attention / pure sliding window
+        _flow(1, [700], 256, 64, 16, hidden_dim=64, seed=5, tau=tau, use_gate=False)
+
+
+def test_chunk_of_one_equals_decode_order():
+    """A one-token chunk through attend-then-admit gives what decode_step-then-attend gives."""
+    Hq, Hk, d, W, P = 32, 8, 128, 32, 16
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cpu").manual_seed(3)
+    pools = [wg.Pool(wg.Config(1, Hq, Hk, d, wg.BF16, P, W, 1, 32, 600), 1, 256) for _ in range(2)]
+    k = torch.randn((200, Hk, d), generator=gen).to(torch.bfloat16).to(dev)
+    v = torch.randn((200, Hk, d), generator=gen).to(torch.bfloat16).to(dev)
+    g = torch.rand((200, Hk), generator=gen).to(dev)
+    for p in pools:
+        p.prefill_admit(0, [0], [200], k, v, g, tau=0.5)
+    scale = 1 / math.sqrt(d)
+    for step in range(40):
+        k1 = torch.randn((1, Hk, d), generator=gen).to(torch.bfloat16).to(dev)
+        v1 = torch.randn((1, Hk, d), generator=gen).to(torch.bfloat16).to(dev)
+        q1 = torch.randn((1, Hq, d), generator=gen).to(torch.bfloat16).to(dev)
+        g1 = torch.rand((1, Hk), generator=gen).to(dev)
+        oa = torch.empty((1, Hq, d), dtype=torch.float32, device=dev)
+        ob = torch.empty((1, Hq, d), dtype=torch.float32, device=dev)
+        pools[0].attend(0, [0], q1, oa, scale, n_q=[1], k_chunk=k1, v_chunk=v1, g_chunk=g1, tau=0.5)
+        pools[0].prefill_admit(0, [0], [1], k1, v1, g1, tau=0.5)
+        pools[1].decode_step(0, [0], k1, v1, g1, tau=0.5)
+        pools[1].attend(0, [0], q1, ob, scale)
+        assert (oa - ob).abs().max().item() < 2e-3
+    ma, mb = pools[0].meta(), pools[1].meta()
+    for name in ("seq_len", "global_len", "global_pt", "local_pt", "ring_g", "free_top"):
+        assert torch.equal(ma[name], mb[name]), name
+
+
+def test_prefill_form_rejects_unsupported_shapes():
+    pool = wg.Pool(wg.Config(1, 8, 2, 64, wg.F32, 16, 32, 1, 8, 64), 1, 64)
+    dev = torch.device("cuda:0")
+    q = torch.zeros((4, 8, 64), device=dev)
+    kv = torch.zeros((4, 2, 64), device=dev)
+    g = torch.zeros((4, 2), device=dev)
+    out = torch.zeros((4, 8, 64), device=dev)
+    with pytest.raises(wg.WgkvError) as e:
+        pool.attend(0, [0], q, out, 0.125, n_q=[4], k_chunk=kv, v_chunk=kv, g_chunk=g)
+    assert e.value.code == -1
