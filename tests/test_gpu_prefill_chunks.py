@@ -160,3 +160,78 @@ def test_prefill_form_rejects_unsupported_shapes():
     with pytest.raises(wg.WgkvError) as e:
         pool.attend(0, [0], q, out, 0.125, n_q=[4], k_chunk=kv, v_chunk=kv, g_chunk=g)
     assert e.value.code == -1
+
+
+def test_llama8b_chunked_prefill_128k_with_gate():
+    """Workload 5: batch 4, 128K tokens in 4K chunks, scores from the random-init linear gate.
+    Admission is compared for every token; gate scores and attention on seeded samples."""
+    cfg = wl.get_config(4)
+    B, Hq, Hk, d, W, P = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local, cfg.page_size
+    N = max(int(cfg.ctx_max * SCALE) // cfg.chunk * cfg.chunk, 2 * cfg.chunk)
+    C, dim = cfg.chunk, cfg.hidden_dim
+    n_chunks = N // C
+    dev = torch.device("cuda:0")
+    max_gp = N // P + 2
+    n_pages = B * Hk * (max_gp + W // P) + 64            # worst case: everything admitted
+    pool = wg.Pool(wg.Config(1, Hq, Hk, d, wg.BF16, P, W, B, max_gp, n_pages), B, B * C)
+    orc = Oracle(OracleConfig(1, Hq, Hk, d, P, W, B, max_gp, n_pages, False))
+    gate_w = wl.draw_linear_gate(cfg, device=dev)
+    gate_w_host = gate_w.float().cpu().numpy()
+    watch = 1                                              # the sequence whose dense history is kept
+    K = np.empty((N, Hk, d), np.float32); V = np.empty((N, Hk, d), np.float32); Gs = np.empty((N, Hk), np.float32)
+    seqs, nt = list(range(B)), [C] * B
+    scale = 1.0 / math.sqrt(d)
+    out = torch.empty((B * C, Hq, d), dtype=torch.float32, device=dev)
+    mask = torch.empty((B * C, Hk), dtype=torch.uint8, device=dev)
+    check_chunks = {0, 1, n_chunks // 2, n_chunks - 1}
+    rng = np.random.default_rng(cfg.seed)
+    admitted = 0
+    worst = [0.0, 0.0]
+    for c in range(n_chunks):
+        hidden = wl.draw_normal(cfg, "hidden", (B * C, dim), device=dev, key=(c,))
+        k = wl.draw_normal(cfg, "k", (B * C, Hk, d), device=dev, key=(c,))
+        v = wl.draw_normal(cfg, "v", (B * C, Hk, d), device=dev, key=(c,))
+        q = wl.draw_normal(cfg, "q", (B * C, Hq, d), device=dev, key=(c,))
+        g = wg.gate_scores(hidden, gate_w)
+        pool.attend(0, seqs, q, out, scale, n_q=nt, k_chunk=k, v_chunk=v, g_chunk=g, tau=cfg.tau)
+        pool.prefill_admit(0, seqs, nt, k, v, g, tau=cfg.tau, admit_mask_out=mask)
+        gh = g.cpu().numpy()
+        admit, _ = orc.push_tokens(0, seqs, nt, None, None, gh, cfg.tau)   # decisions on the kernel's fp32 scores
+        assert np.array_equal(mask.cpu().numpy(), admit), c
+        admitted += int(admit.sum())
+        # gate: sampled rows against fp64
+        rows = rng.integers(0, B * C, 512)
+        logit, gref = linear_gate(hidden[rows].float().cpu().numpy(), gate_w_host)
+        assert np.abs(gh[rows] - gref).max() <= GATE_TOL
+        far = np.abs(logit) > GUARD
+        assert np.array_equal((gh[rows] >= cfg.tau)[far], (gref >= cfg.tau)[far])
+        sl = slice(watch * C, (watch + 1) * C)
+        K[c * C:(c + 1) * C] = k[sl].float().cpu().numpy()
+        V[c * C:(c + 1) * C] = v[sl].float().cpu().numpy()
+        Gs[c * C:(c + 1) * C] = gh[sl]
+        if c in check_chunks:
+            r = np.unique(np.concatenate([[0, C - 1], rng.integers(0, C, 64)]))
+            n_hist = (c + 1) * C
+            ref = attend_definition(K[:n_hist], V[:n_hist], Gs[:n_hist], q[sl][r].float().cpu().numpy(), c * C + r,
+                                    W, cfg.tau, scale)
+            o = out[sl][r].cpu().numpy().astype(np.float64)
+            err = np.abs(o - ref)
+            assert np.isfinite(o).all() and err.max() <= MAX_ABS_TOL and err.mean() <= MEAN_ABS_TOL, (c, err.max(), err.mean())
+            worst = [max(worst[0], err.max()), max(worst[1], err.mean())]
+            free, flag = pool.status()
+            assert flag == 0 and free == orc.free_top
+            print(f"[workload 5] chunk {c}/{n_chunks}: {len(r)} sampled rows ok, free pages {free}", flush=True)
+    rate = admitted / (N * B * Hk)
+    assert 0.4 < rate < 0.6                               # sigma(w.x) with w ~ N(0, 0.02): about half admitted
+    free, flag = pool.status()
+    assert flag == 0 and free == orc.free_top
+    m = {kk: vv.cpu().numpy() for kk, vv in pool.meta().items()}
+    for s in range(B):
+        assert int(m["seq_len"][s, 0]) == N
+        for hh in range(Hk):
+            lp, gp, rg, _ = orc.head_tables(s, 0, hh)
+            assert int(m["global_len"][s, 0, hh]) == orc.global_len(s, 0, hh)
+            assert np.array_equal(m["global_pt"][s, 0, hh], gp) and np.array_equal(m["local_pt"][s, 0, hh], lp)
+            assert np.array_equal(m["ring_g"][s, 0, hh].view(np.uint32), rg.view(np.uint32))
+    print(f"[workload 5] N={N}: admission rate {rate:.3f}, attention max abs err {worst[0]:.2e}, "
+          f"worst mean {worst[1]:.2e}", flush=True)
