@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the per-kernel HIP events (roofline.achieved becomes null)")
     ap.add_argument("--ctx-scale", type=float, default=1.0, help="shrink contexts (debugging only)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -188,12 +190,19 @@ def main():
                          "kernel_avg_us": avg_us, "kernel_p10_us": float(np.percentile(durs, 10) * 1e3),
                          "kernel_p90_us": float(np.percentile(durs, 90) * 1e3), "launches": int(len(durs))})
         events.destroy()
-    traffic_file = os.path.join(ROOT, "profiles", "attend_decode_traffic.json")
+    if args.calibrate_copy:   # known traffic: reads 2^30 bytes, writes 2^30 bytes per launch
+        src = torch.zeros(2 ** 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+    # HBM bytes per launch measured with rocprofv3 counters (see the summary's header for the commands)
+    traffic_file = os.path.join(ROOT, "profiles", f"attend_decode_kernel_{cfg.name}_hbm_traffic.txt")
     if os.path.exists(traffic_file):
-        try:
-            roofline["traffic"] = json.load(open(traffic_file)).get("hbm_bytes_per_launch")
-        except Exception:
-            pass
+        for line in open(traffic_file):
+            if line.startswith("hbm_bytes_per_launch:"):
+                roofline["traffic"] = float(line.split(":")[1])
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

@@ -509,7 +509,8 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
 #pragma unroll
                 for (int g = 0; g < G; g++) {
 #pragma unroll
-                    for (int e = 0; e < EPL; e++) st_coherent(&a.part_acc[(slot * G + g) * D + sub * EPL + e], acc[g][e]);
+                    // stored as [e][sub]: the 16 lanes of one store cover 64 contiguous bytes
+                    for (int e = 0; e < EPL; e++) st_coherent(&a.part_acc[((slot * G + g) * EPL + e) * LPT + sub], acc[g][e]);
                     if (sub == 0) {
                         st_coherent(&a.part_ml[(slot * G + g) * 2], m[g]);
                         st_coherent(&a.part_ml[(slot * G + g) * 2 + 1], l[g]);
@@ -523,6 +524,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
             prev = __builtin_amdgcn_readfirstlane(prev);
             if (prev == w_last - w_first) {  // every other wave of this unit is done: fold
                 constexpr int OPL = G * D / 64;  // outputs per lane, all of one head
+                // lane -> OPL consecutive values of one head in the stored [e][sub] order
                 const int g = (lane * OPL) / D, e0 = (lane * OPL) % D;
                 float Mx = -INFINITY, Ls = 0.f, A[OPL];
 #pragma unroll
@@ -555,7 +557,10 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                 }
                 const float inv = 1.0f / Ls;
 #pragma unroll
-                for (int e = 0; e < OPL; e++) o[g * D + e0 + e] = A[e] * inv;
+                for (int e = 0; e < OPL; e++) {
+                    const int r = e0 + e;  // position in the stored order: r = e_idx * LPT + sub
+                    o[g * D + (r % LPT) * EPL + r / LPT] = A[e] * inv;
+                }
                 if (lane == 0) __hip_atomic_store(&a.counters[u], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
