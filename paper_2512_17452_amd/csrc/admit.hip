@@ -46,6 +46,11 @@ __global__ void init_kernel(View pv) {
     for (size_t i = i0; i < n_u * pv.maxgp; i += stride) pv.global_pt[i] = -1;
     for (size_t i = i0; i < n_u * pv.W; i += stride) pv.ring_g[i] = 0.0f;
     for (size_t i = i0; i < (size_t)kMaxCallUnits; i += stride) pv.unit_counters[i] = 0;
+    // the pool starts as zeros: attention may read rows of a page beyond the last token
+    // written (they get weight zero) and those must be finite
+    uint4 *pool16 = reinterpret_cast<uint4 *>(pv.pool);
+    const size_t n16 = (size_t)pv.n_pages * pv.page_bytes / 16;
+    for (size_t i = i0; i < n16; i += stride) pool16[i] = make_uint4(0u, 0u, 0u, 0u);
     if (i0 == 0) { *pv.free_top = pv.n_pages; *pv.err_flag = 0; }
 }
 
@@ -353,7 +358,7 @@ __global__ __launch_bounds__(256) void free_seq_kernel(View pv, int sid) {
 // ---- host-side launchers (called from the C ABI layer) ----
 
 hipError_t launch_init(const View &pv, hipStream_t st) {
-    hipLaunchKernelGGL(init_kernel, dim3(1024), dim3(256), 0, st, pv);
+    hipLaunchKernelGGL(init_kernel, dim3(4096), dim3(256), 0, st, pv);
     return hipGetLastError();
 }
 

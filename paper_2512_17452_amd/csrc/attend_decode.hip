@@ -186,15 +186,16 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                                         : pv.local_pt + (size_t)um * pv.nlp;
             // A tile inside one page (P >= 16) needs one page id for the whole wave:
             // lane i keeps the page id of tile k0+i and the base address goes through
-            // scalar registers.  Only full tiles take that pipelined path; a partial
-            // last tile, and every tile when pages are smaller than a tile, is handled
-            // one at a time afterwards with a page lookup per row.
+            // scalar registers.  Rows of a partly filled last tile beyond the last token
+            // are read too (finite: the pool is zeroed at start-up and only ever holds K/V
+            // rows) and get weight zero.  With pages smaller than a tile every tile is
+            // handled one at a time with a page lookup per row.
             const bool page_per_tile = pv.logP >= 4;
-            const int n_fast = page_per_tile ? max(0, min(n, count / kTile - k0)) : 0;
+            const int n_fast = page_per_tile ? n : 0;
             int ptreg = 0;
 
-            // Row addresses of full tile j (clamped to the last full tile of the piece: a
-            // tile asked for beyond the end is re-read and never used).  No memory access.
+            // Row addresses of tile j (clamped to the last tile of the piece: a tile asked
+            // for beyond the end is re-read and never used).  No memory access.
             auto tile_rows = [&](int j, const char *(&rowp)[RPT]) {
                 j = min(j, n_fast - 1);
                 const int k = k0 + j;
@@ -449,7 +450,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                     if constexpr (S > 2) process(std::integral_constant<int, 2 % S>{}, std::true_type{}, j + 2);
                     if constexpr (S > 3) process(std::integral_constant<int, 3 % S>{}, std::true_type{}, j + 3);
                 }
-                // the last n_fast % S full tiles are already in their register sets: no more loads
+                // the last n_fast % S tiles are already in their register sets: no more loads
                 if constexpr (S > 1) {
                     if (j < n_fast) process(std::integral_constant<int, 0>{}, std::false_type{}, j);
                     if (j + 1 < n_fast) process(std::integral_constant<int, 1 % S>{}, std::false_type{}, j + 1);
@@ -531,7 +532,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                 for (int e = 0; e < OPL; e++) A[e] = 0.f;
                 // the partials sit in device-coherent memory, one round trip away: ask for
                 // several of them before folding any
-                constexpr int MB = (OPL <= 8) ? 8 : 4;
+                constexpr int MB = (OPL <= 8) ? 16 : 4;
                 for (int w0 = w_first; w0 <= w_last; w0 += MB) {
                     float mv[MB], lv[MB], av[MB][OPL];
 #pragma unroll
