@@ -9,8 +9,9 @@
 // that were neither admitted nor inside the window are gone (Sec. 4.2, "Initial
 // cache population") and are invisible under M_ij anyway.
 //
-// One block owns 64 chunk positions of one (sequence, kv head); its four waves are
-// the four query heads of the group, so a K/V tile staged in LDS feeds all of them.
+// One block owns 64 chunk positions of one (sequence, kv head); its eight waves are
+// (query head of the group) x (row block of 32 positions), so a K/V tile staged in LDS
+// feeds all of them and two waves share each SIMD.
 // Everything is computed transposed, S^T = K Q^T and O^T = V^T P^T with
 // v_mfma_f32_32x32x16_bf16: a lane then owns one query column, so the running max,
 // the denominator and the rescale factor are plain per-lane scalars, and the
@@ -45,7 +46,7 @@ __device__ __forceinline__ uint32_t pf_pack(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, t);
 }
 
-__global__ __launch_bounds__(256) void attend_prefill_kernel(View pv, CallSeqs cs, PrefillAttnArgs a) {
+__global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs cs, PrefillAttnArgs a) {
     __shared__ __attribute__((aligned(16))) char s_k[2][kPfKT * kPfKStride];
     __shared__ __attribute__((aligned(16))) char s_vt[2][kPfD * kPfVStride];
     __shared__ __attribute__((aligned(16))) int s_lo[2][kPfKT];
@@ -57,7 +58,10 @@ __global__ __launch_bounds__(256) void attend_prefill_kernel(View pv, CallSeqs c
     const int sid = cs.sid[b];
     const int um = unit_meta(pv, sid, a.layer, h);
     const int G = 4;
+    // eight waves: wave -> (query head of the group, row block of 32 positions); two waves
+    // share a SIMD, so one can run its softmax while the other keeps the matrix core busy
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int head = wave & 3, rb = wave >> 2;
     const int qn = lane & 31, half = lane >> 5;
     const int gl = pv.global_len[um];
     const int w_eff = min(pv.W, t0);              // ring entries that exist
@@ -66,88 +70,107 @@ __global__ __launch_bounds__(256) void attend_prefill_kernel(View pv, CallSeqs c
     const int n_c = (i_end + kPfKT - 1) / kPfKT;
     const int n_tiles = n_g + n_r + n_c;
 
-    // ---- Q^T operand: this lane's query of each row block, all 8 d-slices of 16 ----
-    pf_bf16x8_t qv[2][8];
-    int qpos[2];
-#pragma unroll
-    for (int rb = 0; rb < 2; rb++) {
-        const int i = min(qt * kPfQ + rb * 32 + qn, T - 1);
-        qpos[rb] = t0 + i;
-        const char *qp = a.q + ((size_t)(base + i) * pv.Hq + (size_t)h * G + wave) * kPfD * 2;
+    // ---- Q^T operand: this lane's query, all 8 d-slices of 16 ----
+    pf_bf16x8_t qv[8];
+    const int qi = min(qt * kPfQ + rb * 32 + qn, T - 1);
+    const int qpos = t0 + qi;
+    {
+        const char *qp = a.q + ((size_t)(base + qi) * pv.Hq + (size_t)h * G + head) * kPfD * 2;
 #pragma unroll
         for (int ks = 0; ks < 8; ks++)
-            qv[rb][ks] = *reinterpret_cast<const pf_bf16x8_t *>(qp + (ks * 16 + half * 8) * 2);
+            qv[ks] = *reinterpret_cast<const pf_bf16x8_t *>(qp + (ks * 16 + half * 8) * 2);
     }
+    pf_f32x16_t o[4];
+    float m = -INFINITY, l = 0.f;
+#pragma unroll
+    for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int c = 0; c < 16; c++) o[db][c] = 0.f;
 
-    pf_f32x16_t o[2][4];
-    float m[2], l[2];
-#pragma unroll
-    for (int rb = 0; rb < 2; rb++) {
-        m[rb] = -INFINITY;
-        l[rb] = 0.f;
-#pragma unroll
-        for (int db = 0; db < 4; db++)
-#pragma unroll
-            for (int c = 0; c < 16; c++) o[rb][db][c] = 0.f;
-    }
-
-    // ---- staging of a key tile: thread -> (key, 16-byte d chunk), two passes ----
-    const int ld_key = threadIdx.x >> 4, ld_dc = threadIdx.x & 15;
-    uint4 kreg[2], vreg[2];
-    int lo_reg[2], hi_reg[2];
+    // ---- staging of a key tile: thread -> (pair of keys 2j, 2j+1; 16-byte d chunk) ----
+    // the two V rows of a pair are interleaved element-wise so that the transposed tile is
+    // written with 32-bit stores
+    const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
+    // threads with ld_sel = 0 carry the K chunk of key 2j and the V chunks of both keys' low
+    // half (d chunk ld_dc, elements 0..3); ld_sel = 1: K of key 2j+1 and elements 4..7
+    const int ld_key = 2 * ld_pair + ld_sel;
+    uint4 kreg;
+    uint2 vreg[2];
+    int lo_reg, hi_reg;
+    // Page ids live in registers, one per lane, so that the address of a key row never
+    // waits for a page-table load: 64 consecutive entries of the global table (reloaded
+    // every 64 pages) and the whole local table when it has at most 64 entries.
+    int pt_base = 0;
+    int ptreg = (lane < pv.maxgp) ? pv.global_pt[(size_t)um * pv.maxgp + lane] : 0;
+    const bool lp_in_reg = pv.nlp <= 64;
+    const int lpreg = (lp_in_reg && lane < pv.nlp) ? pv.local_pt[(size_t)um * pv.nlp + lane] : 0;
+    const int slot0 = t0 > pv.W ? t0 % pv.W : 0;  // ring slot of the oldest position
+    const int64_t v_delta_chunk = a.v - a.k;
     auto fetch = [&](int t) {
+        const char *kp[2];
+        int64_t v_delta;
+        int lo[2] = {INT_MAX, INT_MAX}, hi[2] = {INT_MAX, INT_MAX};  // invisible unless shown otherwise
+        if (t < n_g) {  // global cache: visible to every query
+            if (((t * kPfKT + kPfKT - 1) >> pv.logP) >= pt_base + 64) {
+                pt_base = (t * kPfKT) >> pv.logP;
+                ptreg = (pt_base + lane < pv.maxgp) ? pv.global_pt[(size_t)um * pv.maxgp + pt_base + lane] : 0;
+            }
 #pragma unroll
-        for (int p = 0; p < 2; p++) {
-            const int key = ld_key + 16 * p;
-            const char *kp, *vp;
-            int lo = INT_MAX, hi = INT_MAX;  // invisible unless shown otherwise
-            if (t < n_g) {                   // global cache: visible to every query
-                const int idx = t * kPfKT + key, idc = min(idx, gl - 1);
-                const char *pg = page_ptr(pv, pv.global_pt[(size_t)um * pv.maxgp + (idc >> pv.logP)]) +
-                                 (size_t)(idc & (pv.P - 1)) * (kPfD * 2);
-                kp = pg;
-                vp = pg + pv.v_off;
-                if (idx < gl) lo = INT_MIN;
-            } else if (t < n_g + n_r) {      // ring, oldest position first
-                const int idx = (t - n_g) * kPfKT + key, idc = min(idx, w_eff - 1);
-                const int pos = t0 - w_eff + idc, slot = pos % pv.W;
-                const char *pg = page_ptr(pv, pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)]) +
-                                 (size_t)(slot & (pv.P - 1)) * (kPfD * 2);
-                kp = pg;
-                vp = pg + pv.v_off;
+            for (int e = 0; e < 2; e++) {
+                const int idx = t * kPfKT + 2 * ld_pair + e, idc = min(idx, gl - 1);
+                const int pg = __shfl(ptreg, (idc >> pv.logP) - pt_base);
+                kp[e] = page_ptr(pv, pg) + (size_t)(idc & (pv.P - 1)) * (kPfD * 2);
+                if (idx < gl) lo[e] = INT_MIN;
+            }
+            v_delta = pv.v_off;
+        } else if (t < n_g + n_r) {  // ring, oldest position first
+#pragma unroll
+            for (int e = 0; e < 2; e++) {
+                const int idx = (t - n_g) * kPfKT + 2 * ld_pair + e, idc = min(idx, w_eff - 1);
+                int slot = slot0 + idc;
+                slot = slot >= pv.W ? slot - pv.W : slot;
+                const int pos = t0 - w_eff + idc;
+                const int pg = lp_in_reg ? __shfl(lpreg, slot >> pv.logP)
+                                         : pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)];
+                kp[e] = page_ptr(pv, pg) + (size_t)(slot & (pv.P - 1)) * (kPfD * 2);
                 if (idx < w_eff) {
-                    lo = pos;
-                    hi = (pv.ring_g[(size_t)um * pv.W + slot] >= a.tau) ? INT_MAX : pos + pv.W - 1;
-                }
-            } else {                         // this chunk
-                const int idx = (t - n_g - n_r) * kPfKT + key, idc = min(idx, T - 1);
-                const size_t row = (size_t)(base + idc) * pv.Hkv + h;
-                kp = a.k + row * (kPfD * 2);
-                vp = a.v + row * (kPfD * 2);
-                if (idx < T) {
-                    lo = t0 + idx;
-                    hi = (a.g[row] >= a.tau) ? INT_MAX : t0 + idx + pv.W - 1;
+                    lo[e] = pos;
+                    hi[e] = (pv.ring_g[(size_t)um * pv.W + slot] >= a.tau) ? INT_MAX : pos + pv.W - 1;
                 }
             }
-            kreg[p] = *reinterpret_cast<const uint4 *>(kp + ld_dc * 16);
-            vreg[p] = *reinterpret_cast<const uint4 *>(vp + ld_dc * 16);
-            lo_reg[p] = lo;
-            hi_reg[p] = hi;
+            v_delta = pv.v_off;
+        } else {  // this chunk
+#pragma unroll
+            for (int e = 0; e < 2; e++) {
+                const int idx = (t - n_g - n_r) * kPfKT + 2 * ld_pair + e, idc = min(idx, T - 1);
+                const size_t row = (size_t)(base + idc) * pv.Hkv + h;
+                kp[e] = a.k + row * (kPfD * 2);
+                if (idx < T) {
+                    lo[e] = t0 + idx;
+                    hi[e] = (a.g[row] >= a.tau) ? INT_MAX : t0 + idx + pv.W - 1;
+                }
+            }
+            v_delta = v_delta_chunk;
         }
+        kreg = *reinterpret_cast<const uint4 *>((ld_sel ? kp[1] : kp[0]) + ld_dc * 16);
+        // V: the same 8-byte half chunk of both keys of the pair
+        vreg[0] = *reinterpret_cast<const uint2 *>(kp[0] + v_delta + ld_dc * 16 + ld_sel * 8);
+        vreg[1] = *reinterpret_cast<const uint2 *>(kp[1] + v_delta + ld_dc * 16 + ld_sel * 8);
+        lo_reg = ld_sel ? lo[1] : lo[0];
+        hi_reg = ld_sel ? hi[1] : hi[0];
     };
     auto stage = [&](int buf) {
+        *reinterpret_cast<uint4 *>(&s_k[buf][ld_key * kPfKStride + ld_dc * 16]) = kreg;
+        // transposed V: row d, columns (key 2j, key 2j+1) as one 32-bit word
+        const uint32_t a0[2] = {vreg[0].x, vreg[0].y}, a1[2] = {vreg[1].x, vreg[1].y};
 #pragma unroll
-        for (int p = 0; p < 2; p++) {
-            const int key = ld_key + 16 * p;
-            *reinterpret_cast<uint4 *>(&s_k[buf][key * kPfKStride + ld_dc * 16]) = kreg[p];
-            const uint32_t w[4] = {vreg[p].x, vreg[p].y, vreg[p].z, vreg[p].w};
-#pragma unroll
-            for (int e = 0; e < 8; e++) {  // transposed: [d][key]
-                const unsigned short x = (unsigned short)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
-                *reinterpret_cast<unsigned short *>(&s_vt[buf][(ld_dc * 8 + e) * kPfVStride + key * 2]) = x;
-            }
-            if (ld_dc == 0) { s_lo[buf][key] = lo_reg[p]; s_hi[buf][key] = hi_reg[p]; }
+        for (int e = 0; e < 4; e++) {
+            const uint32_t x0 = (e & 1) ? (a0[e >> 1] >> 16) : (a0[e >> 1] & 0xffffu);
+            const uint32_t x1 = (e & 1) ? (a1[e >> 1] & 0xffff0000u) : (a1[e >> 1] << 16);
+            const int dd = ld_dc * 8 + ld_sel * 4 + e;
+            *reinterpret_cast<uint32_t *>(&s_vt[buf][dd * kPfVStride + ld_pair * 4]) = x0 | x1;
         }
+        if (ld_dc == 0) { s_lo[buf][ld_key] = lo_reg; s_hi[buf][ld_key] = hi_reg; }
     };
 
     fetch(0);
@@ -159,72 +182,66 @@ __global__ __launch_bounds__(256) void attend_prefill_kernel(View pv, CallSeqs c
         if (t + 1 < n_tiles) fetch(t + 1);  // in flight while this tile is multiplied
 
         // ---- S^T = K Q^T : rows = keys of the tile, columns = this wave's queries ----
-        pf_f32x16_t s[2];
+        pf_f32x16_t s;
 #pragma unroll
-        for (int rb = 0; rb < 2; rb++)
-#pragma unroll
-            for (int c = 0; c < 16; c++) s[rb][c] = 0.f;
+        for (int c = 0; c < 16; c++) s[c] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ks++) {
             const pf_bf16x8_t ka =
                 *reinterpret_cast<const pf_bf16x8_t *>(&s_k[buf][qn * kPfKStride + (ks * 16 + half * 8) * 2]);
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qv[0][ks], s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qv[1][ks], s[1], 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qv[ks], s, 0, 0, 0);
         }
         // register c = 4j+i of a lane holds key 8j + 4*half + i of the tile
         const bool plain = (t < n_g) && ((t + 1) * kPfKT <= gl);  // full tile of the global cache: no mask
-        uint32_t pb[2][8];
+        float sc[16];
+        float mt = -INFINITY;
+        if (plain) {
 #pragma unroll
-        for (int rb = 0; rb < 2; rb++) {
-            float sc[16];
-            float mt = -INFINITY;
+            for (int c = 0; c < 16; c++) {
+                sc[c] = s[c] * a.scale_log2e;
+                mt = fmaxf(mt, sc[c]);
+            }
+        } else {
 #pragma unroll
             for (int j = 0; j < 4; j++) {
-                int4 lo4 = make_int4(INT_MIN, INT_MIN, INT_MIN, INT_MIN), hi4 = make_int4(INT_MAX, INT_MAX, INT_MAX, INT_MAX);
-                if (!plain) {
-                    lo4 = *reinterpret_cast<const int4 *>(&s_lo[buf][8 * j + 4 * half]);
-                    hi4 = *reinterpret_cast<const int4 *>(&s_hi[buf][8 * j + 4 * half]);
-                }
+                const int4 lo4 = *reinterpret_cast<const int4 *>(&s_lo[buf][8 * j + 4 * half]);
+                const int4 hi4 = *reinterpret_cast<const int4 *>(&s_hi[buf][8 * j + 4 * half]);
                 const int lo_[4] = {lo4.x, lo4.y, lo4.z, lo4.w}, hi_[4] = {hi4.x, hi4.y, hi4.z, hi4.w};
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
-                    const bool vis = (qpos[rb] >= lo_[i]) && (qpos[rb] <= hi_[i]);
-                    const float x = vis ? s[rb][4 * j + i] * a.scale_log2e : -INFINITY;
+                    const bool vis = (qpos >= lo_[i]) && (qpos <= hi_[i]);
+                    const float x = vis ? s[4 * j + i] * a.scale_log2e : -INFINITY;
                     sc[4 * j + i] = x;
                     mt = fmaxf(mt, x);
                 }
             }
-            mt = fmaxf(mt, __shfl_xor(mt, 32));  // the other 16 keys of this query
-            const float mnew = fmaxf(m[rb], mt);
-            const float msafe = mnew == -INFINITY ? 0.f : mnew;
-            const float corr = __builtin_amdgcn_exp2f(m[rb] - msafe);
-            float ps = 0.f;
-            float p[16];
-#pragma unroll
-            for (int c = 0; c < 16; c++) p[c] = __builtin_amdgcn_exp2f(sc[c] - msafe);
-#pragma unroll
-            for (int c = 0; c < 8; c++) {
-                pb[rb][c] = pf_pack(p[2 * c], p[2 * c + 1]);
-                ps += __uint_as_float(pb[rb][c] << 16) + __uint_as_float(pb[rb][c] & 0xffff0000u);  // the rounded weights
-            }
-            l[rb] = l[rb] * corr + ps;
-            if (__builtin_amdgcn_ballot_w64(mnew > m[rb]) != 0) {
-#pragma unroll
-                for (int db = 0; db < 4; db++)
-#pragma unroll
-                    for (int c = 0; c < 16; c++) o[rb][db][c] *= corr;
-            }
-            m[rb] = mnew;
         }
+        mt = fmaxf(mt, __shfl_xor(mt, 32));  // the other 16 keys of this query
+        const float mnew = fmaxf(m, mt);
+        const float msafe = mnew == -INFINITY ? 0.f : mnew;
+        const float corr = __builtin_amdgcn_exp2f(m - msafe);
+        uint32_t pb[8];
+        float ps = 0.f;
+        const pf_bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+        for (int c = 0; c < 8; c++) {
+            pb[c] = pf_pack(__builtin_amdgcn_exp2f(sc[2 * c] - msafe), __builtin_amdgcn_exp2f(sc[2 * c + 1] - msafe));
+            // the denominator sums the rounded weights, the ones the second product uses
+            ps = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pf_bf16x2_t, pb[c]), ones, ps, false);
+        }
+        l = l * corr + ps;
+        if (__builtin_amdgcn_ballot_w64(mnew > m) != 0) {
+#pragma unroll
+            for (int db = 0; db < 4; db++)
+#pragma unroll
+                for (int c = 0; c < 16; c++) o[db][c] *= corr;
+        }
+        m = mnew;
         // ---- O^T += V^T P^T : rows = d, columns = queries, contraction over the 32 keys ----
 #pragma unroll
         for (int t2 = 0; t2 < 2; t2++) {
-            pf_bf16x8_t pbv[2];
-#pragma unroll
-            for (int rb = 0; rb < 2; rb++) {
-                const uint4 u4 = make_uint4(pb[rb][4 * t2], pb[rb][4 * t2 + 1], pb[rb][4 * t2 + 2], pb[rb][4 * t2 + 3]);
-                pbv[rb] = __builtin_bit_cast(pf_bf16x8_t, u4);
-            }
+            const uint4 p4 = make_uint4(pb[4 * t2], pb[4 * t2 + 1], pb[4 * t2 + 2], pb[4 * t2 + 3]);
+            const pf_bf16x8_t pbv = __builtin_bit_cast(pf_bf16x8_t, p4);
 #pragma unroll
             for (int db = 0; db < 4; db++) {
                 // the lane's 8 contraction slots are keys 16*t2 + 4*half + {0..3} and + 8 more
@@ -233,28 +250,26 @@ __global__ __launch_bounds__(256) void attend_prefill_kernel(View pv, CallSeqs c
                 const uint2 v1 = *reinterpret_cast<const uint2 *>(vp + 16);
                 const uint4 u4 = make_uint4(v0.x, v0.y, v1.x, v1.y);
                 const pf_bf16x8_t va = __builtin_bit_cast(pf_bf16x8_t, u4);
-                o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbv[0], o[0][db], 0, 0, 0);
-                o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbv[1], o[1][db], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbv, o[db], 0, 0, 0);
             }
         }
         if (t + 1 < n_tiles) stage(buf ^ 1);
         __syncthreads();
     }
 
-    // ---- normalise and write: register c = 4j+i of o[rb][db] is d = 32*db + 8j + 4*half + i ----
-#pragma unroll
-    for (int rb = 0; rb < 2; rb++) {
+    // ---- normalise and write: register c = 4j+i of o[db] is d = 32*db + 8j + 4*half + i ----
+    {
         const int i = qt * kPfQ + rb * 32 + qn;
-        const float lt = l[rb] + __shfl_xor(l[rb], 32);
+        const float lt = l + __shfl_xor(l, 32);
         if (i < T) {
             const float inv = 1.0f / lt;
-            float *op = a.out + ((size_t)(base + i) * pv.Hq + (size_t)h * G + wave) * kPfD;
+            float *op = a.out + ((size_t)(base + i) * pv.Hq + (size_t)h * G + head) * kPfD;
 #pragma unroll
             for (int db = 0; db < 4; db++)
 #pragma unroll
                 for (int j = 0; j < 4; j++) {
-                    const float4 w4 = make_float4(o[rb][db][4 * j] * inv, o[rb][db][4 * j + 1] * inv,
-                                                  o[rb][db][4 * j + 2] * inv, o[rb][db][4 * j + 3] * inv);
+                    const float4 w4 = make_float4(o[db][4 * j] * inv, o[db][4 * j + 1] * inv,
+                                                  o[db][4 * j + 2] * inv, o[db][4 * j + 3] * inv);
                     *reinterpret_cast<float4 *>(op + 32 * db + 8 * j + 4 * half) = w4;
                 }
         }
@@ -284,7 +299,7 @@ hipError_t launch_attend_prefill(const View &pv, const CallSeqs &cs, int layer, 
     for (int b = 0; b < cs.n; b++) max_t = max(max_t, cs.ntok[b]);
     if (max_t == 0) return hipSuccess;
     dim3 grid((max_t + kPfQ - 1) / kPfQ, pv.Hkv, cs.n);
-    hipLaunchKernelGGL(attend_prefill_kernel, grid, dim3(256), 0, st, pv, cs, a);
+    hipLaunchKernelGGL(attend_prefill_kernel, grid, dim3(512), 0, st, pv, cs, a);
     return hipGetLastError();
 }
 
