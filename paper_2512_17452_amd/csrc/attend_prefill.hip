@@ -60,7 +60,7 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
     const int G = 4;
     // eight waves: wave -> (query head of the group, row block of 32 positions); two waves
     // share a SIMD, so one can run its softmax while the other keeps the matrix core busy
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int head = wave & 3, rb = wave >> 2;
     const int qn = lane & 31, half = lane >> 5;
     const int gl = pv.global_len[um];
@@ -159,6 +159,25 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
         lo_reg = ld_sel ? lo[1] : lo[0];
         hi_reg = ld_sel ? hi[1] : hi[0];
     };
+    // Full tiles of the global cache, pages of at least 4 tokens: the four keys a wave
+    // stages share a page, so the page base is scalar and a lane only adds a fixed offset.
+    const bool lean_ok = pv.P >= 4;
+    const uint32_t lean_row = (uint32_t)((2 * ld_pair) & (pv.P - 1));
+    const uint32_t lean_k_off = (lean_row + ld_sel) * (kPfD * 2) + ld_dc * 16;
+    const uint32_t lean_v_off = lean_row * (kPfD * 2) + pv.v_off + ld_dc * 16 + ld_sel * 8;
+    auto fetch_lean = [&](int t) {
+        if (((t * kPfKT + kPfKT - 1) >> pv.logP) >= pt_base + 64) {
+            pt_base = (t * kPfKT) >> pv.logP;
+            ptreg = (pt_base + lane < pv.maxgp) ? pv.global_pt[(size_t)um * pv.maxgp + pt_base + lane] : 0;
+        }
+        const int pg = __builtin_amdgcn_readlane(ptreg, ((t * kPfKT + 4 * wave) >> pv.logP) - pt_base);
+        const char *sb = page_ptr(pv, pg) + (size_t)((t * kPfKT) & (pv.P - 1)) * (kPfD * 2);
+        kreg = *reinterpret_cast<const uint4 *>(sb + lean_k_off);
+        vreg[0] = *reinterpret_cast<const uint2 *>(sb + lean_v_off);
+        vreg[1] = *reinterpret_cast<const uint2 *>(sb + lean_v_off + kPfD * 2);
+        lo_reg = INT_MIN;
+        hi_reg = INT_MAX;
+    };
     auto stage = [&](int buf) {
         *reinterpret_cast<uint4 *>(&s_k[buf][ld_key * kPfKStride + ld_dc * 16]) = kreg;
         // transposed V: row d, columns (key 2j, key 2j+1) as one 32-bit word
@@ -173,26 +192,48 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
         if (ld_dc == 0) { s_lo[buf][ld_key] = lo_reg; s_hi[buf][ld_key] = hi_reg; }
     };
 
+    const int n_plain = gl / kPfKT;  // full tiles of the global cache: no mask
     fetch(0);
     stage(0);
     __syncthreads();
 
     for (int t = 0; t < n_tiles; t++) {
         const int buf = t & 1;
-        if (t + 1 < n_tiles) fetch(t + 1);  // in flight while this tile is multiplied
+        // LDS latency is the scarce thing here: the eight K fragments are requested at once,
+        // the address arithmetic and global loads of the next tile run while they arrive,
+        // and the V fragments are requested before the softmax that hides their latency.
+        pf_bf16x8_t ka[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++)
+            ka[ks] = *reinterpret_cast<const pf_bf16x8_t *>(&s_k[buf][qn * kPfKStride + (ks * 16 + half * 8) * 2]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < n_tiles) {  // in flight while this tile is multiplied
+            if (lean_ok && t + 1 < n_plain) fetch_lean(t + 1);
+            else fetch(t + 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 
         // ---- S^T = K Q^T : rows = keys of the tile, columns = this wave's queries ----
         pf_f32x16_t s;
 #pragma unroll
         for (int c = 0; c < 16; c++) s[c] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ks++) {
-            const pf_bf16x8_t ka =
-                *reinterpret_cast<const pf_bf16x8_t *>(&s_k[buf][qn * kPfKStride + (ks * 16 + half * 8) * 2]);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qv[ks], s, 0, 0, 0);
-        }
+        for (int ks = 0; ks < 8; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qv[ks], s, 0, 0, 0);
+        // the lane's 8 contraction slots of V^T are keys 16*t2 + 4*half + {0..3} and + 8 more
+        pf_bf16x8_t va[2][4];
+#pragma unroll
+        for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+            for (int db = 0; db < 4; db++) {
+                const char *vp = &s_vt[buf][(db * 32 + qn) * kPfVStride + (16 * t2 + 4 * half) * 2];
+                const uint2 v0 = *reinterpret_cast<const uint2 *>(vp);
+                const uint2 v1 = *reinterpret_cast<const uint2 *>(vp + 16);
+                const uint4 u4 = make_uint4(v0.x, v0.y, v1.x, v1.y);
+                va[t2][db] = __builtin_bit_cast(pf_bf16x8_t, u4);
+            }
+        __builtin_amdgcn_sched_barrier(0);
         // register c = 4j+i of a lane holds key 8j + 4*half + i of the tile
-        const bool plain = (t < n_g) && ((t + 1) * kPfKT <= gl);  // full tile of the global cache: no mask
+        const bool plain = t < n_plain;
         float sc[16];
         float mt = -INFINITY;
         if (plain) {
@@ -243,15 +284,8 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
             const uint4 p4 = make_uint4(pb[4 * t2], pb[4 * t2 + 1], pb[4 * t2 + 2], pb[4 * t2 + 3]);
             const pf_bf16x8_t pbv = __builtin_bit_cast(pf_bf16x8_t, p4);
 #pragma unroll
-            for (int db = 0; db < 4; db++) {
-                // the lane's 8 contraction slots are keys 16*t2 + 4*half + {0..3} and + 8 more
-                const char *vp = &s_vt[buf][(db * 32 + qn) * kPfVStride + (16 * t2 + 4 * half) * 2];
-                const uint2 v0 = *reinterpret_cast<const uint2 *>(vp);
-                const uint2 v1 = *reinterpret_cast<const uint2 *>(vp + 16);
-                const uint4 u4 = make_uint4(v0.x, v0.y, v1.x, v1.y);
-                const pf_bf16x8_t va = __builtin_bit_cast(pf_bf16x8_t, u4);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pbv, o[db], 0, 0, 0);
-            }
+            for (int db = 0; db < 4; db++)
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t2][db], pbv, o[db], 0, 0, 0);
         }
         if (t + 1 < n_tiles) stage(buf ^ 1);
         __syncthreads();
