@@ -7,6 +7,13 @@ per layer `wgkv_decode_step` (lazy promotion + ring write) then `wgkv_attend`
 resident in HBM when the timed region starts.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+With `--workload llama8b_chunked_prefill_128k` a step is instead one chunk of the
+batch's prompts through one layer (linear gate -> chunk attention under the
+vertical-slash mask on the matrix cores -> admission), the roofline object then
+describes the chunk-attention kernel against the dense bf16 MFMA peak, and the
+chunks before the timed ones are the warm-up (they have to run anyway: they
+fill the cache the timed chunks attend over).
 """
 import argparse
 import ctypes as C
@@ -22,6 +29,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E published peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 
 
 def log(*a):
@@ -97,6 +105,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = wl.get_config(args.workload)
+    if cfg.chunk:
+        return main_prefill(args, cfg, torch, wg, wl, dev)
     B, L, Hq, Hk, d, W, P = cfg.batch, cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local, cfg.page_size
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     ctx = wl.context_lengths(cfg)
@@ -220,6 +230,92 @@ def main():
                    "attend_us_per_layer": roofline.get("kernel_avg_us"),
                    "gpu_ms_per_step": gpu_ms / args.steps, "host_wall_ms_per_step": wall_ms / args.steps},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(res), flush=True)
+
+
+def main_prefill(args, cfg, torch, wg, wl, dev):
+    """Chunked prefill of the whole batch, one layer: the last `--steps` chunks are timed."""
+    B, Hq, Hk, d, W, P, Cn, dim = (cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local,
+                                   cfg.page_size, cfg.chunk, cfg.hidden_dim)
+    G, N = Hq // Hk, cfg.ctx_max
+    n_chunks = N // Cn
+    steps = min(args.steps, n_chunks)
+    first_timed = n_chunks - steps
+    max_gp = N // P + 2
+    pool = wg.Pool(wg.Config(1, Hq, Hk, d, wg.BF16, P, W, B, max_gp, B * Hk * (max_gp + W // P) + 64), B, B * Cn)
+    gate_w = wl.draw_linear_gate(cfg, device=dev)
+    seqs, nt, scale = list(range(B)), [Cn] * B, 1.0 / math.sqrt(d)
+    out = torch.empty((B * Cn, Hq, d), dtype=torch.float32, device=dev)
+    # admitted-token prefix counts per (sequence, head): the visible pairs of a query at position p are
+    # min(W, p+1) window keys plus the admitted keys at positions <= p-W (Sec. 4.2 mask)
+    adm_prefix = torch.zeros((B, N + 1, Hk), dtype=torch.int64, device=dev)
+    events = HipEvents(2 * steps)
+    e_all = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    flops, gate_ms, admit_ms, wall0 = [], 0.0, 0.0, None
+    for c in range(n_chunks):
+        hidden = wl.draw_normal(cfg, "hidden", (B * Cn, dim), device=dev, key=(c,))
+        k = wl.draw_normal(cfg, "k", (B * Cn, Hk, d), device=dev, key=(c,))
+        v = wl.draw_normal(cfg, "v", (B * Cn, Hk, d), device=dev, key=(c,))
+        q = wl.draw_normal(cfg, "q", (B * Cn, Hq, d), device=dev, key=(c,))
+        timed = c >= first_timed
+        if c == first_timed:
+            torch.cuda.synchronize()
+            wall0 = time.perf_counter()
+            e_all[0].record()
+        if timed:
+            i = c - first_timed
+            pool.set_profile_events(events.ev[2 * i], events.ev[2 * i + 1])
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            ev[0].record()
+        g = wg.gate_scores(hidden, gate_w)
+        if timed:
+            ev[1].record()
+        pool.attend(0, seqs, q, out, scale, n_q=nt, k_chunk=k, v_chunk=v, g_chunk=g, tau=cfg.tau)
+        if timed:
+            ev[2].record()
+        pool.prefill_admit(0, seqs, nt, k, v, g, tau=cfg.tau)
+        if timed:
+            ev[3].record()
+        # bookkeeping for the flop count (not part of the path; after the timed calls of this chunk)
+        adm = (g >= cfg.tau).view(B, Cn, Hk).to(torch.int64)
+        t0 = c * Cn
+        adm_prefix[:, t0 + 1:t0 + Cn + 1] = adm_prefix[:, t0:t0 + 1] + torch.cumsum(adm, dim=1)
+        if timed:
+            pos = torch.arange(t0, t0 + Cn, device=dev)
+            older = adm_prefix[:, torch.clamp(pos - W + 1, min=0)]          # admitted at positions <= pos-W
+            pairs = (torch.clamp(pos + 1, max=W)[None, :, None] + older).sum()
+            torch.cuda.synchronize()
+            flops.append(4.0 * d * G * float(pairs))
+            gate_ms += ev[0].elapsed_time(ev[1])
+            admit_ms += ev[2].elapsed_time(ev[3])
+    e_all[1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - wall0) * 1e3
+    pool.set_profile_events(None, None)
+    free, flag = pool.status()
+    assert flag == 0
+    durs = np.array([events.elapsed_ms(events.ev[2 * i], events.ev[2 * i + 1]) for i in range(steps)])
+    events.destroy()
+    path_ms = float(durs.sum()) + gate_ms + admit_ms   # the three calls of the path, without the input generation between them
+    tflops = float(np.sum(flops)) / float(durs.sum()) / 1e9
+    log(f"[bench] chunks {first_timed}..{n_chunks - 1}: attention {durs.sum():.1f} ms, gate {gate_ms:.2f} ms, "
+        f"admit {admit_ms:.2f} ms, wall incl. input generation {wall_ms:.1f} ms")
+    res = {
+        "metric": "prefill_chunk_latency_us (one layer: linear gate + chunk attention under the vertical-slash mask + admission)",
+        "value": path_ms / steps * 1e3, "unit": "us/chunk", "n_gpus": 1, "steps": steps, "warmup": first_timed,
+        "ms_per_step": path_ms / steps, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": B, "layers": 1, "q_heads": Hq, "kv_heads": Hk, "head_dim": d,
+                   "w_local": W, "page_size": P, "tau": cfg.tau, "chunk": Cn, "prompt_tokens": N,
+                   "timed_chunks": [first_timed, n_chunks - 1], "gate_us_per_chunk": gate_ms / steps * 1e3,
+                   "admit_us_per_chunk": admit_ms / steps * 1e3, "attend_us_per_chunk": float(durs.mean() * 1e3),
+                   "prompt_tokens_per_s": B * Cn * steps / (path_ms * 1e-3)},
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "attend_prefill_kernel",
+                     "algorithmic_flops": float(np.sum(flops)), "kernel_total_ms": float(durs.sum()),
+                     "launches": int(steps)},
+        "cpu_baseline": None,
     }
     print(json.dumps(res), flush=True)
 

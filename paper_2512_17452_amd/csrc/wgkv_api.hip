@@ -403,10 +403,12 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
     }
     if (total == 0) return WGKV_OK;
     if (workspace_bytes < attend_prefill_ws_bytes(p->view, n_seqs, total)) return WGKV_ERR_WORKSPACE;
-    return launch_attend_prefill(p->view, cs, layer, q_dev, k_chunk_dev, v_chunk_dev, g_chunk_dev,
-                                 tau, scale, out_dev, workspace_dev, st) == hipSuccess
-               ? WGKV_OK
-               : WGKV_ERR_HIP;
+    if (p->ev0 && hipEventRecord(p->ev0, st) != hipSuccess) return WGKV_ERR_HIP;
+    if (launch_attend_prefill(p->view, cs, layer, q_dev, k_chunk_dev, v_chunk_dev, g_chunk_dev, tau,
+                              scale, out_dev, workspace_dev, st) != hipSuccess)
+        return WGKV_ERR_HIP;
+    if (p->ev1 && hipEventRecord(p->ev1, st) != hipSuccess) return WGKV_ERR_HIP;
+    return WGKV_OK;
 }
 
 int wgkv_free_seq(wgkv_pool *p, int32_t seq_id, wgkv_stream stream) {
