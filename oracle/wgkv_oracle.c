@@ -24,6 +24,9 @@
  *      pool (Sec. 4.1), initial cache population (Sec. 4.2) and lazy promotion
  *      (Sec. 4.3, steps (1)-(3)).
  *
+ *  (3) the gates that produce the scores: the linear gate of the chunked-prefill
+ *      workload and the Write-Gate MLP of Sec. 3.2 (at the end of the file).
+ *
  * All floating-point work is done in double; inputs arrive as float (the
  * exact widening of bf16 or fp32 data).  Threshold tests are done on the
  * stored fp32 score with the C `>=` operator, so a NaN score never admits.
@@ -545,5 +548,64 @@ int orc_linear_gate(int64_t T, int dim, int n_kv_heads, const float *hidden, con
             if (logit_out) logit_out[t * n_kv_heads + h] = s;
             if (g_out) g_out[t * n_kv_heads + h] = 1.0 / (1.0 + exp(-s));
         }
+    return ORC_OK;
+}
+
+/* Round a double to the nearest bfloat16 (ties to even) and return it as a double.
+ * Finite inputs in the normal float range only (that is all the callers produce). */
+static double round_to_bf16(double x) {
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/*
+ * Write-Gate MLP (Sec. 3.2, feature equation and gate equation).  Per token t and
+ * kv head h:
+ *     x = [ RMSNorm(k[t][h]) ; RMSNorm(k_rope[t][h]) ]                 (2d numbers)
+ *     g = sigmoid( W2[h] . GELU( W1[h] x + b1[h] ) + b2[h] )
+ * The paper leaves the hidden width, the GELU flavour and the RMSNorm constants
+ * open; here the width is an argument, GELU is the exact one,
+ * GELU(z) = z/2 (1 + erf(z / sqrt 2)), and RMSNorm(v) = v / sqrt(mean(v^2) + eps)
+ * carries no learnable scale.
+ *   k, k_rope : [T][H][d]      W1 : [H][width][2d]    b1 : [H][width]
+ *   W2        : [H][width]     b2 : [H]               logit_out, g_out : [T][H]
+ * feature_bf16 != 0 rounds every normalised feature to bfloat16 before the first
+ * product, as a bf16 model that hands its RMSNorm output to a bf16 matmul does.
+ */
+int orc_gate_mlp(int64_t T, int H, int d, int width, const float *k, const float *k_rope,
+                 const float *W1, const float *b1, const float *W2, const float *b2, double eps,
+                 int feature_bf16, double *logit_out, double *g_out) {
+    if (T < 0 || H < 1 || d < 1 || width < 1) return ORC_ERR_ARG;
+    double *x = (double *)malloc(sizeof(double) * 2 * (size_t)d);
+    if (!x) return ORC_ERR_ARG;
+    for (int64_t t = 0; t < T; t++)
+        for (int h = 0; h < H; h++) {
+            for (int part = 0; part < 2; part++) {
+                const float *v = (part == 0 ? k : k_rope) + ((size_t)t * H + h) * d;
+                double ss = 0.0;
+                for (int e = 0; e < d; e++) ss += (double)v[e] * (double)v[e];
+                const double r = 1.0 / sqrt(ss / d + eps);
+                for (int e = 0; e < d; e++) {
+                    const double xn = (double)v[e] * r;
+                    x[part * d + e] = feature_bf16 ? round_to_bf16(xn) : xn;
+                }
+            }
+            double logit = (double)b2[h];
+            for (int u = 0; u < width; u++) {
+                const float *w = W1 + ((size_t)h * width + u) * 2 * d;
+                double z = (double)b1[(size_t)h * width + u];
+                for (int e = 0; e < 2 * d; e++) z += (double)w[e] * x[e];
+                const double gelu = 0.5 * z * (1.0 + erf(z / sqrt(2.0)));
+                logit += (double)W2[(size_t)h * width + u] * gelu;
+            }
+            if (logit_out) logit_out[t * H + h] = logit;
+            if (g_out) g_out[t * H + h] = 1.0 / (1.0 + exp(-logit));
+        }
+    free(x);
     return ORC_OK;
 }

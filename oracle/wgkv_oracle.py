@@ -89,6 +89,8 @@ def lib():
         L.orc_linear_gate.argtypes = [C.c_int64, C.c_int, C.c_int, C.POINTER(C.c_float),
                                       C.POINTER(C.c_float), C.POINTER(C.c_double),
                                       C.POINTER(C.c_double)]
+        L.orc_gate_mlp.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int] + [C.POINTER(C.c_float)] * 6 + \
+                                  [C.c_double, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -257,4 +259,21 @@ def linear_gate(hidden, w):
     g = np.zeros((T, Hk), dtype=np.float64)
     lib().orc_linear_gate(T, dim, Hk, _p(hidden, C.c_float), _p(w, C.c_float),
                           _p(logit, C.c_double), _p(g, C.c_double))
+    return logit, g
+
+
+def gate_mlp(k, k_rope, W1, b1, W2, b2, eps=1e-6, feature_bf16=False):
+    """(logit, g) in fp64 of the Write-Gate MLP (Sec. 3.2) for k, k_rope [T, Hkv, d],
+    W1 [Hkv, width, 2d], b1 [Hkv, width], W2 [Hkv, width], b2 [Hkv]."""
+    k = _f32(k); k_rope = _f32(k_rope); W1 = _f32(W1); b1 = _f32(b1); W2 = _f32(W2); b2 = _f32(b2)
+    T, Hk, d = k.shape
+    width = W1.shape[1]
+    assert k_rope.shape == k.shape and W1.shape == (Hk, width, 2 * d)
+    assert b1.shape == (Hk, width) and W2.shape == (Hk, width) and b2.shape == (Hk,)
+    logit = np.zeros((T, Hk), dtype=np.float64)
+    g = np.zeros((T, Hk), dtype=np.float64)
+    rc = lib().orc_gate_mlp(T, Hk, d, width, _p(k, C.c_float), _p(k_rope, C.c_float), _p(W1, C.c_float),
+                            _p(b1, C.c_float), _p(W2, C.c_float), _p(b2, C.c_float), C.c_double(eps),
+                            1 if feature_bf16 else 0, _p(logit, C.c_double), _p(g, C.c_double))
+    assert rc == 0, rc
     return logit, g
