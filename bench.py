@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the per-kernel HIP events (roofline.achieved becomes null)")
     ap.add_argument("--ctx-scale", type=float, default=1.0, help="shrink contexts (debugging only)")
+    ap.add_argument("--gate", choices=["linear", "mlp"], default="linear",
+                    help="chunked-prefill workload only: the workload's linear gate on the hidden state, or the "
+                         "Write-Gate MLP (width 4*head_dim, random weights) on the keys before/after the rotary embedding")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM counters)")
     args = ap.parse_args()
@@ -245,6 +248,7 @@ def main_prefill(args, cfg, torch, wg, wl, dev):
     max_gp = N // P + 2
     pool = wg.Pool(wg.Config(1, Hq, Hk, d, wg.BF16, P, W, B, max_gp, B * Hk * (max_gp + W // P) + 64), B, B * Cn)
     gate_w = wl.draw_linear_gate(cfg, device=dev)
+    mlp = wl.draw_gate_mlp(cfg, 4 * d, device=dev) if args.gate == "mlp" else None
     seqs, nt, scale = list(range(B)), [Cn] * B, 1.0 / math.sqrt(d)
     out = torch.empty((B * Cn, Hq, d), dtype=torch.float32, device=dev)
     # admitted-token prefix counts per (sequence, head): the visible pairs of a query at position p are
@@ -268,7 +272,13 @@ def main_prefill(args, cfg, torch, wg, wl, dev):
             pool.set_profile_events(events.ev[2 * i], events.ev[2 * i + 1])
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
             ev[0].record()
-        g = wg.gate_scores(hidden, gate_w)
+        if mlp is None:
+            g = wg.gate_scores(hidden, gate_w)
+        else:  # k stands in for the rotated keys, a second draw for the keys before the rotation
+            k_pre = wl.draw_normal(cfg, "k_pre", (B * Cn, Hk, d), device=dev, key=(c,), std=1.5)
+            if timed:
+                ev[0].record()
+            g = wg.gate_mlp_scores(k_pre, k, *mlp)
         if timed:
             ev[1].record()
         pool.attend(0, seqs, q, out, scale, n_q=nt, k_chunk=k, v_chunk=v, g_chunk=g, tau=cfg.tau)
@@ -302,13 +312,13 @@ def main_prefill(args, cfg, torch, wg, wl, dev):
     log(f"[bench] chunks {first_timed}..{n_chunks - 1}: attention {durs.sum():.1f} ms, gate {gate_ms:.2f} ms, "
         f"admit {admit_ms:.2f} ms, wall incl. input generation {wall_ms:.1f} ms")
     res = {
-        "metric": "prefill_chunk_latency_us (one layer: linear gate + chunk attention under the vertical-slash mask + admission)",
+        "metric": "prefill_chunk_latency_us (one layer: write gate + chunk attention under the vertical-slash mask + admission)",
         "value": path_ms / steps * 1e3, "unit": "us/chunk", "n_gpus": 1, "steps": steps, "warmup": first_timed,
         "ms_per_step": path_ms / steps, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "layers": 1, "q_heads": Hq, "kv_heads": Hk, "head_dim": d,
                    "w_local": W, "page_size": P, "tau": cfg.tau, "chunk": Cn, "prompt_tokens": N,
-                   "timed_chunks": [first_timed, n_chunks - 1], "gate_us_per_chunk": gate_ms / steps * 1e3,
+                   "timed_chunks": [first_timed, n_chunks - 1], "gate": args.gate, "gate_us_per_chunk": gate_ms / steps * 1e3,
                    "admit_us_per_chunk": admit_ms / steps * 1e3, "attend_us_per_chunk": float(durs.mean() * 1e3),
                    "prompt_tokens_per_s": B * Cn * steps / (path_ms * 1e-3)},
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -121,6 +121,26 @@ int wgkv_gate_scores(int32_t dtype, int64_t n_tokens, int32_t hidden_dim, int32_
                      const void *hidden_dev, const void *gate_w_dev, float *g_out_dev,
                      wgkv_stream stream);
 
+/* Sec. 3.2, feature equation and gate equation (the Write-Gate MLP), per token t and
+ * kv head h:  x = [RMSNorm(k[t][h]) ; RMSNorm(k_rope[t][h])],
+ *             g[t][h] = sigmoid(W2[h] . GELU(W1[h] x + b1[h]) + b2[h]).
+ * The paper leaves width, GELU flavour and RMSNorm constants open: width is an
+ * argument, GELU is the exact one (erf), RMSNorm(v) = v / sqrt(mean(v^2) + eps) has no
+ * learnable scale.  With bf16 inputs the normalised features are rounded to bf16 before
+ * the first product; accumulation, GELU and sigmoid are fp32.
+ *   k_dev, k_rope_dev : [n_tokens][n_kv_heads][head_dim] of `dtype` (keys before and
+ *                       after the rotary embedding), 16-byte aligned
+ *   w1_dev [n_kv_heads][width][2*head_dim], w2_dev [n_kv_heads][width] of `dtype`;
+ *   b1_dev float [n_kv_heads][width], b2_dev float [n_kv_heads]
+ *   g_out_dev float [n_tokens][n_kv_heads]
+ * All buffers are device memory owned by the caller; the call only enqueues work on
+ * `stream`.  bf16 with head_dim 64 or 128 and width a multiple of 32 runs on the matrix
+ * cores, every other shape on a plain kernel.  Errors: INVALID_ARG, HIP. */
+int wgkv_gate_mlp_scores(int32_t dtype, int64_t n_tokens, int32_t n_kv_heads, int32_t head_dim,
+                         int32_t width, const void *k_dev, const void *k_rope_dev,
+                         const void *w1_dev, const float *b1_dev, const void *w2_dev,
+                         const float *b2_dev, float eps, float *g_out_dev, wgkv_stream stream);
+
 /* Sec. 4.2 "Initial cache population", also for one chunk of a chunked prefill:
  * feeds n_tokens_host[b] new tokens of layer `layer` to sequence seq_ids_host[b]
  * (distinct ids, n_seqs <= WGKV_MAX_CALL_SEQS).  Tokens that leave the window in

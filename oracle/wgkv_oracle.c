@@ -581,9 +581,10 @@ int orc_gate_mlp(int64_t T, int H, int d, int width, const float *k, const float
                  const float *W1, const float *b1, const float *W2, const float *b2, double eps,
                  int feature_bf16, double *logit_out, double *g_out) {
     if (T < 0 || H < 1 || d < 1 || width < 1) return ORC_ERR_ARG;
-    double *x = (double *)malloc(sizeof(double) * 2 * (size_t)d);
-    if (!x) return ORC_ERR_ARG;
-    for (int64_t t = 0; t < T; t++)
+    /* tokens are independent: spread them over the host threads */
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; t++) {
+        double *x = (double *)malloc(sizeof(double) * 2 * (size_t)d);
         for (int h = 0; h < H; h++) {
             for (int part = 0; part < 2; part++) {
                 const float *v = (part == 0 ? k : k_rope) + ((size_t)t * H + h) * d;
@@ -606,6 +607,7 @@ int orc_gate_mlp(int64_t T, int H, int d, int width, const float *k, const float
             if (logit_out) logit_out[t * H + h] = logit;
             if (g_out) g_out[t * H + h] = 1.0 / (1.0 + exp(-logit));
         }
-    free(x);
+        free(x);
+    }
     return ORC_OK;
 }

@@ -5,5 +5,5 @@ package only marshals arguments.  PyTorch supplies device memory and the stream.
 There is no CPU fallback: importing works anywhere, calling needs the built
 library and a GPU.
 """
-from .binding import (Config, Pool, WgkvError, gate_scores, load_library, library_path,  # noqa: F401
+from .binding import (Config, Pool, WgkvError, gate_mlp_scores, gate_scores, load_library, library_path,  # noqa: F401
                       EXPORTED_SYMBOLS, F32, BF16)

@@ -11,7 +11,7 @@ F32, BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
-    "wgkv_gate_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_free_seq",
+    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_free_seq",
     "wgkv_status", "wgkv_set_profile_events", "wgkv_destroy",
 ]
 
@@ -82,6 +82,7 @@ def load_library():
     L.wgkv_query_sizes.argtypes = [C.POINTER(_CConfig), i32, i64, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
     L.wgkv_init_pool.argtypes = [C.POINTER(_CConfig), vp, sz, vp, sz, vp, C.POINTER(vp)]
     L.wgkv_gate_scores.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp]
+    L.wgkv_gate_mlp_scores.argtypes = [i32, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp]
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
@@ -125,6 +126,28 @@ def gate_scores(hidden, gate_w, out=None):
         out = torch.empty((T, Hk), dtype=torch.float32, device=hidden.device)
     dt = F32 if hidden.dtype == torch.float32 else BF16
     _check(L.wgkv_gate_scores(dt, T, dim, Hk, _ptr(hidden), _ptr(gate_w), _ptr(out), _stream()), "wgkv_gate_scores")
+    return out
+
+
+def gate_mlp_scores(k, k_rope, w1, b1, w2, b2, eps=1e-6, out=None):
+    """wgkv_gate_mlp_scores: the Write-Gate MLP on keys before / after the rotary embedding.
+    k, k_rope [T, Hkv, d]; w1 [Hkv, width, 2d], w2 [Hkv, width] of the keys' dtype;
+    b1 [Hkv, width], b2 [Hkv] float32.  Returns float32 [T, Hkv]."""
+    import torch
+    L = load_library()
+    T, Hk, d = k.shape
+    width = w1.shape[1]
+    for x in (k, k_rope, w1, b1, w2, b2):
+        assert x.is_cuda and x.is_contiguous()
+    assert k_rope.shape == k.shape and w1.shape == (Hk, width, 2 * d) and w2.shape == (Hk, width)
+    assert b1.shape == (Hk, width) and b2.shape == (Hk,)
+    assert k.dtype in (torch.float32, torch.bfloat16) and k_rope.dtype == k.dtype
+    assert w1.dtype == k.dtype and w2.dtype == k.dtype and b1.dtype == torch.float32 and b2.dtype == torch.float32
+    if out is None:
+        out = torch.empty((T, Hk), dtype=torch.float32, device=k.device)
+    dt = F32 if k.dtype == torch.float32 else BF16
+    _check(L.wgkv_gate_mlp_scores(dt, T, Hk, d, width, _ptr(k), _ptr(k_rope), _ptr(w1), _ptr(b1), _ptr(w2),
+                                  _ptr(b2), eps, _ptr(out), _stream()), "wgkv_gate_mlp_scores")
     return out
 
 

@@ -25,6 +25,9 @@ hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int
                                 const void *q, float scale, float *out, void *ws, int32_t *counters,
                                 int n_cu, int grid_max, int min_tpb, hipStream_t st, hipEvent_t ev0,
                                 hipEvent_t ev1);
+hipError_t launch_gate_mlp(int dtype, int64_t n_tokens, int n_kv_heads, int head_dim, int width,
+                           const void *k, const void *k_rope, const void *w1, const float *b1,
+                           const void *w2, const float *b2, float eps, float *g_out, hipStream_t st);
 hipError_t launch_gate_linear(int dtype, int64_t n_tokens, int hidden_dim, int n_kv_heads,
                               const void *hidden, const void *w, float *g_out, hipStream_t st);
 size_t attend_prefill_ws_bytes(const View &pv, int n_seqs, int64_t total_q);
@@ -238,6 +241,23 @@ int wgkv_gate_scores(int32_t dtype, int64_t n_tokens, int32_t hidden_dim, int32_
     if (n_tokens == 0) return WGKV_OK;
     return launch_gate_linear(dtype, n_tokens, hidden_dim, n_kv_heads, hidden_dev, gate_w_dev,
                               g_out_dev, (hipStream_t)stream) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
+}
+
+int wgkv_gate_mlp_scores(int32_t dtype, int64_t n_tokens, int32_t n_kv_heads, int32_t head_dim,
+                         int32_t width, const void *k_dev, const void *k_rope_dev,
+                         const void *w1_dev, const float *b1_dev, const void *w2_dev,
+                         const float *b2_dev, float eps, float *g_out_dev, wgkv_stream stream) {
+    if ((dtype != WGKV_F32 && dtype != WGKV_BF16) || n_tokens < 0 || n_kv_heads < 1 ||
+        n_kv_heads > 65535 || head_dim < 1 || head_dim > 4096 || width < 1 || !w1_dev || !b1_dev ||
+        !w2_dev || !b2_dev || !(eps >= 0.f) || !std::isfinite(eps))
+        return WGKV_ERR_INVALID_ARG;
+    if (n_tokens == 0) return WGKV_OK;  // nothing to read or write: the token buffers may be NULL
+    if (!k_dev || !k_rope_dev || !g_out_dev) return WGKV_ERR_INVALID_ARG;
+    if ((((uintptr_t)k_dev | (uintptr_t)k_rope_dev | (uintptr_t)w1_dev) & 15) != 0) return WGKV_ERR_INVALID_ARG;
+    return launch_gate_mlp(dtype, n_tokens, n_kv_heads, head_dim, width, k_dev, k_rope_dev, w1_dev,
+                           b1_dev, w2_dev, b2_dev, eps, g_out_dev, (hipStream_t)stream) == hipSuccess
                ? WGKV_OK
                : WGKV_ERR_HIP;
 }

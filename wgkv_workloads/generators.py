@@ -14,7 +14,8 @@ import torch
 from .configs import WorkloadConfig
 
 _PURPOSE = {"rates": 1, "scores": 2, "k": 3, "v": 4, "q": 5, "ctx": 6, "gate_w": 7, "hidden": 8,
-            "dec_scores": 9, "dec_k": 10, "dec_v": 11}
+            "dec_scores": 9, "dec_k": 10, "dec_v": 11, "k_pre": 12, "k_rope": 13, "mlp_w1": 14, "mlp_b1": 15,
+            "mlp_w2": 16, "mlp_b2": 17}
 
 
 def _rng(cfg: WorkloadConfig, purpose: str, *key) -> np.random.Generator:
@@ -102,3 +103,15 @@ def draw_normal(cfg: WorkloadConfig, purpose: str, shape, device="cpu", key=(), 
 def draw_linear_gate(cfg: WorkloadConfig, device="cpu") -> torch.Tensor:
     """Random-init per-kv-head linear gate weights ~ N(0, 0.02), [n_kv_heads, hidden_dim]."""
     return draw_normal(cfg, "gate_w", (cfg.n_kv_heads, cfg.hidden_dim), device=device, std=0.02)
+
+
+def draw_gate_mlp(cfg: WorkloadConfig, width: int, device="cpu"):
+    """Random-init Write-Gate MLP parameters for every kv head: W1 [Hkv, width, 2d] ~ N(0, 1/(2d)),
+    b1 [Hkv, width] ~ N(0, 0.25), W2 [Hkv, width] ~ N(0, 4/width) in the workload dtype (biases fp32),
+    b2 [Hkv] ~ N(0, 1): hidden pre-activations and logits of order one, so the scores spread over (0, 1)."""
+    Hk, d = cfg.n_kv_heads, cfg.head_dim
+    w1 = draw_normal(cfg, "mlp_w1", (Hk, width, 2 * d), device=device, std=(2 * d) ** -0.5)
+    b1 = draw_normal(cfg, "mlp_b1", (Hk, width), device=device, std=0.5, dtype=torch.float32)
+    w2 = draw_normal(cfg, "mlp_w2", (Hk, width), device=device, std=2.0 * width ** -0.5)
+    b2 = draw_normal(cfg, "mlp_b2", (Hk,), device=device, std=1.0, dtype=torch.float32)
+    return w1, b1, w2, b2
