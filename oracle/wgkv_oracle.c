@@ -24,7 +24,11 @@
  *      pool (Sec. 4.1), initial cache population (Sec. 4.2) and lazy promotion
  *      (Sec. 4.3, steps (1)-(3)).
  *
- *  (3) the gates that produce the scores: the linear gate of the chunked-prefill
+ *  (3) budgeted eviction on the global cache (the appendix on the synergy with
+ *      eviction): importance scores from an observation window and removal of
+ *      the lowest-scored entries with compaction and release of pages.
+ *
+ *  (4) the gates that produce the scores: the linear gate of the chunked-prefill
  *      workload and the Write-Gate MLP of Sec. 3.2 (at the end of the file).
  *
  * All floating-point work is done in double; inputs arrive as float (the
@@ -547,6 +551,139 @@ int orc_linear_gate(int64_t T, int dim, int n_kv_heads, const float *hidden, con
             for (int e = 0; e < dim; e++) s += (double)hidden[t * dim + e] * (double)w[(size_t)h * dim + e];
             if (logit_out) logit_out[t * n_kv_heads + h] = s;
             if (g_out) g_out[t * n_kv_heads + h] = 1.0 / (1.0 + exp(-s));
+        }
+    return ORC_OK;
+}
+
+/*
+ * Budgeted eviction on the global cache (appendix "Eviction policy implementation").
+ *
+ * Importance of the N entries of one head's global cache, from the queries of the
+ * last n_obs positions (the observation window), in the appendix' three steps:
+ *   (1) A^(hq) = Softmax(Q_obs^(hq) K^T * scale) for every query head hq of the group,
+ *   (2) S_raw_j = sum_i max_hq A^(hq)_ij,
+ *   (3) S = MaxPool(S_raw, pool_w) along the cache order.
+ * Readings: K is the head's global cache alone (the only entries that can be evicted;
+ * every one of them is older than the window, so every observation query sees all of
+ * them and no mask is needed) and the softmax is normalised over these N entries;
+ * the pooling window is centred (j - pool_w/2 .. j + pool_w/2) and clipped at the
+ * ends of the cache, pool_w odd.
+ *   q_obs : [n_obs][n_q_heads][d]; s_raw_out, s_out : [N] (either may be NULL)
+ */
+int orc_evict_scores(const orc_state *S, int layer, int seq, int h, const float *q_obs, int n_obs,
+                     double scale, int pool_w, double *s_raw_out, double *s_out) {
+    if (!S || !S->c.keep_payload || layer < 0 || layer >= S->c.n_layers || seq < 0 ||
+        seq >= S->c.max_seqs || h < 0 || h >= S->c.n_kv_heads || n_obs < 1 || pool_w < 1 ||
+        pool_w % 2 == 0 || !q_obs)
+        return ORC_ERR_ARG;
+    const orc_head *H = &S->sl[(size_t)seq * S->c.n_layers + layer].h[h];
+    const int d = S->c.head_dim, G = S->c.n_q_heads / S->c.n_kv_heads;
+    const int64_t N = H->glen;
+    if (N == 0) return ORC_OK;
+    double *raw = (double *)calloc((size_t)N, sizeof(double));
+    double *a = (double *)malloc(sizeof(double) * (size_t)N * G);
+    if (!raw || !a) { free(raw); free(a); return ORC_ERR_NOMEM; }
+    for (int i = 0; i < n_obs; i++) {
+        for (int g = 0; g < G; g++) {
+            const float *q = q_obs + ((size_t)i * S->c.n_q_heads + (size_t)h * G + g) * d;
+            double *row = a + (size_t)g * N;
+            double mx = -INFINITY;
+            for (int64_t j = 0; j < N; j++) {
+                double dot = 0.0;
+                for (int e = 0; e < d; e++) dot += (double)q[e] * (double)H->gk[j * d + e];
+                row[j] = dot * scale;
+                if (row[j] > mx) mx = row[j];
+            }
+            double den = 0.0;
+            for (int64_t j = 0; j < N; j++) { row[j] = exp(row[j] - mx); den += row[j]; }
+            for (int64_t j = 0; j < N; j++) row[j] /= den;
+        }
+        for (int64_t j = 0; j < N; j++) {
+            double best = a[j];
+            for (int g = 1; g < G; g++) if (a[(size_t)g * N + j] > best) best = a[(size_t)g * N + j];
+            raw[j] += best;
+        }
+    }
+    for (int64_t j = 0; j < N; j++) {
+        if (s_raw_out) s_raw_out[j] = raw[j];
+        if (s_out) {
+            double best = raw[j];
+            for (int64_t jj = j - pool_w / 2; jj <= j + pool_w / 2; jj++)
+                if (jj >= 0 && jj < N && raw[jj] > best) best = raw[jj];
+            s_out[j] = best;
+        }
+    }
+    free(raw); free(a);
+    return ORC_OK;
+}
+
+/* Order of fp32 scores used for eviction: the total order of the bit patterns
+ * (negative < positive, NaN with the sign bit clear above everything). */
+static uint32_t score_key(float x) {
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+/*
+ * Removes, from every head of the given sequences, the floor(frac * N) entries of its
+ * global cache with the lowest scores ("remove the bottom 10 %" in the appendix; the
+ * policy works on each kv head on its own).  Among equal scores the older entry goes
+ * first.  The survivors keep their order and are packed to the front; pages that no
+ * longer hold an entry go back to the free stack, units in (position in the call, kv
+ * head) order, a unit's pages in ascending table index.  The page order is this
+ * project's own rule (the paper has none).
+ *   scores : float [n_seqs * n_kv_heads][stride], entry j of unit (b, h) at
+ *            scores[(b * n_kv_heads + h) * stride + j]
+ *   n_evicted_out (optional): [n_seqs * n_kv_heads]
+ */
+int orc_evict_apply(orc_state *S, int layer, int n_seqs, const int32_t *seq_ids, const float *scores,
+                    int64_t stride, float frac, int64_t *n_evicted_out) {
+    if (!S || layer < 0 || layer >= S->c.n_layers || n_seqs < 0 || !seq_ids || !scores ||
+        !(frac >= 0.0f) || !(frac <= 1.0f))
+        return ORC_ERR_ARG;
+    const int Hk = S->c.n_kv_heads, d = S->c.head_dim, P = S->c.page_size;
+    for (int b = 0; b < n_seqs; b++) {
+        if (seq_ids[b] < 0 || seq_ids[b] >= S->c.max_seqs) return ORC_ERR_ARG;
+        for (int b2 = 0; b2 < b; b2++) if (seq_ids[b2] == seq_ids[b]) return ORC_ERR_ARG;
+    }
+    for (int b = 0; b < n_seqs; b++)
+        for (int h = 0; h < Hk; h++) {
+            orc_head *H = &S->sl[(size_t)seq_ids[b] * S->c.n_layers + layer].h[h];
+            const float *sc = scores + ((size_t)b * Hk + h) * stride;
+            const int64_t N = H->glen;
+            if (N > stride) return ORC_ERR_ARG;
+            const int64_t n_e = (int64_t)floor((double)frac * (double)N);
+            if (n_evicted_out) n_evicted_out[(size_t)b * Hk + h] = n_e;
+            if (n_e == 0) continue;
+            /* plain selection: n_e times take the smallest (key, index) not yet taken */
+            char *gone = (char *)calloc((size_t)N, 1);
+            if (!gone) return ORC_ERR_NOMEM;
+            for (int64_t r = 0; r < n_e; r++) {
+                int64_t best = -1;
+                for (int64_t j = 0; j < N; j++)
+                    if (!gone[j] && (best < 0 || score_key(sc[j]) < score_key(sc[best]))) best = j;
+                gone[best] = 1;
+            }
+            int64_t w = 0;
+            for (int64_t j = 0; j < N; j++) {
+                if (gone[j]) continue;
+                if (w != j) {
+                    H->gpos[w] = H->gpos[j];
+                    if (S->c.keep_payload) {
+                        memmove(H->gk + w * d, H->gk + j * d, sizeof(float) * d);
+                        memmove(H->gv + w * d, H->gv + j * d, sizeof(float) * d);
+                    }
+                }
+                w++;
+            }
+            free(gone);
+            const int64_t old_pages = (N + P - 1) / P, new_pages = (w + P - 1) / P;
+            for (int64_t lp = new_pages; lp < old_pages; lp++) {
+                S->free_stack[S->free_top++] = H->global_pt[lp];
+                H->global_pt[lp] = -1;
+            }
+            H->glen = w;
         }
     return ORC_OK;
 }

@@ -89,6 +89,10 @@ def lib():
         L.orc_linear_gate.argtypes = [C.c_int64, C.c_int, C.c_int, C.POINTER(C.c_float),
                                       C.POINTER(C.c_float), C.POINTER(C.c_double),
                                       C.POINTER(C.c_double)]
+        L.orc_evict_scores.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.c_int,
+                                       C.c_double, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.orc_evict_apply.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_float),
+                                      C.c_int64, C.c_float, C.POINTER(C.c_int64)]
         L.orc_gate_mlp.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int] + [C.POINTER(C.c_float)] * 6 + \
                                   [C.c_double, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _lib = L
@@ -191,6 +195,35 @@ class Oracle:
         if rc:
             raise OracleError(rc)
         return gk[:n], gv[:n], rk, rv
+
+    def evict_scores(self, layer, seq, h, q_obs, scale, pool_w=5):
+        """(s_raw, s) importance of the entries of one head's global cache from the observation
+        queries q_obs [n_obs, n_q_heads, d] (appendix "Eviction policy implementation")."""
+        q_obs = _f32(q_obs)
+        n_obs = q_obs.shape[0]
+        assert q_obs.shape == (n_obs, self.cfg.n_q_heads, self.cfg.head_dim)
+        n = self.global_len(seq, layer, h)
+        raw = np.zeros(max(n, 1), dtype=np.float64)
+        sm = np.zeros(max(n, 1), dtype=np.float64)
+        rc = self._L.orc_evict_scores(self._s, layer, seq, h, _p(q_obs, C.c_float), n_obs, float(scale),
+                                      int(pool_w), _p(raw, C.c_double), _p(sm, C.c_double))
+        if rc:
+            raise OracleError(rc)
+        return raw[:n], sm[:n]
+
+    def evict_apply(self, layer, seq_ids, scores, frac):
+        """Removes the floor(frac * N) lowest-scored global entries of every head of the sequences;
+        scores float32 [len(seq_ids) * n_kv_heads, stride].  Returns the number removed per unit."""
+        seq_ids = np.ascontiguousarray(seq_ids, dtype=np.int32)
+        scores = _f32(scores)
+        n_units = len(seq_ids) * self.cfg.n_kv_heads
+        assert scores.ndim == 2 and scores.shape[0] == n_units
+        gone = np.zeros(max(n_units, 1), dtype=np.int64)
+        rc = self._L.orc_evict_apply(self._s, layer, len(seq_ids), _p(seq_ids, C.c_int32), _p(scores, C.c_float),
+                                     scores.shape[1], np.float32(frac), _p(gone, C.c_int64))
+        if rc:
+            raise OracleError(rc)
+        return gone[:n_units]
 
     def attend_cached(self, seq, layer, q, scale):
         q = _f32(q).reshape(self.cfg.n_q_heads, self.cfg.head_dim)
