@@ -136,6 +136,10 @@ def test_apply_edge_fractions_and_score_order():
     sc = np.zeros((2, max(N)), np.float32)
     assert list(o.evict_apply(0, [0], sc, 0.0)) == [0, 0] and o.global_len(0, 0, 0) == N[0]
     assert list(o.evict_apply(0, [0], sc, 1.0 / (max(N) + 1))) == [0, 0]         # floor(frac N) = 0
+    # all scores equal: the cut falls inside the tie and the oldest entries go
+    gone = o.evict_apply(0, [0], sc, np.float32(2.5 / N[0]))
+    assert gone[0] == 2 and np.array_equal(o.global_pos(0, 0, 0), pos0[2:])
+    pos0, N[0] = pos0[2:], N[0] - 2
     # negative below zero below positive below NaN: the order of the bit patterns
     sc[0, :4] = [np.nan, -1.0, 3.0, 0.0]
     sc[0, 4:] = 7.0
