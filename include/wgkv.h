@@ -189,6 +189,24 @@ int wgkv_attend(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *s
                 const void *v_chunk_dev, const float *g_chunk_dev, float tau, float scale,
                 float *out_dev, void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
 
+/* Appendix "Eviction policy implementation", the removal step: every kv head of the
+ * given sequences (distinct ids) drops the floor(frac * N) entries of its global cache
+ * with the lowest scores, N its current length ("the bottom 10 %": frac = 0.1; each
+ * head on its own).  Scores are compared in the total order of their fp32 bit patterns;
+ * among equal scores the older entry goes first.  The survivors keep their order and
+ * are packed to the front in place; pages left without an entry return to the free
+ * stack, units in (position in the call, kv head) order, a unit's pages in ascending
+ * table index.  When to call it (the memory budget) is the caller's policy.
+ *   scores_dev : float [n_seqs * n_kv_heads][stride], entry j of the head at
+ *                [(b * n_kv_heads + h) * stride + j]; stride must cover the host's
+ *                upper bound of every head's length (wgkv_status makes it exact)
+ *   n_evicted_out_dev : optional int32 [n_seqs * n_kv_heads]
+ * Errors: INVALID_ARG, WORKSPACE, HIP. */
+int wgkv_evict_apply(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                     const float *scores_dev, int64_t stride, float frac,
+                     int32_t *n_evicted_out_dev, void *workspace_dev, size_t workspace_bytes,
+                     wgkv_stream stream);
+
 /* Returns every page of a sequence slot to the free stack (layers ascending, kv
  * heads ascending, a unit's local pages then its global pages) and clears it. */
 int wgkv_free_seq(wgkv_pool *pool, int32_t seq_id, wgkv_stream stream);

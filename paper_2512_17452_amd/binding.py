@@ -11,7 +11,7 @@ F32, BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
-    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_free_seq",
+    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_evict_apply", "wgkv_free_seq",
     "wgkv_status", "wgkv_set_profile_events", "wgkv_destroy",
 ]
 
@@ -86,6 +86,7 @@ def load_library():
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
+    L.wgkv_evict_apply.argtypes = [vp, i32, i32, pi32, vp, i64, f32, vp, vp, sz, vp]
     L.wgkv_free_seq.argtypes = [vp, i32, vp]
     L.wgkv_status.argtypes = [vp, vp, C.POINTER(i64), C.POINTER(i32)]
     L.wgkv_set_profile_events.argtypes = [vp, vp, vp]
@@ -204,6 +205,15 @@ class Pool:
                                   _ptr(k_chunk), _ptr(v_chunk), _ptr(g_chunk), tau, scale, _ptr(out),
                                   _ptr(self.workspace), self.workspace.numel(), _stream()), "wgkv_attend")
         return out
+
+    def evict_apply(self, layer, seq_ids, scores, frac, n_evicted_out=None):
+        """wgkv_evict_apply: scores float32 [len(seq_ids) * n_kv_heads, stride] on the device."""
+        import torch
+        assert scores.is_cuda and scores.is_contiguous() and scores.dtype == torch.float32 and scores.dim() == 2
+        assert scores.shape[0] == len(seq_ids) * self.cfg.n_kv_heads
+        _check(self.L.wgkv_evict_apply(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(scores), scores.shape[1],
+                                       frac, _ptr(n_evicted_out), _ptr(self.workspace), self.workspace.numel(),
+                                       _stream()), "wgkv_evict_apply")
 
     def free_seq(self, seq_id):
         _check(self.L.wgkv_free_seq(self.h, seq_id, _stream()), "wgkv_free_seq")

@@ -20,6 +20,9 @@ hipError_t launch_decode_step(const View &pv, const CallSeqs &cs, int layer, flo
                               const void *k, const void *v, const float *g, uint8_t *promoted_out,
                               hipStream_t st);
 hipError_t launch_free_seq(const View &pv, int sid, hipStream_t st);
+size_t evict_ws_bytes(int n_units);
+hipError_t launch_evict_apply(const View &pv, const CallSeqs &cs, int layer, const float *scores,
+                              int64_t stride, float frac, int32_t *n_evicted, void *ws, hipStream_t st);
 size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid);
 hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int32_t *sids,
                                 const void *q, float scale, float *out, void *ws, int32_t *counters,
@@ -168,7 +171,9 @@ int wgkv_query_sizes(const wgkv_config *cfg, int32_t max_call_seqs, int64_t max_
         size_t b = attend_decode_ws_bytes(v, max_call_seqs, kAttnGridMax);
         size_t c = attend_prefill_ws_bytes(v, max_call_seqs, max_call_tokens);
         size_t m = a > b ? a : b;
-        *workspace_bytes = align256(m > c ? m : c);
+        m = m > c ? m : c;
+        const size_t e = evict_ws_bytes(max_call_seqs * cfg->n_kv_heads);
+        *workspace_bytes = align256(m > e ? m : e);
     }
     return WGKV_OK;
 }
@@ -428,6 +433,45 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
                               scale, out_dev, workspace_dev, st) != hipSuccess)
         return WGKV_ERR_HIP;
     if (p->ev1 && hipEventRecord(p->ev1, st) != hipSuccess) return WGKV_ERR_HIP;
+    return WGKV_OK;
+}
+
+int wgkv_evict_apply(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                     const float *scores_dev, int64_t stride, float frac,
+                     int32_t *n_evicted_out_dev, void *workspace_dev, size_t workspace_bytes,
+                     wgkv_stream stream) {
+    int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    if (!scores_dev || !workspace_dev || !(frac >= 0.f) || !(frac <= 1.f) || stride < 0)
+        return WGKV_ERR_INVALID_ARG;
+    const wgkv_config &c = p->cfg;
+    const int H = c.n_kv_heads, P = c.page_size;
+    if (workspace_bytes < evict_ws_bytes(n_seqs * H)) return WGKV_ERR_WORKSPACE;
+    CallSeqs cs;
+    memset(&cs, 0, sizeof(cs));
+    cs.n = n_seqs;
+    for (int b = 0; b < n_seqs; b++) {
+        const size_t sl = (size_t)seq_ids_host[b] * c.n_layers + layer;
+        cs.sid[b] = seq_ids_host[b];
+        cs.t0[b] = p->seq_len_h[sl];
+        // a score row must cover every entry the head may hold (the host knows an upper bound)
+        for (int h = 0; h < H; h++)
+            if (p->g_ub[sl * H + h] > stride) return WGKV_ERR_INVALID_ARG;
+    }
+    if (launch_evict_apply(p->view, cs, layer, scores_dev, stride, frac, n_evicted_out_dev,
+                           workspace_dev, (hipStream_t)stream) != hipSuccess)
+        return WGKV_ERR_HIP;
+    // bounds after the call: N - floor(frac N) does not decrease with N, so it maps an upper
+    // bound of the length to an upper bound of the new length
+    for (int b = 0; b < n_seqs; b++) {
+        const size_t sl = (size_t)seq_ids_host[b] * c.n_layers + layer;
+        for (int h = 0; h < H; h++) {
+            const int64_t g0 = p->g_ub[sl * H + h];
+            const int64_t g1 = g0 - (int64_t)floor((double)frac * (double)g0);
+            p->pages_ub -= (g0 + P - 1) / P - (g1 + P - 1) / P;
+            p->g_ub[sl * H + h] = g1;
+        }
+    }
     return WGKV_OK;
 }
 

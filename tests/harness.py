@@ -56,6 +56,15 @@ class Pair:
             self.touched.add((s, layer))
         np.testing.assert_array_equal(prom.cpu().numpy(), oprom)
 
+    def evict(self, layer, seq_ids, scores, frac):
+        """scores: numpy float32 [len(seq_ids) * Hk, stride]; both sides drop floor(frac * N) per head."""
+        n_units = len(seq_ids) * self.cfg.n_kv_heads
+        gone = torch.full((n_units,), -1, dtype=torch.int32, device=self.dev)
+        self.pool.evict_apply(layer, seq_ids, torch.from_numpy(scores).to(self.dev), frac, n_evicted_out=gone)
+        ogone = self.orc.evict_apply(layer, seq_ids, scores, frac)
+        np.testing.assert_array_equal(gone.cpu().numpy().astype(np.int64), ogone)
+        return ogone
+
     def attend(self, layer, seq_ids, q, scale=None):
         c = self.cfg
         if scale is None:

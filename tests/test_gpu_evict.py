@@ -1,0 +1,114 @@
+"""Removal step of the budgeted eviction (appendix "Eviction policy implementation") on the GPU
+against the oracle, through the C ABI: which entries go, in-place compaction of the rows, page
+release order, and that the cache keeps working afterwards (attention, promotion, reuse of pages)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_17452_amd as wg
+from harness import Pair, rand_tokens
+
+pytestmark = pytest.mark.gpu
+
+
+def _scores(rng, pair, layer, seq_ids, kind, extra=3):
+    Hk = pair.cfg.n_kv_heads
+    N = max(pair.orc.global_len(s, layer, h) for s in seq_ids for h in range(Hk))
+    shape = (len(seq_ids) * Hk, N + extra)
+    if kind == "uniform":
+        return rng.random(shape).astype(np.float32)
+    if kind == "ties":                       # eight distinct values: every cut falls inside a tie
+        return (rng.integers(0, 8, shape) / 8.0).astype(np.float32)
+    if kind == "signed":                     # negative numbers, zeros of both signs, an infinity
+        x = rng.standard_normal(shape).astype(np.float32)
+        x[:, ::7] = 0.0
+        x[:, 3::11] = -0.0
+        x[:, 5::13] = np.inf
+        return x
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("dtype,d,P,W,T,frac,kind", [
+    (wg.F32, 64, 4, 8, 300, 0.1, "uniform"),
+    (wg.BF16, 128, 16, 32, 700, 0.1, "ties"),
+    (wg.BF16, 128, 16, 256, 3000, 0.5, "uniform"),     # more than one tile of 1024 entries per head
+    (wg.BF16, 64, 8, 16, 500, 0.37, "signed"),
+    (wg.F32, 128, 2, 4, 200, 1.0, "uniform"),          # everything goes
+    (wg.BF16, 128, 16, 64, 400, 0.0, "uniform"),       # nothing goes
+])
+def test_evict_apply_state_and_attention(dtype, d, P, W, T, frac, kind):
+    rng = np.random.default_rng(T + d)
+    Hq, Hk, L, B = 8, 2, 2, 3
+    max_gp = T // P + 8
+    n_pages = B * L * Hk * (max_gp + -(-W // P)) + 16
+    pair = Pair(L, Hq, Hk, d, dtype, P, W, B, max_gp, n_pages, max_call_seqs=B, max_call_tokens=B * T)
+    lens = [T, T - 57, T // 2]
+    for layer in range(L):
+        k, v, g = rand_tokens(rng, sum(lens), Hk, d, pair.tdt, rates=[0.7, 0.35])
+        pair.prefill(layer, [0, 1, 2], lens, k, v, g, 0.5)
+    pair.check_state()
+    used_before = n_pages - pair.orc.free_top
+    # evict on layer 1 for two of the sequences, in an order that is not the slot order
+    seqs = [2, 0]
+    sc = _scores(rng, pair, 1, seqs, kind)
+    gone = pair.evict(1, seqs, sc, frac)
+    n_before = [g0 + pair.orc.global_len(s, 1, h) for (s, h), g0 in zip([(s, h) for s in seqs for h in range(Hk)], gone)]
+    assert list(gone) == [int(math.floor(float(np.float32(frac)) * n)) for n in n_before]
+    pair.check_state()
+    assert n_pages - pair.orc.free_top <= used_before
+    q = torch.from_numpy(rng.standard_normal((3, Hq, d)).astype(np.float32)).to(pair.tdt)
+    pair.check_attend(1, [0, 1, 2], q)
+    # the cache goes on: decode steps promote into the packed caches and reuse the released pages
+    for step in range(2 * P + 3):
+        k, v, g = rand_tokens(rng, 3, Hk, d, pair.tdt, rates=[0.9, 0.6])
+        pair.decode(1, [0, 1, 2], k, v, g, 0.5)
+    pair.check_state()
+    pair.check_attend(1, [0, 1, 2], q)
+    # a second round on everything, then free a sequence
+    sc = _scores(rng, pair, 1, [0, 1, 2], "ties")
+    pair.evict(1, [0, 1, 2], sc, 0.25)
+    pair.check_state()
+    pair.check_attend(1, [1, 2], q[:2])
+    pair.pool.free_seq(0)
+    pair.orc.free_seq(0)
+    pair.check_state()
+
+
+def test_evict_apply_many_entries_and_units():
+    """64 heads of about 10K entries (one layer of a long-context batch), 10 % removed."""
+    rng = np.random.default_rng(99)
+    Hq, Hk, d, P, W, B, T = 32, 8, 128, 16, 256, 8, 16000
+    max_gp = T // P + 4
+    n_pages = B * Hk * (max_gp + W // P) + 64
+    pair = Pair(1, Hq, Hk, d, wg.BF16, P, W, B, max_gp, n_pages, max_call_seqs=B, max_call_tokens=T)
+    for s in range(B):
+        k, v, g = rand_tokens(rng, T - 100 * s, Hk, d, pair.tdt, rates=list(np.linspace(0.3, 0.9, Hk)))
+        pair.prefill(0, [s], [T - 100 * s], k, v, g, 0.5)
+    seqs = list(range(B))
+    pair.pool.status()      # exact lengths on the host, so that score rows need not cover the worst case
+    sc = _scores(rng, pair, 0, seqs, "uniform")
+    gone = pair.evict(0, seqs, sc, 0.1)
+    assert gone.min() > 300 and gone.max() > 1200
+    pair.check_state()
+    q = torch.from_numpy(rng.standard_normal((B, Hq, d)).astype(np.float32)).to(pair.tdt)
+    pair.check_attend(0, seqs, q)
+
+
+def test_evict_apply_rejects_bad_arguments():
+    rng = np.random.default_rng(1)
+    pair = Pair(1, 4, 2, 64, wg.F32, 4, 8, 2, 64, 400, max_call_seqs=2, max_call_tokens=256)
+    k, v, g = rand_tokens(rng, 100, 2, 64, pair.tdt)
+    pair.prefill(0, [0], [100], k, v, g, 0.3)
+    dev = pair.dev
+    good = torch.zeros((2, 128), dtype=torch.float32, device=dev)
+    with pytest.raises(wg.WgkvError):
+        pair.pool.evict_apply(0, [0], good, 1.5)
+    with pytest.raises(wg.WgkvError):
+        pair.pool.evict_apply(0, [0], good, float("nan"))
+    with pytest.raises(wg.WgkvError):                      # rows shorter than what a head may hold
+        pair.pool.evict_apply(0, [0], torch.zeros((2, 8), dtype=torch.float32, device=dev), 0.1)
+    with pytest.raises(wg.WgkvError):
+        pair.pool.evict_apply(0, [0, 0], torch.zeros((4, 128), dtype=torch.float32, device=dev), 0.1)
+    pair.check_state()                                      # nothing happened
