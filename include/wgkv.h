@@ -189,6 +189,28 @@ int wgkv_attend(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *s
                 const void *v_chunk_dev, const float *g_chunk_dev, float tau, float scale,
                 float *out_dev, void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
 
+/* Appendix "Eviction policy implementation", the three scoring steps, for every kv head
+ * of the given sequences (distinct ids) over the N entries of its global cache:
+ *   A = Softmax(Q_obs K^T * scale) per query row (n_obs positions x the heads of the group),
+ *   S_raw[j] = sum over positions of the maximum over the group of A[.][j],
+ *   S = MaxPool(S_raw, pool_w) along the cache order.
+ * Readings: K is the global cache alone (the only entries eviction can take; all of them
+ * are older than the window, so no mask applies) and each softmax is normalised over
+ * these N entries; the pooling window is centred and clipped at both ends; pool_w odd.
+ *   q_obs_dev : [n_seqs][n_obs][n_q_heads][head_dim] of cfg.dtype, the queries of the
+ *               last n_obs positions of each sequence (the caller keeps them)
+ *   scores_raw_out_dev, scores_out_dev : two distinct float buffers [n_seqs * n_kv_heads][stride];
+ *               entries [0, N) of each row are written, the rest is left alone; stride must
+ *               cover the host's upper bound of every head's length (see wgkv_status)
+ * fp32 arithmetic; sums run in a fixed order, so the result repeats run to run.  The
+ * workspace from wgkv_query_sizes covers n_obs <= 256 (n_units * n_obs * group * 8 bytes
+ * are needed); n_obs <= 4096, pool_w <= 255, the group size must divide 64.
+ * Errors: INVALID_ARG, WORKSPACE, HIP. */
+int wgkv_evict_scores(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                      const void *q_obs_dev, int32_t n_obs, float scale, int32_t pool_w,
+                      float *scores_raw_out_dev, float *scores_out_dev, int64_t stride,
+                      void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
+
 /* Appendix "Eviction policy implementation", the removal step: every kv head of the
  * given sequences (distinct ids) drops the floor(frac * N) entries of its global cache
  * with the lowest scores, N its current length ("the bottom 10 %": frac = 0.1; each

@@ -11,7 +11,7 @@ F32, BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
-    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_evict_apply", "wgkv_free_seq",
+    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_free_seq",
     "wgkv_status", "wgkv_set_profile_events", "wgkv_destroy",
 ]
 
@@ -86,6 +86,7 @@ def load_library():
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
+    L.wgkv_evict_scores.argtypes = [vp, i32, i32, pi32, vp, i32, f32, i32, vp, vp, i64, vp, sz, vp]
     L.wgkv_evict_apply.argtypes = [vp, i32, i32, pi32, vp, i64, f32, vp, vp, sz, vp]
     L.wgkv_free_seq.argtypes = [vp, i32, vp]
     L.wgkv_status.argtypes = [vp, vp, C.POINTER(i64), C.POINTER(i32)]
@@ -205,6 +206,19 @@ class Pool:
                                   _ptr(k_chunk), _ptr(v_chunk), _ptr(g_chunk), tau, scale, _ptr(out),
                                   _ptr(self.workspace), self.workspace.numel(), _stream()), "wgkv_attend")
         return out
+
+    def evict_scores(self, layer, seq_ids, q_obs, scale, stride, pool_w=5):
+        """wgkv_evict_scores: q_obs [len(seq_ids), n_obs, n_q_heads, d]; returns (raw, pooled), float32
+        [len(seq_ids) * n_kv_heads, stride], rows valid up to each head's global length."""
+        import torch
+        assert q_obs.is_cuda and q_obs.is_contiguous() and q_obs.dim() == 4 and q_obs.shape[0] == len(seq_ids)
+        n_units = len(seq_ids) * self.cfg.n_kv_heads
+        raw = torch.zeros((n_units, stride), dtype=torch.float32, device=self.device)
+        out = torch.zeros((n_units, stride), dtype=torch.float32, device=self.device)
+        _check(self.L.wgkv_evict_scores(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(q_obs), q_obs.shape[1],
+                                        scale, pool_w, _ptr(raw), _ptr(out), stride, _ptr(self.workspace),
+                                        self.workspace.numel(), _stream()), "wgkv_evict_scores")
+        return raw, out
 
     def evict_apply(self, layer, seq_ids, scores, frac, n_evicted_out=None):
         """wgkv_evict_apply: scores float32 [len(seq_ids) * n_kv_heads, stride] on the device."""

@@ -1,0 +1,223 @@
+// Importance scores for budgeted eviction (appendix "Eviction policy implementation"),
+// per (sequence, kv head), over the N entries of the head's global cache and the queries
+// of an observation window (n_obs positions x G query heads of the group):
+//   (1) A = Softmax(Q_obs K^T * scale), one softmax per query row over the N entries,
+//   (2) S_raw_j = sum_i max_g A[(i,g)][j],
+//   (3) S = MaxPool(S_raw, pool_w), centred, clipped at the ends of the cache.
+// A softmax row needs its maximum and its denominator before any weight is final, so the
+// keys are swept twice:
+//   stats pass  : block = (unit, 64 query rows), all keys   -> (max, denominator) per row
+//   weight pass : block = (unit, 64 keys), all query rows   -> S_raw of its keys
+//   pool pass   : S from S_raw
+// Every sum runs in a fixed order, so the scores (and what gets evicted) repeat run to run.
+#include "wgkv_dev.h"
+
+namespace wgkv {
+
+constexpr int kEsTile = 64;   // rows / keys per tile
+constexpr int kEsDk = 32;     // slice of head_dim staged per step
+
+struct EvictScoreArgs {
+    int layer;
+    int n_obs;
+    int pool_w;
+    float scale_log2e;
+    const char *q;        // [n_seqs][n_obs][Hq][d]
+    float *stats;         // workspace [n_units][n_obs * G][2]
+    float *raw;           // [n_units][stride]
+    float *out;           // [n_units][stride]
+    long long stride;
+};
+
+template <int DT>
+__device__ __forceinline__ float es_ld(const char *p, size_t i) {
+    return DT == WGKV_F32 ? reinterpret_cast<const float *>(p)[i]
+                          : __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(p)[i] << 16);
+}
+
+// acc[i][k] = q_row(row0 + 4 ty + i) . key(key0 + tx + 16 k), unscaled.  Rows / keys past the end count as zero.
+template <int DT>
+__device__ __forceinline__ void es_tile(const View &pv, const EvictScoreArgs &a, int um, int b, int h, int row0,
+                                        int key0, int n_rows, int N, float (&acc)[4][4],
+                                        float (*sq)[kEsDk + 1], float (*sk)[kEsDk + 1]) {
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int k = 0; k < 4; k++) acc[i][k] = 0.f;
+    for (int d0 = 0; d0 < pv.d; d0 += kEsDk) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < kEsTile * kEsDk; e += 256) {
+            const int r = e / kEsDk, c = e % kEsDk;
+            float qv = 0.f, kv = 0.f;
+            if (d0 + c < pv.d) {
+                const int row = row0 + r, key = key0 + r;
+                if (row < n_rows) {
+                    const int i = row / pv.G, g = row % pv.G;
+                    qv = es_ld<DT>(a.q, (((size_t)b * a.n_obs + i) * pv.Hq + (size_t)h * pv.G + g) * pv.d + d0 + c);
+                }
+                if (key < N) {
+                    const char *pg = page_ptr(pv, pv.global_pt[(size_t)um * pv.maxgp + (key >> pv.logP)]) +
+                                     (size_t)(key & (pv.P - 1)) * pv.row_bytes;
+                    kv = es_ld<DT>(pg, d0 + c);
+                }
+            }
+            sq[r][c] = qv;
+            sk[r][c] = kv;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int c = 0; c < kEsDk; c++) {
+            float qa[4], kb[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) qa[i] = sq[4 * ty + i][c];
+#pragma unroll
+            for (int k = 0; k < 4; k++) kb[k] = sk[tx + 16 * k][c];
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int k = 0; k < 4; k++) acc[i][k] = fmaf(qa[i], kb[k], acc[i][k]);
+        }
+    }
+}
+
+// (max, denominator) of every softmax row, in the base-2 exponent domain (score * scale * log2 e)
+template <int DT>
+__global__ __launch_bounds__(256) void evict_stats_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
+    __shared__ float sq[kEsTile][kEsDk + 1], sk[kEsTile][kEsDk + 1];
+    const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
+    const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+    const int N = pv.global_len[um], n_rows = a.n_obs * pv.G;
+    const int row0 = blockIdx.x * kEsTile;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    float m[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) { m[i] = -INFINITY; l[i] = 0.f; }
+    for (int key0 = 0; key0 < N; key0 += kEsTile) {
+        float acc[4][4];
+        es_tile<DT>(pv, a, um, b, h, row0, key0, n_rows, N, acc, sq, sk);
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            float x[4], mt = -INFINITY;
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                x[k] = (key0 + tx + 16 * k < N) ? acc[i][k] * a.scale_log2e : -INFINITY;
+                mt = fmaxf(mt, x[k]);
+            }
+            // the 16 lanes tx = 0..15 of a row sit in one aligned group of 16 lanes
+            mt = fmaxf(mt, __shfl_xor(mt, 1));
+            mt = fmaxf(mt, __shfl_xor(mt, 2));
+            mt = fmaxf(mt, __shfl_xor(mt, 4));
+            mt = fmaxf(mt, __shfl_xor(mt, 8));
+            const float mn = fmaxf(m[i], mt);  // finite: every tile has at least one key
+            float ps = 0.f;
+#pragma unroll
+            for (int k = 0; k < 4; k++) ps += exp2f(x[k] - mn);
+            ps = group_sum<16>(ps);
+            l[i] = l[i] * exp2f(m[i] - mn) + ps;
+            m[i] = mn;
+        }
+    }
+    if (tx == 0)
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int row = row0 + 4 * ty + i;
+            if (row < n_rows) {
+                a.stats[((size_t)u * n_rows + row) * 2 + 0] = m[i];
+                a.stats[((size_t)u * n_rows + row) * 2 + 1] = l[i];
+            }
+        }
+}
+
+// S_raw of 64 keys: all query rows in tiles of 64, weights through LDS for the maximum over the
+// group and the sum over the observation window
+template <int DT>
+__global__ __launch_bounds__(256) void evict_weights_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
+    __shared__ float sq[kEsTile][kEsDk + 1], sk[kEsTile][kEsDk + 1];
+    __shared__ float sp[kEsTile][kEsTile + 1];   // weights of a tile: [row][key]
+    __shared__ float s_part[4][kEsTile];
+    const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
+    const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+    const int N = pv.global_len[um], n_rows = a.n_obs * pv.G;
+    const int key0 = blockIdx.x * kEsTile;
+    if (key0 >= N) return;  // block-uniform
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int kj = threadIdx.x & 63, part = threadIdx.x >> 6;  // role in the reduction: key, quarter of the rows
+    float sum = 0.f;
+    for (int row0 = 0; row0 < n_rows; row0 += kEsTile) {
+        float acc[4][4];
+        es_tile<DT>(pv, a, um, b, h, row0, key0, n_rows, N, acc, sq, sk);
+        __syncthreads();  // the previous tile's reduction is done with sp
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int row = row0 + 4 * ty + i;
+            float mr = 0.f, inv = 0.f;
+            if (row < n_rows) {
+                mr = a.stats[((size_t)u * n_rows + row) * 2 + 0];
+                inv = 1.0f / a.stats[((size_t)u * n_rows + row) * 2 + 1];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+                sp[4 * ty + i][tx + 16 * k] = (row < n_rows) ? exp2f(acc[i][k] * a.scale_log2e - mr) * inv : 0.f;
+        }
+        __syncthreads();
+        // rows of a tile are (observation row, head of the group) with the heads adjacent
+        for (int il = part; il < kEsTile / pv.G; il += 4) {
+            float best = sp[il * pv.G][kj];
+            for (int g = 1; g < pv.G; g++) best = fmaxf(best, sp[il * pv.G + g][kj]);
+            sum += best;
+        }
+    }
+    s_part[part][kj] = sum;
+    __syncthreads();
+    if (part == 0 && key0 + kj < N)
+        a.raw[(size_t)u * a.stride + key0 + kj] = ((s_part[0][kj] + s_part[1][kj]) + s_part[2][kj]) + s_part[3][kj];
+}
+
+__global__ __launch_bounds__(256) void evict_pool_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
+    const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
+    const int N = pv.global_len[unit_meta(pv, cs.sid[b], a.layer, h)];
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= N) return;
+    const float *raw = a.raw + (size_t)u * a.stride;
+    float best = raw[j];
+    for (int jj = max(0, j - a.pool_w / 2); jj <= min(N - 1, j + a.pool_w / 2); jj++) best = fmaxf(best, raw[jj]);
+    a.out[(size_t)u * a.stride + j] = best;
+}
+
+size_t evict_scores_ws_bytes(const View &pv, int n_units, int n_obs) {
+    return (((size_t)n_units * n_obs * pv.G * 2 * sizeof(float)) + 255) / 256 * 256;
+}
+
+// max_len: upper bound of the units' lengths (sizes the grids; blocks past a unit's end return at once)
+hipError_t launch_evict_scores(const View &pv, const CallSeqs &cs, int layer, const void *q_obs, int n_obs,
+                               float scale, int pool_w, float *raw, float *out, int64_t stride, int64_t max_len,
+                               void *ws, hipStream_t st) {
+    const int n_units = cs.n * pv.Hkv;
+    if (max_len <= 0) return hipSuccess;
+    EvictScoreArgs a;
+    a.layer = layer;
+    a.n_obs = n_obs;
+    a.pool_w = pool_w;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.q = (const char *)q_obs;
+    a.stats = (float *)ws;
+    a.raw = raw;
+    a.out = out;
+    a.stride = stride;
+    const int n_rows = n_obs * pv.G;
+    const dim3 g_stats((n_rows + kEsTile - 1) / kEsTile, n_units);
+    const dim3 g_keys((unsigned)((max_len + kEsTile - 1) / kEsTile), n_units);
+    const dim3 g_pool((unsigned)((max_len + 255) / 256), n_units);
+    if (pv.dtype == WGKV_F32) {
+        hipLaunchKernelGGL(evict_stats_kernel<WGKV_F32>, g_stats, dim3(256), 0, st, pv, cs, a);
+        hipLaunchKernelGGL(evict_weights_kernel<WGKV_F32>, g_keys, dim3(256), 0, st, pv, cs, a);
+    } else {
+        hipLaunchKernelGGL(evict_stats_kernel<WGKV_BF16>, g_stats, dim3(256), 0, st, pv, cs, a);
+        hipLaunchKernelGGL(evict_weights_kernel<WGKV_BF16>, g_keys, dim3(256), 0, st, pv, cs, a);
+    }
+    hipLaunchKernelGGL(evict_pool_kernel, g_pool, dim3(256), 0, st, pv, cs, a);
+    return hipGetLastError();
+}
+
+}  // namespace wgkv

@@ -21,6 +21,10 @@ hipError_t launch_decode_step(const View &pv, const CallSeqs &cs, int layer, flo
                               hipStream_t st);
 hipError_t launch_free_seq(const View &pv, int sid, hipStream_t st);
 size_t evict_ws_bytes(int n_units);
+size_t evict_scores_ws_bytes(const View &pv, int n_units, int n_obs);
+hipError_t launch_evict_scores(const View &pv, const CallSeqs &cs, int layer, const void *q_obs, int n_obs,
+                               float scale, int pool_w, float *raw, float *out, int64_t stride, int64_t max_len,
+                               void *ws, hipStream_t st);
 hipError_t launch_evict_apply(const View &pv, const CallSeqs &cs, int layer, const float *scores,
                               int64_t stride, float frac, int32_t *n_evicted, void *ws, hipStream_t st);
 size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid);
@@ -172,7 +176,9 @@ int wgkv_query_sizes(const wgkv_config *cfg, int32_t max_call_seqs, int64_t max_
         size_t c = attend_prefill_ws_bytes(v, max_call_seqs, max_call_tokens);
         size_t m = a > b ? a : b;
         m = m > c ? m : c;
-        const size_t e = evict_ws_bytes(max_call_seqs * cfg->n_kv_heads);
+        size_t e = evict_ws_bytes(max_call_seqs * cfg->n_kv_heads);
+        const size_t e2 = evict_scores_ws_bytes(v, max_call_seqs * cfg->n_kv_heads, 256);  // observation windows up to 256
+        e = e > e2 ? e : e2;
         *workspace_bytes = align256(m > e ? m : e);
     }
     return WGKV_OK;
@@ -434,6 +440,39 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
         return WGKV_ERR_HIP;
     if (p->ev1 && hipEventRecord(p->ev1, st) != hipSuccess) return WGKV_ERR_HIP;
     return WGKV_OK;
+}
+
+int wgkv_evict_scores(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                      const void *q_obs_dev, int32_t n_obs, float scale, int32_t pool_w,
+                      float *scores_raw_out_dev, float *scores_out_dev, int64_t stride,
+                      void *workspace_dev, size_t workspace_bytes, wgkv_stream stream) {
+    int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    if (!q_obs_dev || !scores_raw_out_dev || !scores_out_dev || scores_raw_out_dev == scores_out_dev ||
+        !workspace_dev || n_obs < 1 || n_obs > 4096 || pool_w < 1 || pool_w > 255 || pool_w % 2 == 0 ||
+        !std::isfinite(scale) || stride < 0 || 64 % p->view.G != 0)
+        return WGKV_ERR_INVALID_ARG;
+    const wgkv_config &c = p->cfg;
+    const int H = c.n_kv_heads;
+    if (workspace_bytes < evict_scores_ws_bytes(p->view, n_seqs * H, n_obs)) return WGKV_ERR_WORKSPACE;
+    CallSeqs cs;
+    memset(&cs, 0, sizeof(cs));
+    cs.n = n_seqs;
+    int64_t max_len = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        const size_t sl = (size_t)seq_ids_host[b] * c.n_layers + layer;
+        cs.sid[b] = seq_ids_host[b];
+        cs.t0[b] = p->seq_len_h[sl];
+        for (int h = 0; h < H; h++) {
+            if (p->g_ub[sl * H + h] > stride) return WGKV_ERR_INVALID_ARG;  // a row must cover what a head may hold
+            max_len = max_len > p->g_ub[sl * H + h] ? max_len : p->g_ub[sl * H + h];
+        }
+    }
+    return launch_evict_scores(p->view, cs, layer, q_obs_dev, n_obs, scale, pool_w, scores_raw_out_dev,
+                               scores_out_dev, stride, max_len, workspace_dev,
+                               (hipStream_t)stream) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
 }
 
 int wgkv_evict_apply(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,

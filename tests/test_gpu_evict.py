@@ -112,3 +112,88 @@ def test_evict_apply_rejects_bad_arguments():
     with pytest.raises(wg.WgkvError):
         pair.pool.evict_apply(0, [0, 0], torch.zeros((4, 128), dtype=torch.float32, device=dev), 0.1)
     pair.check_state()                                      # nothing happened
+
+
+# ---- the scoring steps ----
+# fp32 products of exactly representable inputs, fp32 exp2 and sums of up to n_obs weights in [0, 1]:
+# relative error of a score ~1e-6 per operation; scores are at most n_obs.
+SCORE_RTOL = 2e-5
+
+
+def _check_scores(pair, layer, seqs, q_obs, scale, pool_w):
+    Hk = pair.cfg.n_kv_heads
+    N = [pair.orc.global_len(s, layer, h) for s in seqs for h in range(Hk)]
+    stride = max(N) + 5
+    raw, out = pair.pool.evict_scores(layer, seqs, q_obs.to(pair.dev), scale, stride, pool_w=pool_w)
+    raw, out = raw.cpu().numpy(), out.cpu().numpy()
+    worst = 0.0
+    refs = np.zeros_like(out)
+    for b, s in enumerate(seqs):
+        for h in range(Hk):
+            u = b * Hk + h
+            r_ref, s_ref = pair.orc.evict_scores(layer, s, h, q_obs[b].float().numpy(), scale, pool_w=pool_w)
+            n = N[u]
+            assert np.all(raw[u, n:] == 0) and np.all(out[u, n:] == 0)          # rows past the length are left alone
+            if n:
+                tol = SCORE_RTOL * max(1.0, float(r_ref.max()))
+                assert np.abs(raw[u, :n] - r_ref).max() <= tol
+                assert np.abs(out[u, :n] - s_ref).max() <= tol
+                worst = max(worst, np.abs(out[u, :n] - s_ref).max() / max(1.0, float(r_ref.max())))
+                refs[u, :n] = s_ref
+    return out, refs, N, worst
+
+
+@pytest.mark.parametrize("dtype,Hq,Hk,d,P,W,T,n_obs,pool_w", [
+    (wg.F32, 8, 2, 64, 4, 8, 300, 16, 5),
+    (wg.BF16, 8, 2, 128, 16, 32, 500, 32, 5),
+    (wg.BF16, 4, 4, 128, 16, 16, 200, 7, 3),          # group of one, rows not a multiple of the tile
+    (wg.BF16, 16, 2, 64, 8, 16, 333, 24, 1),          # group of eight, no pooling
+    (wg.F32, 4, 2, 128, 2, 4, 150, 40, 9),
+])
+def test_evict_scores_match_fp64(dtype, Hq, Hk, d, P, W, T, n_obs, pool_w):
+    rng = np.random.default_rng(T * 3 + n_obs)
+    B = 2
+    max_gp = T // P + 4
+    pair = Pair(1, Hq, Hk, d, dtype, P, W, B, max_gp, B * Hk * (max_gp + -(-W // P)) + 8, max_call_seqs=B,
+                max_call_tokens=B * T)
+    lens = [T, T // 3]
+    k, v, g = rand_tokens(rng, sum(lens), Hk, d, pair.tdt, rates=list(np.linspace(0.8, 0.3, Hk)))
+    pair.prefill(0, [0, 1], lens, k, v, g, 0.5)
+    pair.pool.status()
+    q_obs = torch.from_numpy(rng.standard_normal((B, n_obs, Hq, d)).astype(np.float32)).to(pair.tdt)
+    scale = 1.0 / math.sqrt(d)
+    _, _, N, worst = _check_scores(pair, 0, [1, 0], q_obs, scale, pool_w)
+    assert min(N) > 10
+    pair.check_state()          # scoring changes nothing
+
+
+def test_evict_scores_then_apply():
+    """Both steps chained on each side: the GPU removes by its fp32 scores, the oracle by its own fp64
+    scores (rounded to fp32, its input format), and the states must then agree bit for bit."""
+    rng = np.random.default_rng(2024)
+    Hq, Hk, d, P, W, T, n_obs = 8, 2, 128, 16, 64, 900, 48
+    max_gp = T // P + 4
+    pair = Pair(1, Hq, Hk, d, wg.BF16, P, W, 1, max_gp, Hk * (max_gp + W // P) + 8, max_call_seqs=1, max_call_tokens=T)
+    k, v, g = rand_tokens(rng, T, Hk, d, pair.tdt, rates=[0.7, 0.5])
+    pair.prefill(0, [0], [T], k, v, g, 0.5)
+    pair.pool.status()
+    q_obs = torch.from_numpy(rng.standard_normal((1, n_obs, Hq, d)).astype(np.float32)).to(pair.tdt)
+    scale = 1.0 / math.sqrt(d)
+    out, refs, N, _ = _check_scores(pair, 0, [0], q_obs, scale, 5)
+    frac = 0.1
+    for u in range(Hk):
+        # Max-pooling makes runs of exactly equal scores on both sides (copies of one value), which the
+        # common tie rule settles; what could differ is the order of two distinct values closer than the
+        # rounding error.  The seeded input must not have that at the cut: the entries that a stable
+        # sort of either side's scores puts below the cut are the same.
+        n_e = int(math.floor(float(np.float32(frac)) * N[u]))
+        low_gpu = set(np.argsort(out[u, :N[u]], kind="stable")[:n_e])
+        low_orc = set(np.argsort(refs[u, :N[u]].astype(np.float32), kind="stable")[:n_e])
+        assert n_e > 10 and low_gpu == low_orc, "the cut falls into a near-tie of distinct scores: pick another seed"
+    gone = torch.zeros((Hk,), dtype=torch.int32, device=pair.dev)
+    pair.pool.evict_apply(0, [0], torch.from_numpy(out).to(pair.dev), frac, n_evicted_out=gone)
+    ogone = pair.orc.evict_apply(0, [0], refs.astype(np.float32), frac)
+    np.testing.assert_array_equal(gone.cpu().numpy(), ogone)
+    pair.check_state()
+    q = torch.from_numpy(rng.standard_normal((1, Hq, d)).astype(np.float32)).to(pair.tdt)
+    pair.check_attend(0, [0], q)
