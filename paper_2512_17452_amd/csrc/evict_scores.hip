@@ -174,6 +174,171 @@ __global__ __launch_bounds__(256) void evict_weights_kernel(View pv, CallSeqs cs
         a.raw[(size_t)u * a.stride + key0 + kj] = ((s_part[0][kj] + s_part[1][kj]) + s_part[2][kj]) + s_part[3][kj];
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Matrix-core versions of the two sweeps for the shape of the paper's models (bf16, head_dim 128,
+// group of 4, n_obs a multiple of 8).  Scores are formed transposed, S^T = K Q^T with
+// v_mfma_f32_32x32x16_bf16: rows = 32 keys of a tile staged in LDS, columns = 32 query rows of a
+// wave, ordered (observation row, head) with the four heads of a row adjacent.  A lane then owns
+// one query row: its maximum, denominator and normalisation are per-lane scalars, the maximum
+// over the group is a maximum over the four lanes of a quad, and the sum over the window is a sum
+// over quads and waves.
+typedef __attribute__((ext_vector_type(8))) __bf16 es_bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float es_f32x16_t;
+constexpr int kEmD = 128, kEmKT = 32, kEmRow = 272;  // bytes per key row in LDS: 256 + 16 of padding
+
+// the eight operand slices of a lane's query row (column `col` of the unit), zeros past the end
+__device__ __forceinline__ void em_load_q(const View &pv, const EvictScoreArgs &a, int b, int h, int col, int n_cols,
+                                          int half, es_bf16x8_t (&qv)[8]) {
+    const int cc = min(col, n_cols - 1), i = cc >> 2, g = cc & 3;
+    const char *qp = a.q + (((size_t)b * a.n_obs + i) * pv.Hq + (size_t)h * 4 + g) * (kEmD * 2);
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) qv[ks] = *reinterpret_cast<const es_bf16x8_t *>(qp + (ks * 16 + half * 8) * 2);
+}
+
+__global__ __launch_bounds__(512) void evict_stats_mfma_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
+    __shared__ __attribute__((aligned(16))) char s_k[2][kEmKT * kEmRow];
+    const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
+    const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+    const int N = pv.global_len[um], n_cols = a.n_obs * 4;
+    if (N == 0) return;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 31, half = lane >> 5;
+    const int col = (blockIdx.x * 8 + wave) * 32 + n;
+    es_bf16x8_t qv[8];
+    em_load_q(pv, a, b, h, col, n_cols, half, qv);
+    // staging: thread -> (key of the tile, 16-byte chunk); page ids in a per-lane register
+    const int ld_key = threadIdx.x >> 4, ld_c = threadIdx.x & 15;
+    int pt_base = 0;
+    int ptreg = (lane < pv.maxgp) ? pv.global_pt[(size_t)um * pv.maxgp + lane] : 0;
+    uint4 kreg;
+    auto fetch = [&](int t) __attribute__((always_inline)) {
+        if (((t * kEmKT + kEmKT - 1) >> pv.logP) >= pt_base + 64) {
+            pt_base = (t * kEmKT) >> pv.logP;
+            ptreg = (pt_base + lane < pv.maxgp) ? pv.global_pt[(size_t)um * pv.maxgp + pt_base + lane] : 0;
+        }
+        const int idx = min(t * kEmKT + ld_key, N - 1);
+        const int pg = __shfl(ptreg, (idx >> pv.logP) - pt_base);
+        kreg = *reinterpret_cast<const uint4 *>(page_ptr(pv, pg) + (size_t)(idx & (pv.P - 1)) * (kEmD * 2) + ld_c * 16);
+    };
+    const int n_tiles = (N + kEmKT - 1) / kEmKT;
+    fetch(0);
+    *reinterpret_cast<uint4 *>(&s_k[0][ld_key * kEmRow + ld_c * 16]) = kreg;
+    __syncthreads();
+    float m = -INFINITY, l = 0.f;
+    for (int t = 0; t < n_tiles; t++) {
+        const int buf = t & 1;
+        if (t + 1 < n_tiles) fetch(t + 1);
+        es_f32x16_t s;
+#pragma unroll
+        for (int c = 0; c < 16; c++) s[c] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) {
+            const es_bf16x8_t ka = *reinterpret_cast<const es_bf16x8_t *>(&s_k[buf][n * kEmRow + (ks * 16 + half * 8) * 2]);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qv[ks], s, 0, 0, 0);
+        }
+        // register 4j+i of a lane holds key 8j + 4*half + i of the tile
+        float x[16], mt = -INFINITY;
+        const int k0 = t * kEmKT + 4 * half;
+#pragma unroll
+        for (int c = 0; c < 16; c++) {
+            x[c] = (k0 + 8 * (c >> 2) + (c & 3) < N) ? s[c] * a.scale_log2e : -INFINITY;
+            mt = fmaxf(mt, x[c]);
+        }
+        const float mn = fmaxf(m, mt);
+        const float ms = mn == -INFINITY ? 0.f : mn;  // this half may hold no valid key of the last tile
+        float ps = 0.f;
+#pragma unroll
+        for (int c = 0; c < 16; c++) ps += exp2f(x[c] - ms);
+        l = l * exp2f(m - ms) + ps;
+        m = mn;
+        if (t + 1 < n_tiles) *reinterpret_cast<uint4 *>(&s_k[buf ^ 1][ld_key * kEmRow + ld_c * 16]) = kreg;
+        __syncthreads();
+    }
+    // the two halves of the wave hold different keys of the same query row
+    const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
+    const float M = fmaxf(m, m2);  // finite: N > 0
+    const float Lsum = l * exp2f(m - M) + l2 * exp2f(m2 - M);
+    if (half == 0 && col < n_cols) {
+        a.stats[((size_t)u * n_cols + col) * 2 + 0] = M;
+        a.stats[((size_t)u * n_cols + col) * 2 + 1] = Lsum;
+    }
+}
+
+constexpr int kEmKeys = 128;  // keys per block of the weight sweep (4 tiles)
+
+__global__ __launch_bounds__(512) void evict_weights_mfma_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
+    __shared__ __attribute__((aligned(16))) char s_k[kEmKeys * kEmRow];
+    __shared__ float s_acc[8][kEmKeys];
+    const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
+    const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+    const int N = pv.global_len[um], n_cols = a.n_obs * 4;
+    const int key0 = blockIdx.x * kEmKeys;
+    if (key0 >= N) return;  // block-uniform
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 31, half = lane >> 5;
+    // the block's keys into LDS, zero rows past the end of the cache
+    for (int e = threadIdx.x; e < kEmKeys * 16; e += 512) {
+        const int key = key0 + (e >> 4), c = e & 15;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (key < N)
+            v = *reinterpret_cast<const uint4 *>(page_ptr(pv, pv.global_pt[(size_t)um * pv.maxgp + (key >> pv.logP)]) +
+                                                 (size_t)(key & (pv.P - 1)) * (kEmD * 2) + c * 16);
+        *reinterpret_cast<uint4 *>(&s_k[(e >> 4) * kEmRow + c * 16]) = v;
+    }
+    __syncthreads();
+    float acc[4][16];
+#pragma unroll
+    for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+        for (int c = 0; c < 16; c++) acc[kt][c] = 0.f;
+    for (int col0 = wave * 32; col0 < n_cols; col0 += 256) {  // wave-uniform
+        const int col = col0 + n;
+        es_bf16x8_t qv[8];
+        em_load_q(pv, a, b, h, col, n_cols, half, qv);
+        const bool live = col < n_cols;
+        const float mr = a.stats[((size_t)u * n_cols + min(col, n_cols - 1)) * 2 + 0];
+        const float inv = live ? 1.0f / a.stats[((size_t)u * n_cols + min(col, n_cols - 1)) * 2 + 1] : 0.f;
+#pragma unroll
+        for (int kt = 0; kt < 4; kt++) {
+            es_f32x16_t s;
+#pragma unroll
+            for (int c = 0; c < 16; c++) s[c] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ks++) {
+                const es_bf16x8_t ka =
+                    *reinterpret_cast<const es_bf16x8_t *>(&s_k[(kt * 32 + n) * kEmRow + (ks * 16 + half * 8) * 2]);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qv[ks], s, 0, 0, 0);
+            }
+#pragma unroll
+            for (int c = 0; c < 16; c++) {
+                float p = exp2f(s[c] * a.scale_log2e - mr) * inv;     // weight of (query row, key)
+                p = fmaxf(p, dpp_f<kDppXor1>(p));                      // maximum over the four heads of the
+                p = fmaxf(p, dpp_f<kDppXor2>(p));                      // observation row: the lanes of a quad
+                acc[kt][c] += p;
+            }
+        }
+    }
+    // every lane of a quad holds the quad's sum; add the eight quads of a half, then the waves
+#pragma unroll
+    for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+        for (int c = 0; c < 16; c++) {
+            float v = acc[kt][c];
+            v += __shfl_xor(v, 4);
+            v += __shfl_xor(v, 8);
+            v += __shfl_xor(v, 16);
+            if (n == 0) s_acc[wave][kt * 32 + 8 * (c >> 2) + 4 * half + (c & 3)] = v;
+        }
+    __syncthreads();
+    if (threadIdx.x < kEmKeys && key0 + threadIdx.x < N) {
+        float v = s_acc[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < 8; w++) v += s_acc[w][threadIdx.x];
+        a.raw[(size_t)u * a.stride + key0 + threadIdx.x] = v;
+    }
+}
+
 __global__ __launch_bounds__(256) void evict_pool_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
     const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
     const int N = pv.global_len[unit_meta(pv, cs.sid[b], a.layer, h)];
@@ -209,7 +374,12 @@ hipError_t launch_evict_scores(const View &pv, const CallSeqs &cs, int layer, co
     const dim3 g_stats((n_rows + kEsTile - 1) / kEsTile, n_units);
     const dim3 g_keys((unsigned)((max_len + kEsTile - 1) / kEsTile), n_units);
     const dim3 g_pool((unsigned)((max_len + 255) / 256), n_units);
-    if (pv.dtype == WGKV_F32) {
+    if (pv.dtype == WGKV_BF16 && pv.d == kEmD && pv.G == 4 && n_obs % 8 == 0) {
+        const dim3 g_stats_m((n_rows + 255) / 256, n_units);
+        const dim3 g_keys_m((unsigned)((max_len + kEmKeys - 1) / kEmKeys), n_units);
+        hipLaunchKernelGGL(evict_stats_mfma_kernel, g_stats_m, dim3(512), 0, st, pv, cs, a);
+        hipLaunchKernelGGL(evict_weights_mfma_kernel, g_keys_m, dim3(512), 0, st, pv, cs, a);
+    } else if (pv.dtype == WGKV_F32) {
         hipLaunchKernelGGL(evict_stats_kernel<WGKV_F32>, g_stats, dim3(256), 0, st, pv, cs, a);
         hipLaunchKernelGGL(evict_weights_kernel<WGKV_F32>, g_keys, dim3(256), 0, st, pv, cs, a);
     } else {

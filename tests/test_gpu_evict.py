@@ -149,6 +149,8 @@ def _check_scores(pair, layer, seqs, q_obs, scale, pool_w):
     (wg.BF16, 4, 4, 128, 16, 16, 200, 7, 3),          # group of one, rows not a multiple of the tile
     (wg.BF16, 16, 2, 64, 8, 16, 333, 24, 1),          # group of eight, no pooling
     (wg.F32, 4, 2, 128, 2, 4, 150, 40, 9),
+    (wg.BF16, 32, 8, 128, 16, 256, 2500, 256, 5),     # the paper's window of 256 queries, matrix-core path
+    (wg.BF16, 8, 2, 128, 16, 8, 140, 8, 5),           # matrix-core path, caches shorter than a block of keys
 ])
 def test_evict_scores_match_fp64(dtype, Hq, Hk, d, P, W, T, n_obs, pool_w):
     rng = np.random.default_rng(T * 3 + n_obs)
