@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--gate", choices=["linear", "mlp"], default="linear",
                     help="chunked-prefill workload only: the workload's linear gate on the hidden state, or the "
                          "Write-Gate MLP (width 4*head_dim, random weights) on the keys before/after the rotary embedding")
+    ap.add_argument("--evict", action="store_true",
+                    help="time the budgeted eviction (scoring from a 256-query observation window + removal of the "
+                         "lowest 10 %) on one layer of the workload's batch with about 4.5K global entries per head")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM counters)")
     args = ap.parse_args()
@@ -108,6 +111,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = wl.get_config(args.workload)
+    if args.evict:
+        return main_evict(args, cfg, torch, wg, wl, dev)
     if cfg.chunk:
         return main_prefill(args, cfg, torch, wg, wl, dev)
     B, L, Hq, Hk, d, W, P = cfg.batch, cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local, cfg.page_size
@@ -233,6 +238,70 @@ def main():
                    "attend_us_per_layer": roofline.get("kernel_avg_us"),
                    "gpu_ms_per_step": gpu_ms / args.steps, "host_wall_ms_per_step": wall_ms / args.steps},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(res), flush=True)
+
+
+def main_evict(args, cfg, torch, wg, wl, dev):
+    """One layer of the workload's batch, every head filled to a little above the paper's budget of 4096
+    entries, then `--steps` rounds of scoring + removal (each round refills what was removed)."""
+    B, Hq, Hk, d, W, P = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local, cfg.page_size
+    n_obs, frac, target = 256, 0.1, 4500
+    T = 2 * target + W                                   # scores uniform in (0,1), tau 0.5: half is admitted
+    max_gp = T // P + 4
+    pool = wg.Pool(wg.Config(1, Hq, Hk, d, wg.BF16, P, W, B, max_gp, B * Hk * (max_gp + -(-W // P)) + 64), B, T)
+    seqs = list(range(B))
+    gen = torch.Generator(device=dev).manual_seed(cfg.seed)
+
+    def feed(n):
+        for s_ in seqs:
+            k = wl.draw_normal(cfg, "k", (n, Hk, d), device=dev, key=(s_, n))
+            v = wl.draw_normal(cfg, "v", (n, Hk, d), device=dev, key=(s_, n))
+            g = torch.rand((n, Hk), generator=gen, device=dev)
+            pool.prefill_admit(0, [s_], [n], k, v, g, tau=0.5)
+
+    feed(T)
+    q_obs = wl.draw_normal(cfg, "q", (B, n_obs, Hq, d), device=dev)
+    scale = 1.0 / math.sqrt(d)
+    steps = min(args.steps, 16)
+    t_score, t_apply, flops, removed = [], [], [], 0
+    for st in range(args.warmup + steps):
+        pool.status()
+        gl = pool.meta()["global_len"][:, 0, :].cpu().numpy().astype(np.int64)
+        stride = int(gl.max()) + 16
+        raw = torch.empty((B * Hk, stride), dtype=torch.float32, device=dev)
+        out = torch.empty_like(raw)
+        gone = torch.zeros((B * Hk,), dtype=torch.int32, device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        wg.binding._check(pool.L.wgkv_evict_scores(pool.h, 0, B, wg.binding._ids(seqs), wg.binding._ptr(q_obs), n_obs, scale, 5,
+                                                   wg.binding._ptr(raw), wg.binding._ptr(out), stride,
+                                                   wg.binding._ptr(pool.workspace), pool.workspace.numel(),
+                                                   wg.binding._stream()), "wgkv_evict_scores")
+        ev[1].record()
+        pool.evict_apply(0, seqs, out, frac, n_evicted_out=gone)
+        ev[2].record()
+        torch.cuda.synchronize()
+        if st >= args.warmup:
+            t_score.append(ev[0].elapsed_time(ev[1]))
+            t_apply.append(ev[1].elapsed_time(ev[2]))
+            flops.append(2.0 * 2.0 * d * n_obs * (Hq // Hk) * float(gl.sum()))      # two sweeps of Q K^T
+            removed += int(gone.sum())
+        feed(2 * int(frac * target))                      # grow back to about the same size
+    ms = float(np.mean(t_score) + np.mean(t_apply))
+    tflops = float(np.sum(flops)) / float(np.sum(t_score)) / 1e9
+    res = {
+        "metric": "eviction_round_latency_us (one layer: importance scores from 256 observation queries + removal of the lowest 10 %)",
+        "value": ms * 1e3, "unit": "us/round", "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name + " (one layer, heads filled to ~4.5K global entries)", "batch": B, "kv_heads": Hk,
+                   "q_heads": Hq, "head_dim": d, "page_size": P, "n_obs": n_obs, "pool_w": 5, "frac": frac,
+                   "scores_us": float(np.mean(t_score) * 1e3), "apply_us": float(np.mean(t_apply) * 1e3),
+                   "entries_removed_per_round": removed / steps},
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "evict_stats_mfma_kernel + evict_weights_mfma_kernel"},
+        "cpu_baseline": None,
     }
     print(json.dumps(res), flush=True)
 
