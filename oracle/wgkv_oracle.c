@@ -28,7 +28,10 @@
  *      eviction): importance scores from an observation window and removal of
  *      the lowest-scored entries with compaction and release of pages.
  *
- *  (4) the gates that produce the scores: the linear gate of the chunked-prefill
+ *  (4) read-time page selection with key landmarks over the admitted cache (the
+ *      appendix on the synergy with selection) and attention over the selection.
+ *
+ *  (5) the gates that produce the scores: the linear gate of the chunked-prefill
  *      workload and the Write-Gate MLP of Sec. 3.2 (at the end of the file).
  *
  * All floating-point work is done in double; inputs arrive as float (the
@@ -685,6 +688,116 @@ int orc_evict_apply(orc_state *S, int layer, int n_seqs, const int32_t *seq_ids,
             }
             H->glen = w;
         }
+    return ORC_OK;
+}
+
+/*
+ * Read-time page selection over the admitted cache (appendix "Synergy with KV
+ * Selection": Quest-style selection with key landmarks, the per-page minimum and
+ * maximum key vectors, at a budget of so many KVs per query).  The paper only names
+ * the method; the steps below are the published Quest procedure in the form this
+ * project reads it for grouped-query attention:
+ *   landmarks of page p of a head's global cache: lo_p[e] = min, hi_p[e] = max of
+ *     K_j[e] over the entries j the page holds (the last page may be partly filled);
+ *   criticality of the page for a decode query:
+ *     U_p = max over the query heads g of the group of sum_e max(q_g[e] lo_p[e], q_g[e] hi_p[e]),
+ *     an upper bound of every q_g . K_j in the page; one selection per kv head, since
+ *     the group shares the pages;
+ *   the min(n_pages, budget_pages) pages with the largest U are read, together with
+ *     the local window, which is always read.
+ *   q : [n_q_heads][d]; u_out : [ceil(N/P)] for head h.
+ */
+int orc_quest_page_scores(const orc_state *S, int layer, int seq, int h, const float *q, double *u_out) {
+    if (!S || !S->c.keep_payload || layer < 0 || layer >= S->c.n_layers || seq < 0 ||
+        seq >= S->c.max_seqs || h < 0 || h >= S->c.n_kv_heads || !q || !u_out)
+        return ORC_ERR_ARG;
+    const orc_head *H = &S->sl[(size_t)seq * S->c.n_layers + layer].h[h];
+    const int d = S->c.head_dim, P = S->c.page_size, G = S->c.n_q_heads / S->c.n_kv_heads;
+    const int64_t N = H->glen, n_pages = (N + P - 1) / P;
+    for (int64_t p = 0; p < n_pages; p++) {
+        const int64_t j0 = p * P, j1 = (j0 + P < N) ? j0 + P : N;
+        double best = -INFINITY;
+        for (int g = 0; g < G; g++) {
+            const float *qg = q + ((size_t)h * G + g) * d;
+            double sum = 0.0;
+            for (int e = 0; e < d; e++) {
+                double lo = (double)H->gk[j0 * d + e], hi = lo;
+                for (int64_t j = j0 + 1; j < j1; j++) {
+                    const double x = (double)H->gk[j * d + e];
+                    if (x < lo) lo = x;
+                    if (x > hi) hi = x;
+                }
+                const double a = (double)qg[e] * lo, b = (double)qg[e] * hi;
+                sum += a > b ? a : b;
+            }
+            if (sum > best) best = sum;
+        }
+        u_out[p] = best;
+    }
+    return ORC_OK;
+}
+
+/* The pages to read: the n_sel = min(n_pages, budget_pages) largest scores in the total
+ * order of the fp32 bit patterns, among equal scores the page with the lower index
+ * first; returned as ascending page indices.  sel_out: [budget_pages]. */
+int orc_quest_select(const float *scores, int64_t n_pages, int64_t budget_pages, int32_t *sel_out,
+                     int32_t *n_sel_out) {
+    if (!scores || n_pages < 0 || budget_pages < 0 || !sel_out || !n_sel_out) return ORC_ERR_ARG;
+    const int64_t n_sel = n_pages < budget_pages ? n_pages : budget_pages;
+    char *taken = (char *)calloc((size_t)(n_pages > 0 ? n_pages : 1), 1);
+    if (!taken) return ORC_ERR_NOMEM;
+    for (int64_t r = 0; r < n_sel; r++) {
+        int64_t best = -1;
+        for (int64_t p = 0; p < n_pages; p++)
+            if (!taken[p] && (best < 0 || score_key(scores[p]) > score_key(scores[best]))) best = p;
+        taken[best] = 1;
+    }
+    int64_t w = 0;
+    for (int64_t p = 0; p < n_pages; p++) if (taken[p]) sel_out[w++] = (int32_t)p;
+    *n_sel_out = (int32_t)n_sel;
+    free(taken);
+    return ORC_OK;
+}
+
+/* Decode attention of one sequence/layer over the local window and, per kv head, only the
+ * selected pages of its global cache.  sel: [n_kv_heads][stride] ascending page indices,
+ * n_sel: [n_kv_heads].  q, out: [n_q_heads][d]. */
+int orc_attend_selected(const orc_state *S, int seq, int layer, const float *q, const int32_t *sel,
+                        const int32_t *n_sel, int64_t stride, double scale, double *out) {
+    if (!S || !S->c.keep_payload || !q || !sel || !n_sel || !out) return ORC_ERR_ARG;
+    const int Hq = S->c.n_q_heads, Hk = S->c.n_kv_heads, d = S->c.head_dim, W = S->c.w_local;
+    const int G = Hq / Hk, P = S->c.page_size;
+    const orc_sl *sl = &S->sl[(size_t)seq * S->c.n_layers + layer];
+    for (int h = 0; h < Hk; h++) {
+        const orc_head *H = &sl->h[h];
+        const int64_t n_pages = (H->glen + P - 1) / P;
+        int64_t n = 0;
+        for (int i = 0; i < n_sel[h]; i++) {
+            const int64_t p = sel[(size_t)h * stride + i];
+            if (p < 0 || p >= n_pages || (i > 0 && p <= sel[(size_t)h * stride + i - 1])) return ORC_ERR_ARG;
+            n += ((p + 1) * P <= H->glen) ? P : H->glen - p * P;
+        }
+        for (int s = 0; s < W; s++) if (H->ring_pos[s] >= 0) n++;
+        if (n == 0) {
+            for (int qh = h * G; qh < (h + 1) * G; qh++)
+                for (int e = 0; e < d; e++) out[(size_t)qh * d + e] = 0.0;
+            continue;
+        }
+        const float **kr = (const float **)malloc(sizeof(float *) * n);
+        const float **vr = (const float **)malloc(sizeof(float *) * n);
+        double *sc = (double *)malloc(sizeof(double) * n);
+        if (!kr || !vr || !sc) { free(kr); free(vr); free(sc); return ORC_ERR_NOMEM; }
+        int64_t c = 0;
+        for (int i = 0; i < n_sel[h]; i++) {
+            const int64_t p = sel[(size_t)h * stride + i];
+            for (int64_t j = p * P; j < (p + 1) * P && j < H->glen; j++, c++) { kr[c] = H->gk + j * d; vr[c] = H->gv + j * d; }
+        }
+        for (int s = 0; s < W; s++)
+            if (H->ring_pos[s] >= 0) { kr[c] = H->ring_k + (size_t)s * d; vr[c] = H->ring_v + (size_t)s * d; c++; }
+        for (int qh = h * G; qh < (h + 1) * G; qh++)
+            softmax_av(q + (size_t)qh * d, kr, vr, n, d, scale, sc, out + (size_t)qh * d);
+        free(kr); free(vr); free(sc);
+    }
     return ORC_OK;
 }
 

@@ -93,6 +93,12 @@ def lib():
                                        C.c_double, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.orc_evict_apply.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_float),
                                       C.c_int64, C.c_float, C.POINTER(C.c_int64)]
+        L.orc_quest_page_scores.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float),
+                                            C.POINTER(C.c_double)]
+        L.orc_quest_select.argtypes = [C.POINTER(C.c_float), C.c_int64, C.c_int64, C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_int32)]
+        L.orc_attend_selected.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int32),
+                                          C.POINTER(C.c_int32), C.c_int64, C.c_double, C.POINTER(C.c_double)]
         L.orc_gate_mlp.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int] + [C.POINTER(C.c_float)] * 6 + \
                                   [C.c_double, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _lib = L
@@ -225,6 +231,29 @@ class Oracle:
             raise OracleError(rc)
         return gone[:n_units]
 
+    def quest_page_scores(self, layer, seq, h, q):
+        """Criticality of every page of one head's global cache for the decode queries q [n_q_heads, d]."""
+        q = _f32(q).reshape(self.cfg.n_q_heads, self.cfg.head_dim)
+        n_pages = -(-self.global_len(seq, layer, h) // self.cfg.page_size)
+        u = np.zeros(max(n_pages, 1), dtype=np.float64)
+        rc = self._L.orc_quest_page_scores(self._s, layer, seq, h, _p(q, C.c_float), _p(u, C.c_double))
+        if rc:
+            raise OracleError(rc)
+        return u[:n_pages]
+
+    def attend_selected(self, seq, layer, q, sel, n_sel, scale):
+        """Attention over the window and the selected pages; sel int32 [n_kv_heads, stride], n_sel [n_kv_heads]."""
+        q = _f32(q).reshape(self.cfg.n_q_heads, self.cfg.head_dim)
+        sel = np.ascontiguousarray(sel, dtype=np.int32)
+        n_sel = np.ascontiguousarray(n_sel, dtype=np.int32)
+        assert sel.ndim == 2 and sel.shape[0] == self.cfg.n_kv_heads == len(n_sel)
+        out = np.zeros((self.cfg.n_q_heads, self.cfg.head_dim), dtype=np.float64)
+        rc = self._L.orc_attend_selected(self._s, seq, layer, _p(q, C.c_float), _p(sel, C.c_int32), _p(n_sel, C.c_int32),
+                                         sel.shape[1], float(scale), _p(out, C.c_double))
+        if rc:
+            raise OracleError(rc)
+        return out
+
     def attend_cached(self, seq, layer, q, scale):
         q = _f32(q).reshape(self.cfg.n_q_heads, self.cfg.head_dim)
         out = np.zeros((self.cfg.n_q_heads, self.cfg.head_dim), dtype=np.float64)
@@ -310,3 +339,14 @@ def gate_mlp(k, k_rope, W1, b1, W2, b2, eps=1e-6, feature_bf16=False):
                             1 if feature_bf16 else 0, _p(logit, C.c_double), _p(g, C.c_double))
     assert rc == 0, rc
     return logit, g
+
+
+def quest_select(scores, budget_pages):
+    """Ascending indices of the min(n_pages, budget_pages) pages with the largest fp32 scores
+    (equal scores: lower index first)."""
+    scores = _f32(scores).ravel()
+    sel = np.zeros(max(budget_pages, 1), dtype=np.int32)
+    n = C.c_int32(0)
+    rc = lib().orc_quest_select(_p(scores, C.c_float), len(scores), int(budget_pages), _p(sel, C.c_int32), C.byref(n))
+    assert rc == 0, rc
+    return sel[: n.value].copy()
