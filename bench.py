@@ -91,6 +91,10 @@ def main():
     ap.add_argument("--gate", choices=["linear", "mlp"], default="linear",
                     help="chunked-prefill workload only: the workload's linear gate on the hidden state, or the "
                          "Write-Gate MLP (width 4*head_dim, random weights) on the keys before/after the rotary embedding")
+    ap.add_argument("--select-pages", type=int, default=0,
+                    help="decode workloads: read only this many pages of each head's global cache per step, picked "
+                         "with key landmarks (128 pages of 16 = the 2048 KVs per query of the paper's selection run); "
+                         "the step then is promotion + landmark upkeep + page scoring/selection + attention")
     ap.add_argument("--evict", action="store_true",
                     help="time the budgeted eviction (scoring from a 256-query observation window + removal of the "
                          "lowest 10 %) on one layer of the workload's batch with about 4.5K global entries per head")
@@ -164,13 +168,34 @@ def main():
     scale = 1.0 / math.sqrt(d)
     log(f"[bench] setup {time.time() - t_setup:.1f}s")
 
+    sel_b = args.select_pages
+    if sel_b:
+        lm = pool.quest_landmarks()
+        pool.status()
+        n_units = B * Hk
+        pg_stride = int(pool.meta()["global_len"].max().item()) // P + total_steps // P + 4
+        sel_scores = torch.zeros((n_units, pg_stride), dtype=torch.float32, device=dev)
+        sel_pages = torch.zeros((n_units, sel_b), dtype=torch.int32, device=dev)
+        sel_count = torch.zeros((n_units,), dtype=torch.int32, device=dev)
+        for l in range(L):
+            pool.quest_update(l, seqs, lm)
+        _p, _i, _chk = wg.binding._ptr, wg.binding._ids, wg.binding._check
+
     def one_step(st, events=None):
         for l in range(L):
             pool.decode_step(l, seqs, k_new[l], v_new[l], g_new[st, l], tau=cfg.tau)
+            if sel_b:
+                pool.quest_update(l, seqs, lm)
+                _chk(pool.L.wgkv_quest_select(pool.h, l, B, _i(seqs), _p(q_new[l]), _p(lm), lm.numel(), sel_b,
+                                              _p(sel_scores), pg_stride, _p(sel_pages), _p(sel_count),
+                                              wg.binding._stream()), "wgkv_quest_select")
             if events is not None:
                 i = (st - args.warmup) * L + l
                 pool.set_profile_events(events.ev[2 * i], events.ev[2 * i + 1])
-            pool.attend(l, seqs, q_new[l], out[l], scale)
+            if sel_b:
+                pool.attend_selected(l, seqs, q_new[l], sel_pages, sel_count, out[l], scale)
+            else:
+                pool.attend(l, seqs, q_new[l], out[l], scale)
 
     for st in range(args.warmup):
         one_step(st)
@@ -197,6 +222,9 @@ def main():
     bytes0 = attend_algorithmic_bytes(cfg, sl0, gl0, range(L))
     bytes1 = attend_algorithmic_bytes(cfg, sl1, gl1, range(L))
     bytes_per_launch = 0.5 * (np.mean(bytes0) + np.mean(bytes1))
+    if sel_b:   # the attention kernel reads the window and at most sel_b pages per head
+        capped = [attend_algorithmic_bytes(cfg, s_, np.minimum(g_, sel_b * P), range(L)) for s_, g_ in ((sl0, gl0), (sl1, gl1))]
+        bytes_per_launch = 0.5 * (np.mean(capped[0]) + np.mean(capped[1]))
     roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
                 "traffic": None, "kernel": "attend_decode_kernel",
                 "algorithmic_bytes_per_launch": bytes_per_launch}
@@ -217,7 +245,7 @@ def main():
         del src, dst
     # HBM bytes per launch measured with rocprofv3 counters (see the summary's header for the commands)
     traffic_file = os.path.join(ROOT, "profiles", f"attend_decode_kernel_{cfg.name}_hbm_traffic.txt")
-    if os.path.exists(traffic_file):
+    if os.path.exists(traffic_file) and not sel_b:
         for line in open(traffic_file):
             if line.startswith("hbm_bytes_per_launch:"):
                 roofline["traffic"] = float(line.split(":")[1])
@@ -228,12 +256,14 @@ def main():
                                         q_new[0], scale, pool, seqs)
 
     res = {
-        "metric": "decode_step_latency_us (all layers: lazy promotion + ragged paged GQA decode attention)",
+        "metric": "decode_step_latency_us (all layers: lazy promotion + ragged paged GQA decode attention)" if not sel_b else
+                  "decode_step_latency_us (all layers: lazy promotion + landmark upkeep + page selection + attention over window and selected pages)",
         "value": ms_per_step * 1e3, "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "layers": L, "q_heads": Hq, "kv_heads": Hk, "head_dim": d,
                    "w_local": W, "page_size": P, "tau": cfg.tau, "ctx_min": int(ctx.min()), "ctx_max": int(ctx.max()),
+                   "select_pages": sel_b,
                    "mean_cached_tokens_per_head": float((np.minimum(sl1, W)[:, :, None] + gl1).mean()),
                    "attend_us_per_layer": roofline.get("kernel_avg_us"),
                    "gpu_ms_per_step": gpu_ms / args.steps, "host_wall_ms_per_step": wall_ms / args.steps},

@@ -189,6 +189,52 @@ int wgkv_attend(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *s
                 const void *v_chunk_dev, const float *g_chunk_dev, float tau, float scale,
                 float *out_dev, void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
 
+/* ---- read-time page selection over the admitted cache ----
+ * Appendix "Synergy with KV Selection": Quest-style selection with key landmarks (the
+ * per-page minimum and maximum key vectors) at a budget of so many KVs per query.  The
+ * paper names the method only; this is the published Quest procedure as read here for
+ * grouped-query attention: the criticality of page p of a kv head's global cache is
+ *   U_p = max over the query heads g of the group of sum_e max(q_g[e] lo_p[e], q_g[e] hi_p[e]),
+ * an upper bound of every q_g . K_j in the page; the min(n_pages, budget_pages) pages
+ * with the largest U (total order of the fp32 bit patterns, equal scores: lower page
+ * index first) are read, one selection per kv head; the local window is always read.
+ *
+ * Landmarks live in a caller-owned device buffer of wgkv_quest_landmark_bytes bytes,
+ * zero-filled by the caller before its first use: per physical page the minimum and the
+ * maximum row in the pool dtype, then one int32 per (slot, layer, kv head). */
+int wgkv_quest_landmark_bytes(const wgkv_config *cfg, size_t *landmark_bytes);
+
+/* Brings the landmarks of the given sequences' heads (layer `layer`) up to date with
+ * their global caches: only pages that received entries since the last update are
+ * recomputed.  reset != 0 recomputes all their pages; that is needed after
+ * wgkv_evict_apply (entries moved) and after wgkv_free_seq (slot reused).  Call it after
+ * the prefill / decode calls and before wgkv_quest_select.  Errors: INVALID_ARG, HIP. */
+int wgkv_quest_update(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                      void *landmarks_dev, size_t landmark_bytes, int32_t reset, wgkv_stream stream);
+
+/* Scores every page of every head for the decode queries and picks the pages to read.
+ *   q_dev [n_seqs][n_q_heads][head_dim] of cfg.dtype
+ *   page_scores_out_dev float [n_seqs * n_kv_heads][score_stride]: U of pages [0, n_pages);
+ *                       score_stride must cover the host's bound of every head's page count
+ *   sel_pages_out_dev int32 [n_seqs * n_kv_heads][budget_pages]: ascending indices into the
+ *                       head's global page table; sel_count_out_dev int32 [n_seqs * n_kv_heads]
+ * fp32 arithmetic.  Errors: INVALID_ARG, HIP. */
+int wgkv_quest_select(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                      const void *q_dev, void *landmarks_dev, size_t landmark_bytes, int32_t budget_pages,
+                      float *page_scores_out_dev, int64_t score_stride, int32_t *sel_pages_out_dev,
+                      int32_t *sel_count_out_dev, wgkv_stream stream);
+
+/* Decode attention (as wgkv_attend with one query per sequence) over the local window and,
+ * per kv head, only the listed pages of its global cache.
+ *   sel_pages_dev int32 [n_seqs * n_kv_heads][sel_stride], strictly ascending page indices;
+ *   sel_count_dev int32 [n_seqs * n_kv_heads].  Indices outside a head's table are clamped
+ *   (the result is then meaningless but no memory outside the pool is read).
+ * Errors: INVALID_ARG, WORKSPACE, HIP. */
+int wgkv_attend_selected(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                         const void *q_dev, const int32_t *sel_pages_dev, const int32_t *sel_count_dev,
+                         int32_t sel_stride, float scale, float *out_dev, void *workspace_dev,
+                         size_t workspace_bytes, wgkv_stream stream);
+
 /* Appendix "Eviction policy implementation", the three scoring steps, for every kv head
  * of the given sequences (distinct ids) over the N entries of its global cache:
  *   A = Softmax(Q_obs K^T * scale) per query row (n_obs positions x the heads of the group),

@@ -11,7 +11,8 @@ F32, BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
-    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_free_seq",
+    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
+    "wgkv_quest_select", "wgkv_attend_selected", "wgkv_free_seq",
     "wgkv_status", "wgkv_set_profile_events", "wgkv_destroy",
 ]
 
@@ -86,6 +87,10 @@ def load_library():
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
+    L.wgkv_quest_landmark_bytes.argtypes = [C.POINTER(_CConfig), C.POINTER(sz)]
+    L.wgkv_quest_update.argtypes = [vp, i32, i32, pi32, vp, sz, i32, vp]
+    L.wgkv_quest_select.argtypes = [vp, i32, i32, pi32, vp, vp, sz, i32, vp, i64, vp, vp, vp]
+    L.wgkv_attend_selected.argtypes = [vp, i32, i32, pi32, vp, vp, vp, i32, f32, vp, vp, sz, vp]
     L.wgkv_evict_scores.argtypes = [vp, i32, i32, pi32, vp, i32, f32, i32, vp, vp, i64, vp, sz, vp]
     L.wgkv_evict_apply.argtypes = [vp, i32, i32, pi32, vp, i64, f32, vp, vp, sz, vp]
     L.wgkv_free_seq.argtypes = [vp, i32, vp]
@@ -205,6 +210,36 @@ class Pool:
         _check(self.L.wgkv_attend(self.h, layer, len(seq_ids), _ids(seq_ids), _ids(n_q), _ptr(q),
                                   _ptr(k_chunk), _ptr(v_chunk), _ptr(g_chunk), tau, scale, _ptr(out),
                                   _ptr(self.workspace), self.workspace.numel(), _stream()), "wgkv_attend")
+        return out
+
+    def quest_landmarks(self):
+        """A zero-filled landmark buffer of the size the library asks for (uint8 tensor)."""
+        import torch
+        n = C.c_size_t(0)
+        cc = self.cfg.c()
+        _check(self.L.wgkv_quest_landmark_bytes(C.byref(cc), C.byref(n)), "wgkv_quest_landmark_bytes")
+        return torch.zeros(n.value, dtype=torch.uint8, device=self.device)
+
+    def quest_update(self, layer, seq_ids, landmarks, reset=False):
+        _check(self.L.wgkv_quest_update(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(landmarks), landmarks.numel(),
+                                        1 if reset else 0, _stream()), "wgkv_quest_update")
+
+    def quest_select(self, layer, seq_ids, q, landmarks, budget_pages, score_stride):
+        """Returns (page_scores [n_units, score_stride], sel_pages int32 [n_units, budget_pages], sel_count [n_units])."""
+        import torch
+        n_units = len(seq_ids) * self.cfg.n_kv_heads
+        scores = torch.zeros((n_units, score_stride), dtype=torch.float32, device=self.device)
+        sel = torch.full((n_units, budget_pages), -1, dtype=torch.int32, device=self.device)
+        cnt = torch.zeros((n_units,), dtype=torch.int32, device=self.device)
+        _check(self.L.wgkv_quest_select(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(q), _ptr(landmarks),
+                                        landmarks.numel(), budget_pages, _ptr(scores), score_stride, _ptr(sel),
+                                        _ptr(cnt), _stream()), "wgkv_quest_select")
+        return scores, sel, cnt
+
+    def attend_selected(self, layer, seq_ids, q, sel_pages, sel_count, out, scale):
+        _check(self.L.wgkv_attend_selected(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(q), _ptr(sel_pages),
+                                           _ptr(sel_count), sel_pages.shape[1], scale, _ptr(out), _ptr(self.workspace),
+                                           self.workspace.numel(), _stream()), "wgkv_attend_selected")
         return out
 
     def evict_scores(self, layer, seq_ids, q_obs, scale, stride, pool_w=5):

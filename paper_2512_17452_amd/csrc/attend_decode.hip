@@ -39,8 +39,23 @@ struct AttendArgs {
     float *part_ml;           // [(waves + n_units)][G][2]
     float *part_acc;          // [(waves + n_units)][G][d]
     int32_t *counters;        // [n_units] zero between calls: waves done per unit
+    // optional page selection: only these pages of each head's global cache are read
+    const int32_t *sel_pages; // [n_units][sel_stride] ascending indices into the head's global table, or NULL
+    const int32_t *sel_count; // [n_units]
+    int sel_stride;
     int32_t sid[kMaxCallSeqs];
 };
+
+// Tokens a unit reads from its global cache: all gl of them, or those of the selected pages (every
+// page is full except possibly the last one of the cache, which then is the last one selected).
+__device__ __forceinline__ int global_tokens(const View &pv, const AttendArgs &a, int u, int gl) {
+    if (!a.sel_pages) return gl;
+    const int n_pages = (gl + pv.P - 1) >> pv.logP;
+    const int cnt = min(min(max(a.sel_count[u], 0), a.sel_stride), n_pages);
+    if (cnt == 0) return 0;
+    const int last = a.sel_pages[(size_t)u * a.sel_stride + cnt - 1];
+    return (cnt - 1) * pv.P + (last >= n_pages - 1 ? gl - (n_pages - 1) * pv.P : pv.P);
+}
 
 __device__ __forceinline__ int ceil_tiles(int n) { return (n + kTile - 1) / kTile; }
 
@@ -54,7 +69,7 @@ __device__ __forceinline__ void build_tile_prefix(const View &pv, const AttendAr
         if (u < n_units) {
             const int b = u / pv.Hkv, h = u % pv.Hkv, sid = a.sid[b];
             const int t = pv.seq_len[sid * pv.L + a.layer];
-            const int gl = pv.global_len[unit_meta(pv, sid, a.layer, h)];
+            const int gl = global_tokens(pv, a, u, pv.global_len[unit_meta(pv, sid, a.layer, h)]);
             tiles = ceil_tiles(gl) + ceil_tiles(min(t, pv.W));
         }
         int total;
@@ -150,7 +165,8 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
         while (s_ts[u + 1] <= cur) u++;  // also skips units without tiles
         const int b = u / pv.Hkv, h = u % pv.Hkv, sid = a.sid[b];
         const int um = unit_meta(pv, sid, a.layer, h);
-        const int gl = pv.global_len[um];
+        const int gl_all = pv.global_len[um];
+        const int gl = global_tokens(pv, a, u, gl_all);
         const int nloc = min(pv.seq_len[sid * pv.L + a.layer], pv.W);
         const int n_gt = ceil_tiles(gl);
         const int u_begin = s_ts[u], u_end = min(s_ts[u + 1], T1);
@@ -190,6 +206,11 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
             // are read too (finite: the pool is zeroed at start-up and only ever holds K/V
             // rows) and get weight zero.  With pages smaller than a tile every tile is
             // handled one at a time with a page lookup per row.
+            // page id of the vp-th page of the region as this call reads it (with a selection: the
+            // vp-th selected page; an index outside the table is clamped, never followed)
+            const int32_t *sel = (is_glob && a.sel_pages) ? a.sel_pages + (size_t)u * a.sel_stride : nullptr;
+            const int last_page = max(((gl_all + pv.P - 1) >> pv.logP) - 1, 0);
+            auto page_at = [&](int vp) { return pt[sel ? min(max(sel[vp], 0), last_page) : vp]; };
             const bool page_per_tile = pv.logP >= 4;
             const int n_fast = page_per_tile ? n : 0;
             int ptreg = 0;
@@ -211,7 +232,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                 for (int r = 0; r < RPT; r++) {
                     int tok = k * kTile + r * TPW + grp;
                     tok = min(tok, count - 1);  // rows past the end re-read a valid row and get weight 0
-                    const int page = pt[tok >> pv.logP];
+                    const int page = page_at(tok >> pv.logP);
                     rowp[r] = page_ptr(pv, page) + (size_t)(tok & (pv.P - 1)) * ROWB + sub * 16;
                 }
             };
@@ -430,7 +451,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
             };
 
             if (n_fast > 0) {
-                ptreg = pt[((k0 + min(lane, n_fast - 1)) * kTile) >> pv.logP];
+                ptreg = page_at(((k0 + min(lane, n_fast - 1)) * kTile) >> pv.logP);
                 // prologue: fill every register set
 #pragma unroll
                 for (int st = 0; st < S; st++) {
@@ -618,8 +639,12 @@ size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid_max) {
 hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int32_t *sids,
                                 const void *q, float scale, float *out, void *ws, int32_t *counters,
                                 int n_cu, int grid_max, int min_tpw, hipStream_t st, hipEvent_t ev0,
-                                hipEvent_t ev1) {
+                                hipEvent_t ev1, const int32_t *sel_pages, const int32_t *sel_count,
+                                int sel_stride) {
     AttendArgs a;
+    a.sel_pages = sel_pages;
+    a.sel_count = sel_count;
+    a.sel_stride = sel_stride;
     a.layer = layer;
     a.n_seqs = n_seqs;
     a.min_tpw = min_tpw;

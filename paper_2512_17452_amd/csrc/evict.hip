@@ -55,16 +55,18 @@ __global__ __launch_bounds__(kEvictThreads) void evict_compact_kernel(View pv, C
             if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> (8 * pass)) & 255u], 1u);
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            unsigned cum = 0, bin = 0;
+        // the bin in which the running count reaches the rank: a block-wide prefix over the 256 bins
+        {
             const unsigned want = s_sel[2];
-            for (; bin < 255u; bin++) {
-                if (cum + s_hist[bin] >= want) break;
-                cum += s_hist[bin];
+            const int cnt = threadIdx.x < 256 ? (int)s_hist[threadIdx.x] : 0;
+            int total;
+            const int ex = block_excl_scan(cnt, s_tmp, &total);
+            __syncthreads();  // everybody has read s_sel
+            if (threadIdx.x < 256 && (unsigned)ex < want && want <= (unsigned)(ex + cnt)) {
+                s_sel[0] = prefix | ((unsigned)threadIdx.x << (8 * pass));
+                s_sel[1] = mask | (255u << (8 * pass));
+                s_sel[2] = want - (unsigned)ex;  // rank among the keys that share the longer prefix
             }
-            s_sel[0] = prefix | (bin << (8 * pass));
-            s_sel[1] = mask | (255u << (8 * pass));
-            s_sel[2] = want - cum;  // rank among the keys that share the longer prefix
         }
         __syncthreads();
     }

@@ -27,11 +27,18 @@ hipError_t launch_evict_scores(const View &pv, const CallSeqs &cs, int layer, co
                                void *ws, hipStream_t st);
 hipError_t launch_evict_apply(const View &pv, const CallSeqs &cs, int layer, const float *scores,
                               int64_t stride, float frac, int32_t *n_evicted, void *ws, hipStream_t st);
+size_t quest_landmark_bytes(const View &pv);
+hipError_t launch_quest_update(const View &pv, const CallSeqs &cs, int layer, void *landmarks, int reset,
+                               hipStream_t st);
+hipError_t launch_quest_select(const View &pv, const CallSeqs &cs, int layer, const void *q, void *landmarks,
+                               int budget_pages, float *scores, int64_t score_stride, int32_t *sel_pages,
+                               int32_t *sel_count, int64_t max_pages, hipStream_t st);
 size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid);
 hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int32_t *sids,
                                 const void *q, float scale, float *out, void *ws, int32_t *counters,
-                                int n_cu, int grid_max, int min_tpb, hipStream_t st, hipEvent_t ev0,
-                                hipEvent_t ev1);
+                                int n_cu, int grid_max, int min_tpw, hipStream_t st, hipEvent_t ev0,
+                                hipEvent_t ev1, const int32_t *sel_pages, const int32_t *sel_count,
+                                int sel_stride);
 hipError_t launch_gate_mlp(int dtype, int64_t n_tokens, int n_kv_heads, int head_dim, int width,
                            const void *k, const void *k_rope, const void *w1, const float *b1,
                            const void *w2, const float *b2, float eps, float *g_out, hipStream_t st);
@@ -413,7 +420,8 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
         if (workspace_bytes < attend_decode_ws_bytes(p->view, n_seqs, kAttnGridMax)) return WGKV_ERR_WORKSPACE;
         return launch_attend_decode(p->view, layer, n_seqs, seq_ids_host, q_dev, scale, out_dev,
                                     workspace_dev, p->view.unit_counters, p->n_cu, kAttnGridMax,
-                                    kAttnMinTilesPerWave, st, p->ev0, p->ev1) == hipSuccess
+                                    kAttnMinTilesPerWave, st, p->ev0, p->ev1, nullptr, nullptr,
+                                    0) == hipSuccess
                    ? WGKV_OK
                    : WGKV_ERR_HIP;
     }
@@ -440,6 +448,82 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
         return WGKV_ERR_HIP;
     if (p->ev1 && hipEventRecord(p->ev1, st) != hipSuccess) return WGKV_ERR_HIP;
     return WGKV_OK;
+}
+
+int wgkv_quest_landmark_bytes(const wgkv_config *cfg, size_t *landmark_bytes) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!landmark_bytes) return WGKV_ERR_INVALID_ARG;
+    View v = make_view(cfg, nullptr, nullptr);
+    *landmark_bytes = quest_landmark_bytes(v);
+    return WGKV_OK;
+}
+
+static int quest_seqs(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host, CallSeqs *cs,
+                      int64_t *max_len) {
+    int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    memset(cs, 0, sizeof(*cs));
+    cs->n = n_seqs;
+    *max_len = 0;
+    const int H = p->cfg.n_kv_heads;
+    for (int b = 0; b < n_seqs; b++) {
+        const size_t sl = (size_t)seq_ids_host[b] * p->cfg.n_layers + layer;
+        cs->sid[b] = seq_ids_host[b];
+        cs->t0[b] = p->seq_len_h[sl];
+        for (int h = 0; h < H; h++) *max_len = *max_len > p->g_ub[sl * H + h] ? *max_len : p->g_ub[sl * H + h];
+    }
+    return WGKV_OK;
+}
+
+int wgkv_quest_update(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                      void *landmarks_dev, size_t landmark_bytes, int32_t reset, wgkv_stream stream) {
+    CallSeqs cs;
+    int64_t max_len;
+    int rc = quest_seqs(p, layer, n_seqs, seq_ids_host, &cs, &max_len);
+    if (rc) return rc;
+    if (!landmarks_dev || landmark_bytes < quest_landmark_bytes(p->view)) return WGKV_ERR_INVALID_ARG;
+    return launch_quest_update(p->view, cs, layer, landmarks_dev, reset != 0, (hipStream_t)stream) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
+}
+
+int wgkv_quest_select(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                      const void *q_dev, void *landmarks_dev, size_t landmark_bytes, int32_t budget_pages,
+                      float *page_scores_out_dev, int64_t score_stride, int32_t *sel_pages_out_dev,
+                      int32_t *sel_count_out_dev, wgkv_stream stream) {
+    CallSeqs cs;
+    int64_t max_len;
+    int rc = quest_seqs(p, layer, n_seqs, seq_ids_host, &cs, &max_len);
+    if (rc) return rc;
+    const int P = p->cfg.page_size;
+    const int64_t max_pages = (max_len + P - 1) / P;
+    if (!q_dev || !landmarks_dev || landmark_bytes < quest_landmark_bytes(p->view) || budget_pages < 1 ||
+        !page_scores_out_dev || score_stride < max_pages || !sel_pages_out_dev || !sel_count_out_dev)
+        return WGKV_ERR_INVALID_ARG;
+    return launch_quest_select(p->view, cs, layer, q_dev, landmarks_dev, budget_pages, page_scores_out_dev,
+                               score_stride, sel_pages_out_dev, sel_count_out_dev, max_pages,
+                               (hipStream_t)stream) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
+}
+
+int wgkv_attend_selected(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                         const void *q_dev, const int32_t *sel_pages_dev, const int32_t *sel_count_dev,
+                         int32_t sel_stride, float scale, float *out_dev, void *workspace_dev,
+                         size_t workspace_bytes, wgkv_stream stream) {
+    int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    if (!q_dev || !sel_pages_dev || !sel_count_dev || sel_stride < 1 || !out_dev || !workspace_dev ||
+        !std::isfinite(scale))
+        return WGKV_ERR_INVALID_ARG;
+    if (workspace_bytes < attend_decode_ws_bytes(p->view, n_seqs, kAttnGridMax)) return WGKV_ERR_WORKSPACE;
+    return launch_attend_decode(p->view, layer, n_seqs, seq_ids_host, q_dev, scale, out_dev, workspace_dev,
+                                p->view.unit_counters, p->n_cu, kAttnGridMax, kAttnMinTilesPerWave,
+                                (hipStream_t)stream, p->ev0, p->ev1, sel_pages_dev, sel_count_dev,
+                                sel_stride) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
 }
 
 int wgkv_evict_scores(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
