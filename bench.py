@@ -234,6 +234,7 @@ def main():
         roofline.update({"achieved": bytes_per_launch / (avg_us * 1e-6) / 1e9,
                          "frac": bytes_per_launch / (avg_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                          "kernel_avg_us": avg_us, "kernel_p10_us": float(np.percentile(durs, 10) * 1e3),
+                         "kernel_p50_us": float(np.percentile(durs, 50) * 1e3),
                          "kernel_p90_us": float(np.percentile(durs, 90) * 1e3), "launches": int(len(durs))})
         events.destroy()
     if args.calibrate_copy:   # known traffic: reads 2^30 bytes, writes 2^30 bytes per launch
@@ -441,13 +442,25 @@ def run_cpu_baseline(cfg, wl, ctx, rates, dev, gen_prefill, k1, v1, g1, q, scale
     n_pages = B * Hk * (max_gp + W // P + 1)
     orc = Oracle(OracleConfig(1, Hq, Hk, d, P, W, B, max_gp, n_pages, True))
     chunk = 8192
+    admit_s, admit_tokens = 0.0, 0
     for s in range(B):
         k, v, g = gen_prefill(s, 0)
         for a in range(0, int(ctx[s]), chunk):
             b = min(a + chunk, int(ctx[s]))
-            orc.push_tokens(0, [s], [b - a], k[a:b].float().cpu().numpy(), v[a:b].float().cpu().numpy(),
-                            g[a:b].cpu().numpy(), cfg.tau)
+            kh, vh, gh = k[a:b].float().cpu().numpy(), v[a:b].float().cpu().numpy(), g[a:b].cpu().numpy()
+            t_a = time.perf_counter()
+            orc.push_tokens(0, [s], [b - a], kh, vh, gh, cfg.tau)
+            admit_s += time.perf_counter() - t_a
+            admit_tokens += b - a
         del k, v, g
+    cpu_model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu_model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
     log(f"[bench] oracle state for layer 0 built in {time.time() - t0:.1f}s")
     orc.push_tokens(0, seqs, [1] * B, k1.float().cpu().numpy(), v1.float().cpu().numpy(), g1.cpu().numpy(), cfg.tau)
     qh = q.float().cpu().numpy()
@@ -462,7 +475,10 @@ def run_cpu_baseline(cfg, wl, ctx, rates, dev, gen_prefill, k1, v1, g1, q, scale
             "sample": f"decode attention of layer 0 only (batch {B}, {tokens} cached tokens over {B * Hk} "
                       f"(sequence, kv head) units), best of {reps}, {best * 1e3:.1f} ms per layer call, "
                       f"multiplied by {L} layers (extrapolated); promotion/paging not included",
-            "layer_call_ms": best * 1e3}
+            "layer_call_ms": best * 1e3, "cpu_model": cpu_model, "host_cpus": os.cpu_count(),
+            "oracle_admission_us_per_token": admit_s / max(admit_tokens, 1) * 1e6,
+            "oracle_admission_note": f"admission, paging and promotion of layer 0's prompts ({admit_tokens} tokens x {Hk} kv heads, "
+                                     f"payload kept), one host thread, {admit_s:.1f} s in total"}
 
 
 if __name__ == "__main__":
