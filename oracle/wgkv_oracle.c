@@ -548,6 +548,8 @@ int orc_attend_soft(int n_q_heads, int n_kv_heads, int d, int w_local, double sc
  */
 int orc_linear_gate(int64_t T, int dim, int n_kv_heads, const float *hidden, const float *w,
                     double *logit_out, double *g_out) {
+    /* tokens are independent: spread them over the host threads */
+#pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < T; t++)
         for (int h = 0; h < n_kv_heads; h++) {
             double s = 0.0;

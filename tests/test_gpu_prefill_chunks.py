@@ -60,14 +60,18 @@ def _flow(B, lens, chunk, W, P, hidden_dim, seed, tau=0.5, use_gate=True, check_
         k = torch.randn((tot, Hk, d), generator=gen).to(torch.bfloat16)
         v = torch.randn((tot, Hk, d), generator=gen).to(torch.bfloat16)
         if use_gate:
+            # The scores of the flow are the oracle's (fp64 gate, stored as fp32) on both sides; the
+            # gate kernel is checked against them, and its decisions wherever the logit is outside
+            # the band in which fp32 and fp64 may legitimately disagree.
             hidden = torch.randn((tot, hidden_dim), generator=gen).to(torch.bfloat16)
-            g_dev = wg.gate_scores(hidden.to(dev), w.to(dev))
             logit, gref = linear_gate(hidden.float().numpy(), w.float().numpy())
-            g = g_dev.cpu().numpy()
-            assert np.abs(g - gref).max() <= GATE_TOL
+            g = gref.astype(np.float32)
+            g_dev = torch.from_numpy(g).to(dev)
+            g_kernel = wg.gate_scores(hidden.to(dev), w.to(dev)).cpu().numpy()
+            assert np.abs(g_kernel - gref).max() <= GATE_TOL
             far = np.abs(logit) > GUARD
             near += int((~far).sum())
-            assert np.array_equal((g >= tau)[far], (gref >= tau)[far])
+            assert np.array_equal((g_kernel >= tau)[far], (gref >= tau)[far])
         else:
             g = torch.rand((tot, Hk), generator=gen).numpy().astype(np.float32)
             g_dev = torch.from_numpy(g).to(dev)
@@ -76,7 +80,6 @@ def _flow(B, lens, chunk, W, P, hidden_dim, seed, tau=0.5, use_gate=True, check_
         pool.attend(0, seqs, q.to(dev), out, scale, n_q=nt, k_chunk=kd, v_chunk=vd, g_chunk=g_dev, tau=tau)
         mask = torch.zeros((tot, Hk), dtype=torch.uint8, device=dev)
         pool.prefill_admit(0, seqs, nt, kd, vd, g_dev, tau=tau, admit_mask_out=mask)
-        # both sides decide on the same fp32 scores (the kernel's)
         admit, _ = orc.push_tokens(0, seqs, nt, k.float().numpy(), v.float().numpy(), g, tau)
         assert np.array_equal(mask.cpu().numpy(), admit)
         o = out.cpu().numpy()
@@ -114,6 +117,42 @@ def test_chunked_prefill_every_row(chunk, W, P):
     lens = [min(1536, 12 * chunk + 5), min(900, 7 * chunk)] if chunk > 1 else [70, 33]
     _, _, worst, near = _flow(2, lens, chunk, W, P, hidden_dim=256, seed=1000 + chunk)
     print(f"chunk {chunk} W {W} P {P}: max abs err {worst[0]:.2e}, mean {worst[1]:.2e}, {near} scores in the guard band", flush=True)
+
+
+def test_prefill_admit_computes_the_gate_itself():
+    """wgkv_prefill_admit with weights instead of scores.  The GPU then decides on its own fp32 gate
+    scores and the oracle on its fp64 ones; tau is put into a gap of the oracle's scores that is wider
+    than the gate tolerance on both sides, so both must take the same decisions and the states match."""
+    rng = np.random.default_rng(77)
+    Hq, Hk, d, W, P, T, dim = 8, 2, 128, 32, 16, 500, 256
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device="cpu").manual_seed(77)
+    hidden = torch.randn((T, dim), generator=gen).to(torch.bfloat16)
+    w = (0.05 * torch.randn((Hk, dim), generator=gen)).to(torch.bfloat16)
+    k = torch.randn((T, Hk, d), generator=gen).to(torch.bfloat16)
+    v = torch.randn((T, Hk, d), generator=gen).to(torch.bfloat16)
+    _, gref = linear_gate(hidden.float().numpy(), w.float().numpy())
+    srt = np.sort(gref.ravel())
+    gaps = np.nonzero(np.diff(srt) > 4 * GATE_TOL)[0]
+    mids = 0.5 * (srt[gaps] + srt[gaps + 1])
+    tau = float(np.float32(mids[np.argmin(np.abs(mids - 0.5))]))
+    assert 0.4 < tau < 0.6 and np.abs(gref - tau).min() > GATE_TOL
+    max_gp = T // P + 2
+    n_pages = Hk * (max_gp + W // P) + 8
+    pool = wg.Pool(wg.Config(1, Hq, Hk, d, wg.BF16, P, W, 1, max_gp, n_pages), 1, T)
+    orc = Oracle(OracleConfig(1, Hq, Hk, d, P, W, 1, max_gp, n_pages, False))
+    mask = torch.zeros((T, Hk), dtype=torch.uint8, device=dev)
+    pool.prefill_admit(0, [0], [T], k.to(dev), v.to(dev), None, hidden=hidden.to(dev), gate_w=w.to(dev), tau=tau,
+                       admit_mask_out=mask)
+    admit, _ = orc.push_tokens(0, [0], [T], None, None, gref.astype(np.float32), tau)
+    assert np.array_equal(mask.cpu().numpy(), admit) and 0.2 < admit.mean() < 0.8
+    free, flag = pool.status()
+    assert flag == 0 and free == orc.free_top
+    m = {kk: vv.cpu().numpy() for kk, vv in pool.meta().items()}
+    for hh in range(Hk):
+        lp, gp, _, _ = orc.head_tables(0, 0, hh)
+        assert int(m["global_len"][0, 0, hh]) == orc.global_len(0, 0, hh)
+        assert np.array_equal(m["global_pt"][0, 0, hh], gp) and np.array_equal(m["local_pt"][0, 0, hh], lp)
 
 
 def test_given_scores_admit_all_and_none():
@@ -164,7 +203,7 @@ def test_prefill_form_rejects_unsupported_shapes():
 
 def test_llama8b_chunked_prefill_128k_with_gate():
     """Workload 5: batch 4, 128K tokens in 4K chunks, scores from the random-init linear gate.
-    Admission is compared for every token; gate scores and attention on seeded samples."""
+    The gate kernel and admission are compared for every token; attention on seeded samples."""
     cfg = wl.get_config(4)
     B, Hq, Hk, d, W, P = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local, cfg.page_size
     N = max(int(cfg.ctx_max * SCALE) // cfg.chunk * cfg.chunk, 2 * cfg.chunk)
@@ -192,19 +231,20 @@ def test_llama8b_chunked_prefill_128k_with_gate():
         k = wl.draw_normal(cfg, "k", (B * C, Hk, d), device=dev, key=(c,))
         v = wl.draw_normal(cfg, "v", (B * C, Hk, d), device=dev, key=(c,))
         q = wl.draw_normal(cfg, "q", (B * C, Hq, d), device=dev, key=(c,))
-        g = wg.gate_scores(hidden, gate_w)
+        # the scores of the run are the oracle's (fp64 gate stored as fp32), on both sides; the gate
+        # kernel is checked against them on every token
+        logit, gref = linear_gate(hidden.float().cpu().numpy(), gate_w_host)
+        gh = gref.astype(np.float32)
+        g = torch.from_numpy(gh).to(dev)
+        g_kernel = wg.gate_scores(hidden, gate_w).cpu().numpy()
+        assert np.abs(g_kernel - gref).max() <= GATE_TOL
+        far = np.abs(logit) > GUARD
+        assert np.array_equal((g_kernel >= cfg.tau)[far], (gref >= cfg.tau)[far])
         pool.attend(0, seqs, q, out, scale, n_q=nt, k_chunk=k, v_chunk=v, g_chunk=g, tau=cfg.tau)
         pool.prefill_admit(0, seqs, nt, k, v, g, tau=cfg.tau, admit_mask_out=mask)
-        gh = g.cpu().numpy()
-        admit, _ = orc.push_tokens(0, seqs, nt, None, None, gh, cfg.tau)   # decisions on the kernel's fp32 scores
+        admit, _ = orc.push_tokens(0, seqs, nt, None, None, gh, cfg.tau)
         assert np.array_equal(mask.cpu().numpy(), admit), c
         admitted += int(admit.sum())
-        # gate: sampled rows against fp64
-        rows = rng.integers(0, B * C, 512)
-        logit, gref = linear_gate(hidden[rows].float().cpu().numpy(), gate_w_host)
-        assert np.abs(gh[rows] - gref).max() <= GATE_TOL
-        far = np.abs(logit) > GUARD
-        assert np.array_equal((gh[rows] >= cfg.tau)[far], (gref >= cfg.tau)[far])
         sl = slice(watch * C, (watch + 1) * C)
         K[c * C:(c + 1) * C] = k[sl].float().cpu().numpy()
         V[c * C:(c + 1) * C] = v[sl].float().cpu().numpy()
