@@ -95,6 +95,9 @@ def main():
                     help="decode workloads: read only this many pages of each head's global cache per step, picked "
                          "with key landmarks (128 pages of 16 = the 2048 KVs per query of the paper's selection run); "
                          "the step then is promotion + landmark upkeep + page scoring/selection + attention")
+    ap.add_argument("--graph", action="store_true",
+                    help="decode workloads: capture one whole step (all layers) in a HIP graph and time replays "
+                         "instead of direct calls (per-kernel events are then not available)")
     ap.add_argument("--evict", action="store_true",
                     help="time the budgeted eviction (scoring from a 256-query observation window + removal of the "
                          "lowest 10 %) on one layer of the workload's batch with about 4.5K global entries per head")
@@ -200,6 +203,20 @@ def main():
     for st in range(args.warmup):
         one_step(st)
     torch.cuda.synchronize()
+    graph = None
+    if args.graph:
+        assert not sel_b, "--graph times the plain decode step"
+        args.no_kernel_events = True
+        g_static = torch.zeros_like(g_new[0])                     # [L, B, Hk] scores of the step being replayed
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for l in range(L):
+                    pool.decode_step(l, seqs, k_new[l], v_new[l], g_static[l], tau=cfg.tau)
+                    pool.attend(l, seqs, q_new[l], out[l], scale)
+        torch.cuda.current_stream().wait_stream(side)
+        pool.status()                                             # capturing ran nothing: the host counts are reset to the device's
     meta = pool.meta()
     sl0, gl0 = meta["seq_len"].cpu().numpy(), meta["global_len"].cpu().numpy()
     events = None if args.no_kernel_events else HipEvents(2 * args.steps * L)
@@ -208,7 +225,11 @@ def main():
     t0 = time.perf_counter()
     e0.record()
     for st in range(args.warmup, total_steps):
-        one_step(st, events)
+        if graph is not None:
+            g_static.copy_(g_new[st])
+            graph.replay()
+        else:
+            one_step(st, events)
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -264,7 +285,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "layers": L, "q_heads": Hq, "kv_heads": Hk, "head_dim": d,
                    "w_local": W, "page_size": P, "tau": cfg.tau, "ctx_min": int(ctx.min()), "ctx_max": int(ctx.max()),
-                   "select_pages": sel_b,
+                   "select_pages": sel_b, "hip_graph": bool(args.graph),
                    "mean_cached_tokens_per_head": float((np.minimum(sl1, W)[:, :, None] + gl1).mean()),
                    "attend_us_per_layer": roofline.get("kernel_avg_us"),
                    "gpu_ms_per_step": gpu_ms / args.steps, "host_wall_ms_per_step": wall_ms / args.steps},

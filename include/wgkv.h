@@ -165,7 +165,16 @@ int wgkv_prefill_admit(wgkv_pool *pool, int32_t layer, int32_t n_seqs,
  * t mod W (if t >= W) is appended to the global cache iff its stored score
  * >= tau, then (k_new, v_new, g_new) take the slot and t advances.
  *   k_new_dev, v_new_dev : [n_seqs][n_kv_heads][head_dim];  g_new_dev : float [n_seqs][n_kv_heads]
- *   promoted_out_dev     : optional uint8 [n_seqs][n_kv_heads] */
+ *   promoted_out_dev     : optional uint8 [n_seqs][n_kv_heads]
+ * HIP graphs: this call and the decode form of wgkv_attend enqueue kernels only (no
+ * synchronisation, no memset, no allocation) and the kernels take the token counts from
+ * device memory, so a captured sequence of them can be replayed: every replay is one more
+ * token, read from whatever the input buffers hold at that time.  Capturing runs nothing on
+ * the device, and the host-side bookkeeping sees neither captures correctly nor replays at
+ * all: call wgkv_status after the last replay and before the next direct call.  While
+ * replaying, a step that finds no free page (or a full page table) sets the device error
+ * flag and changes nothing.
+ * Errors: INVALID_ARG, OUT_OF_PAGES / PT_OVERFLOW (host-side bounds), HIP. */
 int wgkv_decode_step(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
                      const void *k_new_dev, const void *v_new_dev, const float *g_new_dev,
                      float tau, uint8_t *promoted_out_dev, wgkv_stream stream);
@@ -279,8 +288,9 @@ int wgkv_evict_apply(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32
  * heads ascending, a unit's local pages then its global pages) and clears it. */
 int wgkv_free_seq(wgkv_pool *pool, int32_t seq_id, wgkv_stream stream);
 
-/* Synchronises the stream, reads free_top, the error flag and all lengths back,
- * and replaces the host-side worst-case bounds by the exact values. */
+/* Synchronises the stream, reads free_top, the error flag, all token counts and all
+ * global lengths back, and replaces the host-side bookkeeping (worst-case bounds, token
+ * counts) by the exact values of the device. */
 int wgkv_status(wgkv_pool *pool, wgkv_stream stream, int64_t *pages_free,
                 int32_t *device_error_flag);
 

@@ -264,7 +264,9 @@ __global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs,
     const int u = threadIdx.x;  // n_units <= 1024 = blockDim.x
     int demand = 0, dl = 0, promote = 0, gold = 0, um = 0, slot = 0;
     if (u < n_units) {
-        const int b = u / pv.Hkv, h = u % pv.Hkv, t = cs.t0[b];
+        // the token count comes from device memory, not from the launch arguments, so that a
+        // captured launch can be replayed: every replay is one more token
+        const int b = u / pv.Hkv, h = u % pv.Hkv, t = pv.seq_len[cs.sid[b] * pv.L + a.layer];
         um = unit_meta(pv, cs.sid[b], a.layer, h);
         slot = t % pv.W;
         gold = pv.global_len[um];
@@ -289,7 +291,10 @@ __global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs,
         if (a.promoted_out) a.promoted_out[u] = (uint8_t)promote;
         s_gold[u] = (int)((unsigned)gold | ((unsigned)promote << 31));
     }
-    if (threadIdx.x < cs.n) pv.seq_len[cs.sid[threadIdx.x] * pv.L + a.layer] = cs.t0[threadIdx.x] + 1;
+    __shared__ int s_t[kMaxCallSeqs];
+    if (threadIdx.x < cs.n) s_t[threadIdx.x] = pv.seq_len[cs.sid[threadIdx.x] * pv.L + a.layer];
+    __syncthreads();  // every thread has read the old token counts
+    if (threadIdx.x < cs.n) pv.seq_len[cs.sid[threadIdx.x] * pv.L + a.layer] = s_t[threadIdx.x] + 1;
     if (threadIdx.x == 0) *pv.free_top = top - total;
     __syncthreads();  // tables written above are read below by other threads
     const int lpr = pv.row_bytes >> 4;
@@ -297,7 +302,7 @@ __global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs,
         const int uu = c / lpr, sub = c % lpr;
         const int b = uu / pv.Hkv, h = uu % pv.Hkv;
         const int m = unit_meta(pv, cs.sid[b], a.layer, h);
-        const int sl = cs.t0[b] % pv.W;
+        const int sl = s_t[b] % pv.W;
         char *rp = page_ptr(pv, pv.local_pt[(size_t)m * pv.nlp + (sl >> pv.logP)]) +
                    (size_t)(sl & (pv.P - 1)) * pv.row_bytes + sub * 16;
         const int gi = s_gold[uu];

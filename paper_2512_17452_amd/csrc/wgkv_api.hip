@@ -56,7 +56,7 @@ namespace {
 
 constexpr int kPrefillBlkHost = 1024;   // must match kPrefillBlk in admit.hip
 constexpr int kAttnGridMax = 2048;      // upper bound on the decode-attention grid (blocks of 4 waves)
-constexpr int kAttnMinTilesPerWave = 4;
+constexpr int kAttnMinTilesPerWave = 16;  // below that a share is shorter than the fold of its partial
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -620,10 +620,11 @@ int wgkv_status(wgkv_pool *p, wgkv_stream stream, int64_t *pages_free, int32_t *
     if (!p) return WGKV_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     int32_t top = 0, flag = 0;
-    std::vector<int32_t> gl(p->g_ub.size());
+    std::vector<int32_t> gl(p->g_ub.size()), sl_dev(p->seq_len_h.size());
     if (hipMemcpyAsync(&top, p->view.free_top, 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipMemcpyAsync(&flag, p->view.err_flag, 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipMemcpyAsync(gl.data(), p->view.global_len, gl.size() * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipMemcpyAsync(sl_dev.data(), p->view.seq_len, sl_dev.size() * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess)
         return WGKV_ERR_HIP;
     if (pages_free) *pages_free = top;
@@ -632,6 +633,10 @@ int wgkv_status(wgkv_pool *p, wgkv_stream stream, int64_t *pages_free, int32_t *
     const wgkv_config &c = p->cfg;
     int64_t used = 0;
     for (size_t sl = 0; sl < p->touched_h.size(); sl++) {
+        // token counts as the device has them: replays of a captured decode step advance them
+        // without the host seeing it
+        p->seq_len_h[sl] = sl_dev[sl];
+        p->touched_h[sl] = sl_dev[sl] > 0;
         if (p->touched_h[sl]) used += (int64_t)p->view.nlp * c.n_kv_heads;
         for (int h = 0; h < c.n_kv_heads; h++) {
             const size_t i = sl * c.n_kv_heads + h;
