@@ -38,6 +38,7 @@ struct AttendArgs {
     float *out;               // [n_seqs][Hq][d]
     float *part_ml;           // [(waves + n_units)][G][2]
     float *part_acc;          // [(waves + n_units)][G][d]
+    uint32_t part_ml_bytes, part_acc_bytes;
     int32_t *counters;        // [n_units] zero between calls: waves done per unit
     // optional page selection: only these pages of each head's global cache are read
     const int32_t *sel_pages; // [n_units][sel_stride] ascending indices into the head's global table, or NULL
@@ -100,11 +101,13 @@ __device__ __forceinline__ float bf16_hi(uint32_t x) { return __uint_as_float(x 
 
 // Partials cross compute units (and their L2 slices) inside one launch: they are
 // written and read with device-coherent accesses, so no cache-wide flush is needed.
-__device__ __forceinline__ void st_coherent(float *p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_coherent(const float *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Buffer accesses carry the same cache policy as a device-scope atomic access (sc1) at up to
+// 16 bytes per lane, and an access outside the buffer reads zero or is dropped.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+constexpr int kCoherent = 16;  // cache-policy operand of the buffer builtins: sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t part_rsrc(float *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(p, 0, (int)bytes, 0x00020000);  // raw buffer, 32-bit data format
 }
 
 template <int DT, int D, int G>
@@ -526,16 +529,42 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                 }
             }
         } else {
-            const size_t slot = (size_t)wid + u;
-            if (lane < LPT) {
+            // Partials: per (slot, head) the d values as [16-byte chunk of a lane][lane of the row
+            // group][4], so that one store or load of a row group covers contiguous memory.  Every
+            // row group holds the folded state; group grp handles heads grp, grp + NG, ...
+            constexpr int NG = TPW, GT = (G + NG - 1) / NG, NJ = EPL / 4;
+            const __amdgpu_buffer_rsrc_t r_acc = part_rsrc(a.part_acc, a.part_acc_bytes);
+            const __amdgpu_buffer_rsrc_t r_ml = part_rsrc(a.part_ml, a.part_ml_bytes);
+            const uint32_t slot = (uint32_t)(wid + u);
 #pragma unroll
-                for (int g = 0; g < G; g++) {
+            for (int t = 0; t < GT; t++) {
+                // the state of head grp + NG * t, picked without indexing registers by a run-time value
+                float v[EPL], vm = m[NG * t], vl = l[NG * t];
 #pragma unroll
-                    // stored as [e][sub]: the 16 lanes of one store cover 64 contiguous bytes
-                    for (int e = 0; e < EPL; e++) st_coherent(&a.part_acc[((slot * G + g) * EPL + e) * LPT + sub], acc[g][e]);
+                for (int e = 0; e < EPL; e++) v[e] = acc[NG * t][e];
+#pragma unroll
+                for (int gg = 1; gg < NG; gg++) {
+                    constexpr int last = G - 1;
+                    const int gs = NG * t + gg < G ? NG * t + gg : last;
+                    if (NG * t + gg < G && grp == gg) {
+                        vm = m[gs];
+                        vl = l[gs];
+#pragma unroll
+                        for (int e = 0; e < EPL; e++) v[e] = acc[gs][e];
+                    }
+                }
+                const int g = grp + NG * t;
+                if (g < G) {
+                    const uint32_t rec = slot * G + g;
+#pragma unroll
+                    for (int j = 0; j < NJ; j++) {
+                        const u32x4 pk = {__float_as_uint(v[4 * j]), __float_as_uint(v[4 * j + 1]),
+                                          __float_as_uint(v[4 * j + 2]), __float_as_uint(v[4 * j + 3])};
+                        __builtin_amdgcn_raw_buffer_store_b128(pk, r_acc, rec * (D * 4) + (j * LPT + sub) * 16, 0, kCoherent);
+                    }
                     if (sub == 0) {
-                        st_coherent(&a.part_ml[(slot * G + g) * 2], m[g]);
-                        st_coherent(&a.part_ml[(slot * G + g) * 2 + 1], l[g]);
+                        const u32x2 pk = {__float_as_uint(vm), __float_as_uint(vl)};
+                        __builtin_amdgcn_raw_buffer_store_b64(pk, r_ml, rec * 8, 0, kCoherent);
                     }
                 }
             }
@@ -545,43 +574,65 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
             if (lane == 0) prev = __hip_atomic_fetch_add(&a.counters[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             prev = __builtin_amdgcn_readfirstlane(prev);
             if (prev == w_last - w_first) {  // every other wave of this unit is done: fold
-                constexpr int OPL = G * D / 64;  // outputs per lane, all of one head
-                // lane -> OPL consecutive values of one head in the stored [e][sub] order
-                const int g = (lane * OPL) / D, e0 = (lane * OPL) % D;
-                float Mx = -INFINITY, Ls = 0.f, A[OPL];
+                float Mx[GT], Ls[GT], A[GT][EPL];
 #pragma unroll
-                for (int e = 0; e < OPL; e++) A[e] = 0.f;
+                for (int t = 0; t < GT; t++) {
+                    Mx[t] = -INFINITY;
+                    Ls[t] = 0.f;
+#pragma unroll
+                    for (int e = 0; e < EPL; e++) A[t][e] = 0.f;
+                }
                 // the partials sit in device-coherent memory, one round trip away: ask for
-                // several of them before folding any
-                constexpr int MB = (OPL <= 8) ? 16 : 4;
+                // several of them, 16 bytes a lane and load, before folding any
+                constexpr int R = GT * (EPL + 2);  // registers one partial takes
+                constexpr int BUD = FAST ? 160 : 80;  // registers the batch may take without costing the main loop waves
+                constexpr int MB = BUD / R > 16 ? 16 : (BUD / R < 2 ? 2 : BUD / R);
+                static_assert(MB * GT * (NJ + 1) < 64, "more loads in flight than the wave can count");
                 for (int w0 = w_first; w0 <= w_last; w0 += MB) {
-                    float mv[MB], lv[MB], av[MB][OPL];
+                    u32x2 mlv[MB][GT];
+                    u32x4 av[MB][GT][NJ];
 #pragma unroll
                     for (int i = 0; i < MB; i++) {
-                        const size_t sl = ((size_t)min(w0 + i, w_last) + u) * G + g;
-                        mv[i] = ld_coherent(&a.part_ml[sl * 2]);
-                        lv[i] = ld_coherent(&a.part_ml[sl * 2 + 1]);
+                        const uint32_t sl = (uint32_t)(min(w0 + i, w_last) + u);
 #pragma unroll
-                        for (int e = 0; e < OPL; e++) av[i][e] = ld_coherent(&a.part_acc[sl * D + e0 + e]);
+                        for (int t = 0; t < GT; t++) {
+                            const uint32_t rec = sl * G + min(grp + NG * t, G - 1);
+                            mlv[i][t] = __builtin_amdgcn_raw_buffer_load_b64(r_ml, rec * 8, 0, kCoherent);
+#pragma unroll
+                            for (int j = 0; j < NJ; j++)
+                                av[i][t][j] = __builtin_amdgcn_raw_buffer_load_b128(r_acc, rec * (D * 4) + (j * LPT + sub) * 16, 0, kCoherent);
+                        }
                     }
 #pragma unroll
                     for (int i = 0; i < MB; i++) {
                         if (w0 + i <= w_last) {
-                            const float mn = fmaxf(Mx, mv[i]);
-                            const float ms = mn == -INFINITY ? 0.f : mn;
-                            const float ca = __builtin_amdgcn_exp2f(Mx - ms), cb = __builtin_amdgcn_exp2f(mv[i] - ms);
-                            Ls = Ls * ca + lv[i] * cb;
 #pragma unroll
-                            for (int e = 0; e < OPL; e++) A[e] = A[e] * ca + av[i][e] * cb;
-                            Mx = mn;
+                            for (int t = 0; t < GT; t++) {
+                                const float mi = __uint_as_float(mlv[i][t].x), li = __uint_as_float(mlv[i][t].y);
+                                const float mn = fmaxf(Mx[t], mi);
+                                const float ms = mn == -INFINITY ? 0.f : mn;
+                                const float ca = __builtin_amdgcn_exp2f(Mx[t] - ms), cb = __builtin_amdgcn_exp2f(mi - ms);
+                                Ls[t] = Ls[t] * ca + li * cb;
+#pragma unroll
+                                for (int j = 0; j < NJ; j++) {
+                                    A[t][4 * j] = A[t][4 * j] * ca + __uint_as_float(av[i][t][j].x) * cb;
+                                    A[t][4 * j + 1] = A[t][4 * j + 1] * ca + __uint_as_float(av[i][t][j].y) * cb;
+                                    A[t][4 * j + 2] = A[t][4 * j + 2] * ca + __uint_as_float(av[i][t][j].z) * cb;
+                                    A[t][4 * j + 3] = A[t][4 * j + 3] * ca + __uint_as_float(av[i][t][j].w) * cb;
+                                }
+                                Mx[t] = mn;
+                            }
                         }
                     }
                 }
-                const float inv = 1.0f / Ls;
 #pragma unroll
-                for (int e = 0; e < OPL; e++) {
-                    const int r = e0 + e;  // position in the stored order: r = e_idx * LPT + sub
-                    o[g * D + (r % LPT) * EPL + r / LPT] = A[e] * inv;
+                for (int t = 0; t < GT; t++) {
+                    const int g = grp + NG * t;
+                    if (g < G) {
+                        const float inv = 1.0f / Ls[t];
+#pragma unroll
+                        for (int e = 0; e < EPL; e++) o[g * D + sub * EPL + e] = A[t][e] * inv;
+                    }
                 }
                 if (lane == 0) __hip_atomic_store(&a.counters[u], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -658,6 +709,10 @@ hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int
     a.part_ml = (float *)w;
     size_t off = (slots * pv.G * 2 * sizeof(float) + 255) & ~(size_t)255;
     a.part_acc = (float *)(w + off);
+    const size_t acc_bytes = slots * pv.G * pv.d * sizeof(float);
+    if (acc_bytes > 0x7fffffffu) return hipErrorInvalidValue;  // 32-bit offsets into the partials
+    a.part_ml_bytes = (uint32_t)(slots * pv.G * 2 * sizeof(float));
+    a.part_acc_bytes = (uint32_t)acc_bytes;
     for (int i = 0; i < n_seqs; i++) a.sid[i] = sids[i];
     if (pv.dtype == WGKV_BF16 && pv.d == 128) return launch_g<WGKV_BF16, 128>(pv, a, n_cu, grid_max, st, ev0, ev1);
     if (pv.dtype == WGKV_BF16 && pv.d == 64) return launch_g<WGKV_BF16, 64>(pv, a, n_cu, grid_max, st, ev0, ev1);
