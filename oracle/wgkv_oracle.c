@@ -32,7 +32,12 @@
  *      appendix on the synergy with selection) and attention over the selection.
  *
  *  (5) the gates that produce the scores: the linear gate of the chunked-prefill
- *      workload and the Write-Gate MLP of Sec. 3.2 (at the end of the file).
+ *      workload and the Write-Gate MLP of Sec. 3.2.
+ *
+ *  (6) the training-time attention with the soft gate as a log-space bias
+ *      (Sec. 3.2, "Write-Gated Attention" and "Log-space transformation"), forward
+ *      and the gradients with respect to q, k, v and the gate scores (at the end of
+ *      the file).
  *
  * All floating-point work is done in double; inputs arrive as float (the
  * exact widening of bf16 or fp32 data).  Threshold tests are done on the
@@ -861,5 +866,144 @@ int orc_gate_mlp(int64_t T, int H, int d, int width, const float *k, const float
         }
         free(x);
     }
+    return ORC_OK;
+}
+
+
+/*
+ * Training-time Write-Gated Attention of a whole sequence (Sec. 3.2): causal softmax of
+ *   s_ij = scale * q_i . k_j + log(m_ij + eps),   m_ij = max(1(i - j < W), g_j),
+ * the log-space form of weighting exp(q_i . k_j * scale) by m_ij ("Log-space transformation
+ * for efficient training", with the small eps the text adds inside the logarithm).
+ *   Q: [T][Hq][d]   K, V: [T][Hkv][d]   g: [T][Hkv]; query head qh reads kv head qh / (Hq/Hkv).
+ *   out: [T][Hq][d], lse: [T][Hq] = log sum_j exp(s_ij) (natural logarithm); either may be NULL.
+ */
+int orc_soft_attn_forward(int64_t T, int Hq, int Hkv, int d, int W, double scale, double eps,
+                          const float *Q, const float *K, const float *V, const float *g,
+                          double *out, double *lse) {
+    if (T < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv || d < 1 || W < 1) return ORC_ERR_ARG;
+    const int G = Hq / Hkv;
+    int rc_all = ORC_OK;
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int64_t i = 0; i < T; i++) {
+        double *s = (double *)malloc(sizeof(double) * (size_t)(i + 1));
+        if (!s) { rc_all = ORC_ERR_NOMEM; continue; }
+        for (int qh = 0; qh < Hq; qh++) {
+            const int h = qh / G;
+            const float *qi = Q + ((size_t)i * Hq + qh) * d;
+            double mx = -INFINITY;
+            for (int64_t j = 0; j <= i; j++) {
+                const size_t row = (size_t)j * Hkv + h;
+                double dot = 0.0;
+                for (int e = 0; e < d; e++) dot += (double)qi[e] * (double)K[row * d + e];
+                double m = (i - j < W) ? 1.0 : 0.0;
+                if ((double)g[row] > m) m = (double)g[row];
+                s[j] = scale * dot + log(m + eps);
+                if (s[j] > mx) mx = s[j];
+            }
+            double den = 0.0;
+            for (int64_t j = 0; j <= i; j++) den += exp(s[j] - mx);
+            const double l = mx + log(den);
+            if (lse) lse[(size_t)i * Hq + qh] = l;
+            if (out) {
+                double *o = out + ((size_t)i * Hq + qh) * d;
+                for (int e = 0; e < d; e++) o[e] = 0.0;
+                for (int64_t j = 0; j <= i; j++) {
+                    const double p = exp(s[j] - l);
+                    const float *vj = V + ((size_t)j * Hkv + h) * d;
+                    for (int e = 0; e < d; e++) o[e] += p * (double)vj[e];
+                }
+            }
+        }
+        free(s);
+    }
+    return rc_all;
+}
+
+/*
+ * Gradients of a scalar loss through orc_soft_attn_forward, given dO = dLoss/dOut [T][Hq][d].
+ * With p_ij = exp(s_ij - lse_i), o_i = sum_j p_ij v_j:
+ *   dV_j  = sum_i p_ij dO_i
+ *   dS_ij = p_ij (dO_i . v_j - dO_i . o_i)          (derivative with respect to s_ij)
+ *   dQ_i  = scale sum_j dS_ij k_j      dK_j = scale sum_i dS_ij q_i
+ *   dg_j  = sum_i dS_ij * d log(m_ij + eps)/dg_j = sum_{i : g_j > 1(i-j<W)} dS_ij / (g_j + eps)
+ * (m_ij follows g_j only where g_j exceeds the window indicator).  A kv head collects the terms
+ * of all query heads of its group.  dQ: [T][Hq][d], dK, dV: [T][Hkv][d], dg: [T][Hkv].
+ */
+int orc_soft_attn_backward(int64_t T, int Hq, int Hkv, int d, int W, double scale, double eps,
+                           const float *Q, const float *K, const float *V, const float *g,
+                           const float *dO, double *dQ, double *dK, double *dV, double *dg) {
+    if (T < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv || d < 1 || W < 1) return ORC_ERR_ARG;
+    const int G = Hq / Hkv;
+    int rc_all = ORC_OK;
+    for (size_t x = 0; x < (size_t)T * Hq * d; x++) dQ[x] = 0.0;
+    for (size_t x = 0; x < (size_t)T * Hkv * d; x++) { dK[x] = 0.0; dV[x] = 0.0; }
+    for (size_t x = 0; x < (size_t)T * Hkv; x++) dg[x] = 0.0;
+    /* a kv head owns its rows of dK, dV, dg: one thread per kv head, no shared sums */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < Hkv; h++) {
+        double *p = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1));
+        double *o = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!p || !o) { free(p); free(o); rc_all = ORC_ERR_NOMEM; continue; }
+        for (int jq = 0; jq < G; jq++) {
+            const int qh = h * G + jq;
+            for (int64_t i = 0; i < T; i++) {
+                const float *qi = Q + ((size_t)i * Hq + qh) * d;
+                const float *doi = dO + ((size_t)i * Hq + qh) * d;
+                double mx = -INFINITY;
+                for (int64_t j = 0; j <= i; j++) {
+                    const size_t row = (size_t)j * Hkv + h;
+                    double dot = 0.0;
+                    for (int e = 0; e < d; e++) dot += (double)qi[e] * (double)K[row * d + e];
+                    double m = (i - j < W) ? 1.0 : 0.0;
+                    if ((double)g[row] > m) m = (double)g[row];
+                    p[j] = scale * dot + log(m + eps);
+                    if (p[j] > mx) mx = p[j];
+                }
+                double den = 0.0;
+                for (int64_t j = 0; j <= i; j++) { p[j] = exp(p[j] - mx); den += p[j]; }
+                for (int e = 0; e < d; e++) o[e] = 0.0;
+                for (int64_t j = 0; j <= i; j++) {
+                    p[j] /= den;
+                    const float *vj = V + ((size_t)j * Hkv + h) * d;
+                    for (int e = 0; e < d; e++) o[e] += p[j] * (double)vj[e];
+                }
+                double Di = 0.0;
+                for (int e = 0; e < d; e++) Di += (double)doi[e] * o[e];
+                double *dqi = dQ + ((size_t)i * Hq + qh) * d;
+                for (int64_t j = 0; j <= i; j++) {
+                    const size_t row = (size_t)j * Hkv + h;
+                    const float *kj = K + row * d, *vj = V + row * d;
+                    double dP = 0.0;
+                    for (int e = 0; e < d; e++) dP += (double)doi[e] * (double)vj[e];
+                    const double dS = p[j] * (dP - Di);
+                    for (int e = 0; e < d; e++) {
+                        dV[row * d + e] += p[j] * (double)doi[e];
+                        dqi[e] += scale * dS * (double)kj[e];
+                        dK[row * d + e] += scale * dS * (double)qi[e];
+                    }
+                    const double ind = (i - j < W) ? 1.0 : 0.0;
+                    if ((double)g[row] > ind) dg[row] += dS / ((double)g[row] + eps);
+                }
+            }
+        }
+        free(p); free(o);
+    }
+    return rc_all;
+}
+
+/*
+ * Sparsity term of the training objective (Sec. 3.3): the mean over all n scores of
+ * g + g (1 - g), and its derivative (2 - 2 g) / n with respect to every score.
+ */
+int orc_sparsity_loss(int64_t n, const float *g, double *loss, double *dg) {
+    if (n < 1) return ORC_ERR_ARG;
+    double acc = 0.0;
+    for (int64_t x = 0; x < n; x++) {
+        const double v = (double)g[x];
+        acc += v + v * (1.0 - v);
+        if (dg) dg[x] = (2.0 - 2.0 * v) / (double)n;
+    }
+    *loss = acc / (double)n;
     return ORC_OK;
 }

@@ -86,6 +86,12 @@ def lib():
                                       C.POINTER(C.c_float), C.c_int64, C.POINTER(C.c_float),
                                       C.POINTER(C.c_int64), C.c_int, C.c_double,
                                       C.POINTER(C.c_double)]
+        fp, dp = C.POINTER(C.c_float), C.POINTER(C.c_double)
+        L.orc_soft_attn_forward.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double,
+                                            fp, fp, fp, fp, dp, dp]
+        L.orc_soft_attn_backward.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double,
+                                             fp, fp, fp, fp, fp, dp, dp, dp, dp]
+        L.orc_sparsity_loss.argtypes = [C.c_int64, fp, dp, dp]
         L.orc_linear_gate.argtypes = [C.c_int64, C.c_int, C.c_int, C.POINTER(C.c_float),
                                       C.POINTER(C.c_float), C.POINTER(C.c_double),
                                       C.POINTER(C.c_double)]
@@ -310,6 +316,53 @@ def attend_soft(K, V, g, q, q_pos, w_local, scale, use_log=False, eps=0.0):
     if rc:
         raise OracleError(rc)
     return out
+
+
+def soft_attn_forward(Q, K, V, g, w_local, scale, eps):
+    """Training-time Write-Gated Attention of one sequence (Sec. 3.2, log-space form):
+    (out [T, Hq, d], lse [T, Hq]) in fp64 for Q [T, Hq, d], K, V [T, Hkv, d], g [T, Hkv]."""
+    Q = _f32(Q); K = _f32(K); V = _f32(V); g = _f32(g)
+    T, Hq, d = Q.shape
+    Hk = K.shape[1]
+    assert K.shape == (T, Hk, d) and V.shape == (T, Hk, d) and g.shape == (T, Hk)
+    out = np.zeros((T, Hq, d), dtype=np.float64)
+    lse = np.zeros((T, Hq), dtype=np.float64)
+    rc = lib().orc_soft_attn_forward(T, Hq, Hk, d, int(w_local), float(scale), float(eps), _p(Q, C.c_float),
+                                     _p(K, C.c_float), _p(V, C.c_float), _p(g, C.c_float),
+                                     _p(out, C.c_double), _p(lse, C.c_double))
+    if rc:
+        raise OracleError(rc)
+    return out, lse
+
+
+def soft_attn_backward(Q, K, V, g, dO, w_local, scale, eps):
+    """(dQ, dK, dV, dg) in fp64 of a loss with dLoss/dOut = dO through soft_attn_forward."""
+    Q = _f32(Q); K = _f32(K); V = _f32(V); g = _f32(g); dO = _f32(dO)
+    T, Hq, d = Q.shape
+    Hk = K.shape[1]
+    assert K.shape == (T, Hk, d) and V.shape == (T, Hk, d) and g.shape == (T, Hk) and dO.shape == Q.shape
+    dQ = np.zeros((T, Hq, d), dtype=np.float64)
+    dK = np.zeros((T, Hk, d), dtype=np.float64)
+    dV = np.zeros((T, Hk, d), dtype=np.float64)
+    dg = np.zeros((T, Hk), dtype=np.float64)
+    rc = lib().orc_soft_attn_backward(T, Hq, Hk, d, int(w_local), float(scale), float(eps), _p(Q, C.c_float),
+                                      _p(K, C.c_float), _p(V, C.c_float), _p(g, C.c_float), _p(dO, C.c_float),
+                                      _p(dQ, C.c_double), _p(dK, C.c_double), _p(dV, C.c_double),
+                                      _p(dg, C.c_double))
+    if rc:
+        raise OracleError(rc)
+    return dQ, dK, dV, dg
+
+
+def sparsity_loss(g):
+    """(loss, dloss/dg) of the sparsity term of the training objective (Sec. 3.3) over all scores."""
+    g = _f32(g)
+    loss = C.c_double(0.0)
+    dg = np.zeros(g.shape, dtype=np.float64)
+    rc = lib().orc_sparsity_loss(g.size, _p(g, C.c_float), C.byref(loss), _p(dg, C.c_double))
+    if rc:
+        raise OracleError(rc)
+    return loss.value, dg
 
 
 def linear_gate(hidden, w):
