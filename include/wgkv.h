@@ -121,6 +121,53 @@ int wgkv_gate_scores(int32_t dtype, int64_t n_tokens, int32_t hidden_dim, int32_
                      const void *hidden_dev, const void *gate_w_dev, float *g_out_dev,
                      wgkv_stream stream);
 
+/* Sec. 3.2, "Write-Gated Attention" in its log-space form (the attention that trains the
+ * gate): for every sequence of the call, query position i and query head qh (kv head
+ * h = qh / (n_q_heads / n_kv_heads)),
+ *   s_ij  = scale * q[i][qh] . k[j][h] + log(max(1(i - j < w_local), g[j][h]) + eps),  j <= i
+ *   out[i][qh] = sum_j softmax_j(s_ij) v[j][h],      lse[i][qh] = log sum_j exp(s_ij).
+ * The paper says only that eps is small; it is an argument (eps >= 0).
+ *   n_tokens_host [n_seqs] : tokens per sequence (host); rows of all tensors are the sequences
+ *                            packed one after the other, at most 2^24 - 1 rows in total
+ *   q_dev [rows][n_q_heads][head_dim], k_dev, v_dev [rows][n_kv_heads][head_dim] bf16, 16-byte
+ *   aligned; g_dev float [rows][n_kv_heads]
+ *   out_dev float [rows][n_q_heads][head_dim] (16-byte aligned), lse_dev float [rows][n_q_heads]
+ * Products run on the matrix cores in bf16 with fp32 accumulation; the weights are rounded to
+ * bf16 before the second product and the denominator sums the rounded weights.
+ * Supported: dtype WGKV_BF16, head_dim 128, n_q_heads = 4 * n_kv_heads; anything else returns
+ * INVALID_ARG.  All buffers are device memory owned by the caller; the call only enqueues work
+ * on `stream`.  Errors: INVALID_ARG, HIP. */
+int wgkv_soft_attn_forward(int32_t dtype, int32_t n_seqs, const int32_t *n_tokens_host,
+                           int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                           int32_t w_local, const void *q_dev, const void *k_dev,
+                           const void *v_dev, const float *g_dev, float scale, float eps,
+                           float *out_dev, float *lse_dev, wgkv_stream stream);
+
+/* Bytes of workspace wgkv_soft_attn_backward needs for total_tokens packed rows. */
+size_t wgkv_soft_attn_workspace_bytes(int64_t total_tokens, int32_t n_q_heads);
+
+/* Gradients through wgkv_soft_attn_forward (same Sec. 3.2 equations) of a loss with
+ * dLoss/dOut = dout.  With p_ij = exp(s_ij - lse_i):
+ *   dv[j][h] = sum_{i, qh of h} p_ij dout[i][qh]
+ *   dS_ij    = p_ij (dout[i][qh] . v[j][h] - dout[i][qh] . out[i][qh])
+ *   dq[i][qh] = scale sum_j dS_ij k[j][h],   dk[j][h] = scale sum_{i, qh of h} dS_ij q[i][qh]
+ *   dg[j][h] = sum over (i, qh of h) where g_j exceeds 1(i - j < w_local) of dS_ij / (g_j + eps)
+ * Inputs as in the forward call plus its results out_dev and lse_dev, and
+ *   dout_dev bf16 [rows][n_q_heads][head_dim], 16-byte aligned.
+ * Outputs (all float, 16-byte aligned, fully overwritten): dq_dev [rows][n_q_heads][head_dim],
+ * dk_dev, dv_dev [rows][n_kv_heads][head_dim], dg_dev [rows][n_kv_heads].
+ * workspace_dev: wgkv_soft_attn_workspace_bytes(rows, n_q_heads) bytes, contents undefined
+ * before and after.  p and dS are rounded to bf16 before the products that consume them.
+ * Every output element is written by exactly one wave in a fixed order: results do not change
+ * from run to run.  Errors: INVALID_ARG, WORKSPACE, HIP. */
+int wgkv_soft_attn_backward(int32_t dtype, int32_t n_seqs, const int32_t *n_tokens_host,
+                            int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                            int32_t w_local, const void *q_dev, const void *k_dev,
+                            const void *v_dev, const float *g_dev, float scale, float eps,
+                            const float *out_dev, const float *lse_dev, const void *dout_dev,
+                            float *dq_dev, float *dk_dev, float *dv_dev, float *dg_dev,
+                            void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
+
 /* Sec. 3.2, feature equation and gate equation (the Write-Gate MLP), per token t and
  * kv head h:  x = [RMSNorm(k[t][h]) ; RMSNorm(k_rope[t][h])],
  *             g[t][h] = sigmoid(W2[h] . GELU(W1[h] x + b1[h]) + b2[h]).

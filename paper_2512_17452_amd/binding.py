@@ -12,7 +12,8 @@ F32, BF16 = 0, 1
 EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
     "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
-    "wgkv_quest_select", "wgkv_attend_selected", "wgkv_free_seq",
+    "wgkv_quest_select", "wgkv_attend_selected", "wgkv_soft_attn_forward", "wgkv_soft_attn_workspace_bytes",
+    "wgkv_soft_attn_backward", "wgkv_free_seq",
     "wgkv_status", "wgkv_set_profile_events", "wgkv_destroy",
 ]
 
@@ -84,6 +85,11 @@ def load_library():
     L.wgkv_init_pool.argtypes = [C.POINTER(_CConfig), vp, sz, vp, sz, vp, C.POINTER(vp)]
     L.wgkv_gate_scores.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp]
     L.wgkv_gate_mlp_scores.argtypes = [i32, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp]
+    L.wgkv_soft_attn_forward.argtypes = [i32, i32, pi32, i32, i32, i32, i32, vp, vp, vp, vp, f32, f32, vp, vp, vp]
+    L.wgkv_soft_attn_workspace_bytes.argtypes = [i64, i32]
+    L.wgkv_soft_attn_workspace_bytes.restype = sz
+    L.wgkv_soft_attn_backward.argtypes = [i32, i32, pi32, i32, i32, i32, i32, vp, vp, vp, vp, f32, f32, vp, vp, vp,
+                                          vp, vp, vp, vp, vp, sz, vp]
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
@@ -134,6 +140,48 @@ def gate_scores(hidden, gate_w, out=None):
     dt = F32 if hidden.dtype == torch.float32 else BF16
     _check(L.wgkv_gate_scores(dt, T, dim, Hk, _ptr(hidden), _ptr(gate_w), _ptr(out), _stream()), "wgkv_gate_scores")
     return out
+
+
+def soft_attn_forward(q, k, v, g, n_tokens, w_local, scale, eps):
+    """wgkv_soft_attn_forward: training-time Write-Gated Attention of packed sequences.
+    q [rows, Hq, d], k, v [rows, Hkv, d] bfloat16, g [rows, Hkv] float32, n_tokens: tokens per
+    sequence.  Returns (out float32 [rows, Hq, d], lse float32 [rows, Hq])."""
+    import torch
+    L = load_library()
+    rows, Hq, d = q.shape
+    Hk = k.shape[1]
+    assert k.shape == (rows, Hk, d) and v.shape == k.shape and g.shape == (rows, Hk) and sum(n_tokens) == rows
+    assert q.dtype == torch.bfloat16 and k.dtype == q.dtype and v.dtype == q.dtype and g.dtype == torch.float32
+    assert all(t.is_contiguous() for t in (q, k, v, g))
+    out = torch.empty((rows, Hq, d), dtype=torch.float32, device=q.device)
+    lse = torch.empty((rows, Hq), dtype=torch.float32, device=q.device)
+    rc = L.wgkv_soft_attn_forward(BF16, len(n_tokens), _ids(n_tokens), Hq, Hk, d, int(w_local), _ptr(q), _ptr(k),
+                                  _ptr(v), _ptr(g), float(scale), float(eps), _ptr(out), _ptr(lse), _stream())
+    if rc:
+        raise WgkvError(rc, "wgkv_soft_attn_forward")
+    return out, lse
+
+
+def soft_attn_backward(q, k, v, g, out, lse, dout, n_tokens, w_local, scale, eps):
+    """wgkv_soft_attn_backward: (dq, dk, dv, dg) float32 for dout bfloat16 [rows, Hq, d]."""
+    import torch
+    L = load_library()
+    rows, Hq, d = q.shape
+    Hk = k.shape[1]
+    assert dout.shape == q.shape and dout.dtype == torch.bfloat16 and out.dtype == torch.float32
+    assert all(t.is_contiguous() for t in (q, k, v, g, out, lse, dout))
+    dq = torch.empty((rows, Hq, d), dtype=torch.float32, device=q.device)
+    dk = torch.empty((rows, Hk, d), dtype=torch.float32, device=q.device)
+    dv = torch.empty((rows, Hk, d), dtype=torch.float32, device=q.device)
+    dg = torch.empty((rows, Hk), dtype=torch.float32, device=q.device)
+    nb = int(L.wgkv_soft_attn_workspace_bytes(rows, Hq))
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device=q.device)
+    rc = L.wgkv_soft_attn_backward(BF16, len(n_tokens), _ids(n_tokens), Hq, Hk, d, int(w_local), _ptr(q), _ptr(k),
+                                   _ptr(v), _ptr(g), float(scale), float(eps), _ptr(out), _ptr(lse), _ptr(dout),
+                                   _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _ptr(ws), nb, _stream())
+    if rc:
+        raise WgkvError(rc, "wgkv_soft_attn_backward")
+    return dq, dk, dv, dg
 
 
 def gate_mlp_scores(k, k_rope, w1, b1, w2, b2, eps=1e-6, out=None):

@@ -1,0 +1,644 @@
+// Training-time Write-Gated Attention (Sec. 3.2, "Write-Gated Attention" and "Log-space
+// transformation for efficient training") on the gfx950 matrix cores: causal attention of a
+// whole sequence with the additive bias
+//     B_ij = log(m_ij + eps),   m_ij = max(1(i - j < W_local), g_j),
+// forward with the row log-sum-exp, and the gradients with respect to q, k, v and g.
+//
+//   soft_attn_fwd_kernel       block = 64 query positions x the 4 query heads of a kv head,
+//                              key tiles of 32 staged in LDS; S^T = K Q^T, O^T = V^T P^T
+//   soft_attn_rowdot_kernel    D_i = dO_i . O_i per (position, query head)
+//   soft_attn_bwd_dq_kernel    same blocking as the forward: S^T and dP^T = V dO^T per key tile,
+//                              dS^T = P^T (dP^T - D), dQ^T += K^T dS^T
+//   soft_attn_bwd_dkv_kernel   block = 128 keys of a kv head; its waves are (32 keys) x (role):
+//                              role 0 recomputes S = Q K^T and P and accumulates dV^T += dO^T P,
+//                              role 1 computes dP = dO V^T, takes P through LDS, forms dS and
+//                              accumulates dK^T += Q^T dS and the sum that becomes dg
+//
+// All products are v_mfma_f32_32x32x16_bf16 with fp32 accumulation; every operand that is
+// reused over the whole loop (the block's own rows) sits in registers, the streamed tiles
+// go through LDS in two forms: row-major (rows are the M side of a product over d) and
+// transposed (rows are d, for the products that contract over positions).  A lane of an
+// accumulator tile owns one column, so per-column quantities are plain scalars.
+#include <climits>
+
+#include "wgkv_dev.h"
+
+namespace wgkv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 sa_bf16x8_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 sa_bf16x2_t;
+typedef __attribute__((ext_vector_type(16))) float sa_f32x16_t;
+
+constexpr int kSaD = 128;       // head_dim
+constexpr int kSaG = 4;         // query heads per kv head
+constexpr int kSaQ = 64;        // query positions per block (forward, dQ)
+constexpr int kSaT = 32;        // positions per streamed tile
+constexpr int kSaKB = 128;      // keys per block (dK/dV)
+constexpr int kSaRm = 272;      // bytes per row of a row-major tile in LDS (256 + 16 pad)
+constexpr int kSaTr = 72;       // bytes per d row of a transposed tile (64 + 8 pad)
+
+struct SoftSeqs {
+    int32_t n;
+    int32_t ntok[kMaxCallSeqs];
+    int32_t base[kMaxCallSeqs];  // first packed row of the sequence
+};
+
+struct SoftArgs {
+    int Hq, Hkv, W;
+    float scale_log2e;      // scale * log2(e): scores are kept in base-2 units
+    float scale;
+    float eps;
+    const char *q, *k, *v;  // bf16 [rows][heads][128]
+    const float *g;         // [rows][Hkv]
+    float *out;             // [rows][Hq][128]
+    float *lse;             // [rows][Hq], natural logarithm
+    // backward only
+    const char *dout;       // bf16 [rows][Hq][128]
+    float *rowdot;          // [rows][Hq]
+    float *dq, *dk, *dv, *dg;
+};
+
+__device__ __forceinline__ uint32_t sa_pack(float lo, float hi) {
+    sa_bf16x2_t t = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, t);
+}
+
+// The two bias values of a key in base-2 units: inside the window m = max(1, g), outside m = max(0, g).
+__device__ __forceinline__ void sa_bias(float gj, float eps, float &b_in, float &b_out) {
+    b_in = __log2f(fmaxf(1.0f, gj) + eps);
+    b_out = __log2f(fmaxf(0.0f, gj) + eps);
+}
+
+// One 16-byte chunk of a row goes to the row-major tile.
+__device__ __forceinline__ void sa_put_rm(char *tile, int row, int dc, uint4 x) {
+    *reinterpret_cast<uint4 *>(tile + row * kSaRm + dc * 16) = x;
+}
+// The same four elements (8 bytes) of rows 2p and 2p+1 go to the transposed tile as four 32-bit
+// words (row 2p in the low half): element e of the chunk is d = dc * 8 + sel * 4 + e.
+__device__ __forceinline__ void sa_put_tr(char *tile, int pair, int dc, int sel, uint2 r0, uint2 r1) {
+    const uint32_t a0[2] = {r0.x, r0.y}, a1[2] = {r1.x, r1.y};
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        const uint32_t x0 = (e & 1) ? (a0[e >> 1] >> 16) : (a0[e >> 1] & 0xffffu);
+        const uint32_t x1 = (e & 1) ? (a1[e >> 1] & 0xffff0000u) : (a1[e >> 1] << 16);
+        *reinterpret_cast<uint32_t *>(tile + (dc * 8 + sel * 4 + e) * kSaTr + pair * 4) = x0 | x1;
+    }
+}
+// A operand of a product over d: row qn of a row-major tile, d slice ks.
+__device__ __forceinline__ sa_bf16x8_t sa_get_rm(const char *tile, int qn, int half, int ks) {
+    return *reinterpret_cast<const sa_bf16x8_t *>(tile + qn * kSaRm + (ks * 16 + half * 8) * 2);
+}
+// A operand of a product over the 32 positions of a tile: d row db*32+qn of a transposed tile;
+// the lane's 8 contraction slots are positions 16*t2 + 4*half + {0..3} and + 8 more, which is
+// where the accumulator layout of the first product leaves this lane's values.
+__device__ __forceinline__ sa_bf16x8_t sa_get_tr(const char *tile, int qn, int half, int db, int t2) {
+    const char *p = tile + (db * 32 + qn) * kSaTr + (16 * t2 + 4 * half) * 2;
+    const uint2 v0 = *reinterpret_cast<const uint2 *>(p);
+    const uint2 v1 = *reinterpret_cast<const uint2 *>(p + 16);
+    const uint4 u4 = make_uint4(v0.x, v0.y, v1.x, v1.y);
+    return __builtin_bit_cast(sa_bf16x8_t, u4);
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArgs a) {
+    __shared__ __attribute__((aligned(16))) char s_k[2][kSaT * kSaRm];
+    __shared__ __attribute__((aligned(16))) char s_vt[2][kSaD * kSaTr];
+    __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT];
+    __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT];
+
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;  // longest rows first
+    const int T = cs.ntok[b], base = cs.base[b];
+    if (qt * kSaQ >= T) return;  // block-uniform
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int head = wave & 3, rb = wave >> 2;
+    const int qn = lane & 31, half = lane >> 5;
+    const int q0 = qt * kSaQ;
+    const int i_end = min(T, q0 + kSaQ);
+    const int n_tiles = (i_end + kSaT - 1) / kSaT;
+
+    sa_bf16x8_t qv[8];
+    const int qi = min(q0 + rb * 32 + qn, T - 1);
+    {
+        const char *qp = a.q + ((size_t)(base + qi) * a.Hq + (size_t)h * kSaG + head) * kSaD * 2;
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) qv[ks] = *reinterpret_cast<const sa_bf16x8_t *>(qp + (ks * 16 + half * 8) * 2);
+    }
+    sa_f32x16_t o[4];
+    // l sums the weights as the second product sees them (rounded to bf16) and normalises the
+    // output; lx sums them unrounded and gives the log-sum-exp the backward pass starts from
+    float m = -INFINITY, l = 0.f, lx = 0.f;
+#pragma unroll
+    for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int c = 0; c < 16; c++) o[db][c] = 0.f;
+
+    const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
+    const int ld_key = 2 * ld_pair + ld_sel;
+    const int64_t v_delta = a.v - a.k;
+    uint4 kreg;
+    uint2 vreg0, vreg1;
+    float bin_reg, bout_reg;
+    auto fetch = [&](int t) __attribute__((always_inline)) {
+        const int idx0 = t * kSaT + 2 * ld_pair;
+        const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hkv + h;
+        const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hkv + h;
+        const char *kp0 = a.k + row0 * (kSaD * 2), *kp1 = a.k + row1 * (kSaD * 2);
+        kreg = *reinterpret_cast<const uint4 *>((ld_sel ? kp1 : kp0) + ld_dc * 16);
+        vreg0 = *reinterpret_cast<const uint2 *>(kp0 + v_delta + ld_dc * 16 + ld_sel * 8);
+        vreg1 = *reinterpret_cast<const uint2 *>(kp1 + v_delta + ld_dc * 16 + ld_sel * 8);
+        sa_bias(a.g[ld_sel ? row1 : row0], a.eps, bin_reg, bout_reg);
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+        sa_put_rm(s_k[buf], ld_key, ld_dc, kreg);
+        sa_put_tr(s_vt[buf], ld_pair, ld_dc, ld_sel, vreg0, vreg1);
+        if (ld_dc == 0) { s_bin[buf][ld_key] = bin_reg; s_bout[buf][ld_key] = bout_reg; }
+    };
+
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int t = 0; t < n_tiles; t++) {
+        const int buf = t & 1;
+        sa_bf16x8_t ka[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) ka[ks] = sa_get_rm(s_k[buf], qn, half, ks);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < n_tiles) fetch(t + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        sa_f32x16_t s;
+#pragma unroll
+        for (int c = 0; c < 16; c++) s[c] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qv[ks], s, 0, 0, 0);
+        sa_bf16x8_t va[2][4];
+#pragma unroll
+        for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+            for (int db = 0; db < 4; db++) va[t2][db] = sa_get_tr(s_vt[buf], qn, half, db, t2);
+        __builtin_amdgcn_sched_barrier(0);
+        // register c = 4j+i of a lane holds key 8j + 4*half + i of the tile
+        const bool far = t * kSaT + kSaT - 1 <= q0 - a.W;  // every key outside every window of the block
+        float sc[16];
+        float mt = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const float4 bo4 = *reinterpret_cast<const float4 *>(&s_bout[buf][8 * j + 4 * half]);
+            const float bo[4] = {bo4.x, bo4.y, bo4.z, bo4.w};
+            if (far) {
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    sc[4 * j + i] = fmaf(s[4 * j + i], a.scale_log2e, bo[i]);
+                    mt = fmaxf(mt, sc[4 * j + i]);
+                }
+            } else {
+                const float4 bi4 = *reinterpret_cast<const float4 *>(&s_bin[buf][8 * j + 4 * half]);
+                const float bi[4] = {bi4.x, bi4.y, bi4.z, bi4.w};
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const int jg = t * kSaT + 8 * j + 4 * half + i;
+                    const float bias = (qi - jg < a.W) ? bi[i] : bo[i];
+                    const float x = (jg <= qi) ? fmaf(s[4 * j + i], a.scale_log2e, bias) : -INFINITY;
+                    sc[4 * j + i] = x;
+                    mt = fmaxf(mt, x);
+                }
+            }
+        }
+        mt = fmaxf(mt, __shfl_xor(mt, 32));
+        const float mnew = fmaxf(m, mt);
+        const float msafe = mnew == -INFINITY ? 0.f : mnew;
+        const float corr = __builtin_amdgcn_exp2f(m - msafe);
+        uint32_t pb[8];
+        float ps = 0.f, px = 0.f;
+        const sa_bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+        for (int c = 0; c < 8; c++) {
+            const float p0 = __builtin_amdgcn_exp2f(sc[2 * c] - msafe), p1 = __builtin_amdgcn_exp2f(sc[2 * c + 1] - msafe);
+            px += p0 + p1;
+            pb[c] = sa_pack(p0, p1);
+            ps = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(sa_bf16x2_t, pb[c]), ones, ps, false);
+        }
+        l = l * corr + ps;
+        lx = lx * corr + px;
+        if (__builtin_amdgcn_ballot_w64(mnew > m) != 0) {
+#pragma unroll
+            for (int db = 0; db < 4; db++)
+#pragma unroll
+                for (int c = 0; c < 16; c++) o[db][c] *= corr;
+        }
+        m = mnew;
+#pragma unroll
+        for (int t2 = 0; t2 < 2; t2++) {
+            const uint4 p4 = make_uint4(pb[4 * t2], pb[4 * t2 + 1], pb[4 * t2 + 2], pb[4 * t2 + 3]);
+            const sa_bf16x8_t pbv = __builtin_bit_cast(sa_bf16x8_t, p4);
+#pragma unroll
+            for (int db = 0; db < 4; db++) o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t2][db], pbv, o[db], 0, 0, 0);
+        }
+        if (t + 1 < n_tiles) stage(buf ^ 1);
+        __syncthreads();
+    }
+    // register c = 4j+i of o[db] is d = 32*db + 8j + 4*half + i
+    const int i = q0 + rb * 32 + qn;
+    const float lt = l + __shfl_xor(l, 32), lxt = lx + __shfl_xor(lx, 32);
+    if (i < T) {
+        const float inv = 1.0f / lt;
+        const size_t orow = (size_t)(base + i) * a.Hq + (size_t)h * kSaG + head;
+        float *op = a.out + orow * kSaD;
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float4 w4 = make_float4(o[db][4 * j] * inv, o[db][4 * j + 1] * inv, o[db][4 * j + 2] * inv,
+                                              o[db][4 * j + 3] * inv);
+                *reinterpret_cast<float4 *>(op + 32 * db + 8 * j + 4 * half) = w4;
+            }
+        if (half == 0) a.lse[orow] = (m + __log2f(lxt)) * 0.6931471805599453f;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward, step 0: D_i = dO_i . O_i   (32 lanes per row)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void soft_attn_rowdot_kernel(int64_t n_rows, const char *dout, const float *out,
+                                                               float *rowdot) {
+    const int64_t r = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+    const int sub = threadIdx.x & 31;
+    float acc = 0.f;
+    if (r < n_rows) {
+        const uint2 d2 = *reinterpret_cast<const uint2 *>(dout + (size_t)r * kSaD * 2 + sub * 8);
+        const float4 o4 = *reinterpret_cast<const float4 *>(out + (size_t)r * kSaD + sub * 4);
+        acc = __uint_as_float(d2.x << 16) * o4.x + __uint_as_float(d2.x & 0xffff0000u) * o4.y +
+              __uint_as_float(d2.y << 16) * o4.z + __uint_as_float(d2.y & 0xffff0000u) * o4.w;
+    }
+    acc = group_sum<32>(acc);
+    if (r < n_rows && sub == 0) rowdot[r] = acc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward, dQ: columns of every tile are this wave's 32 queries
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, SoftArgs a) {
+    __shared__ __attribute__((aligned(16))) char s_k[2][kSaT * kSaRm];
+    __shared__ __attribute__((aligned(16))) char s_v[2][kSaT * kSaRm];
+    __shared__ __attribute__((aligned(16))) char s_kt[2][kSaD * kSaTr];
+    __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT];
+    __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT];
+
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;
+    const int T = cs.ntok[b], base = cs.base[b];
+    if (qt * kSaQ >= T) return;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int head = wave & 3, rb = wave >> 2;
+    const int qn = lane & 31, half = lane >> 5;
+    const int q0 = qt * kSaQ;
+    const int i_end = min(T, q0 + kSaQ);
+    const int n_tiles = (i_end + kSaT - 1) / kSaT;
+
+    const int qi = min(q0 + rb * 32 + qn, T - 1);
+    const size_t qrow = (size_t)(base + qi) * a.Hq + (size_t)h * kSaG + head;
+    sa_bf16x8_t qv[8], dov[8];
+    {
+        const char *qp = a.q + qrow * kSaD * 2, *dp = a.dout + qrow * kSaD * 2;
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) {
+            qv[ks] = *reinterpret_cast<const sa_bf16x8_t *>(qp + (ks * 16 + half * 8) * 2);
+            dov[ks] = *reinterpret_cast<const sa_bf16x8_t *>(dp + (ks * 16 + half * 8) * 2);
+        }
+    }
+    const float lse2 = a.lse[qrow] * 1.4426950408889634f;
+    const float Di = a.rowdot[qrow];
+    sa_f32x16_t dq[4];
+#pragma unroll
+    for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int c = 0; c < 16; c++) dq[db][c] = 0.f;
+
+    const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
+    const int ld_key = 2 * ld_pair + ld_sel;
+    const int64_t v_delta = a.v - a.k;
+    uint4 kreg, vreg;
+    uint2 kt0, kt1;
+    float bin_reg, bout_reg;
+    auto fetch = [&](int t) __attribute__((always_inline)) {
+        const int idx0 = t * kSaT + 2 * ld_pair;
+        const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hkv + h;
+        const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hkv + h;
+        const char *kp0 = a.k + row0 * (kSaD * 2), *kp1 = a.k + row1 * (kSaD * 2);
+        const char *ks = ld_sel ? kp1 : kp0;
+        kreg = *reinterpret_cast<const uint4 *>(ks + ld_dc * 16);
+        vreg = *reinterpret_cast<const uint4 *>(ks + v_delta + ld_dc * 16);
+        kt0 = *reinterpret_cast<const uint2 *>(kp0 + ld_dc * 16 + ld_sel * 8);
+        kt1 = *reinterpret_cast<const uint2 *>(kp1 + ld_dc * 16 + ld_sel * 8);
+        sa_bias(a.g[ld_sel ? row1 : row0], a.eps, bin_reg, bout_reg);
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+        sa_put_rm(s_k[buf], ld_key, ld_dc, kreg);
+        sa_put_rm(s_v[buf], ld_key, ld_dc, vreg);
+        sa_put_tr(s_kt[buf], ld_pair, ld_dc, ld_sel, kt0, kt1);
+        if (ld_dc == 0) { s_bin[buf][ld_key] = bin_reg; s_bout[buf][ld_key] = bout_reg; }
+    };
+
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int t = 0; t < n_tiles; t++) {
+        const int buf = t & 1;
+        sa_bf16x8_t ka[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) ka[ks] = sa_get_rm(s_k[buf], qn, half, ks);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 1 < n_tiles) fetch(t + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        sa_f32x16_t s, dp;
+#pragma unroll
+        for (int c = 0; c < 16; c++) { s[c] = 0.f; dp[c] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qv[ks], s, 0, 0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) ka[ks] = sa_get_rm(s_v[buf], qn, half, ks);
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], dov[ks], dp, 0, 0, 0);
+        // dS^T = P^T (dP^T - D_i), rounded to bf16 for the last product
+        uint32_t db_[8];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const float4 bo4 = *reinterpret_cast<const float4 *>(&s_bout[buf][8 * j + 4 * half]);
+            const float4 bi4 = *reinterpret_cast<const float4 *>(&s_bin[buf][8 * j + 4 * half]);
+            const float bo[4] = {bo4.x, bo4.y, bo4.z, bo4.w}, bi[4] = {bi4.x, bi4.y, bi4.z, bi4.w};
+            float ds[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int jg = t * kSaT + 8 * j + 4 * half + i;
+                const float bias = (qi - jg < a.W) ? bi[i] : bo[i];
+                const float x = (jg <= qi) ? fmaf(s[4 * j + i], a.scale_log2e, bias) - lse2 : -INFINITY;
+                ds[i] = __builtin_amdgcn_exp2f(x) * (dp[4 * j + i] - Di);
+            }
+            db_[2 * j] = sa_pack(ds[0], ds[1]);
+            db_[2 * j + 1] = sa_pack(ds[2], ds[3]);
+        }
+#pragma unroll
+        for (int t2 = 0; t2 < 2; t2++) {
+            const uint4 p4 = make_uint4(db_[4 * t2], db_[4 * t2 + 1], db_[4 * t2 + 2], db_[4 * t2 + 3]);
+            const sa_bf16x8_t dsv = __builtin_bit_cast(sa_bf16x8_t, p4);
+#pragma unroll
+            for (int db = 0; db < 4; db++)
+                dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_tr(s_kt[buf], qn, half, db, t2), dsv, dq[db], 0, 0, 0);
+        }
+        if (t + 1 < n_tiles) stage(buf ^ 1);
+        __syncthreads();
+    }
+    const int i = q0 + rb * 32 + qn;
+    if (i < T) {
+        float *op = a.dq + qrow * kSaD;
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float4 w4 = make_float4(dq[db][4 * j] * a.scale, dq[db][4 * j + 1] * a.scale,
+                                              dq[db][4 * j + 2] * a.scale, dq[db][4 * j + 3] * a.scale);
+                *reinterpret_cast<float4 *>(op + 32 * db + 8 * j + 4 * half) = w4;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward, dK / dV / dg: columns of every tile are this wave's 32 keys
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, SoftArgs a) {
+    __shared__ __attribute__((aligned(16))) char s_q[2][kSaT * kSaRm];
+    __shared__ __attribute__((aligned(16))) char s_do[2][kSaT * kSaRm];
+    __shared__ __attribute__((aligned(16))) char s_qt[2][kSaD * kSaTr];
+    __shared__ __attribute__((aligned(16))) char s_dot[2][kSaD * kSaTr];
+    __shared__ __attribute__((aligned(16))) float s_lse[2][kSaT];
+    __shared__ __attribute__((aligned(16))) float s_dd[2][kSaT];
+    __shared__ float s_p[4][16][64];  // P of one (32 keys x 32 queries) tile, lane-private slots
+
+    const int b = blockIdx.z, h = blockIdx.y, kbk = blockIdx.x;  // early key blocks have the most queries: first
+    const int T = cs.ntok[b], base = cs.base[b];
+    const int j0 = kbk * kSaKB;
+    if (j0 >= T) return;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kb = wave & 3, role = wave >> 2;
+    const int qn = lane & 31, half = lane >> 5;
+    const int jg = j0 + kb * 32 + qn;        // this lane's key
+    const int jc = min(jg, T - 1);
+    const size_t krow = (size_t)(base + jc) * a.Hkv + h;
+
+    // the block's own rows: K for role 0, V for role 1, as the N side of a product over d
+    sa_bf16x8_t own[8];
+    {
+        const char *p = (role == 0 ? a.k : a.v) + krow * kSaD * 2;
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) own[ks] = *reinterpret_cast<const sa_bf16x8_t *>(p + (ks * 16 + half * 8) * 2);
+    }
+    const float gj = a.g[krow];
+    float b_in, b_out;
+    sa_bias(gj, a.eps, b_in, b_out);
+    const bool follows_in = gj > 1.0f, follows_out = gj > 0.0f;  // where m_ij is g_j rather than the indicator
+    sa_f32x16_t acc[4];  // role 0: dV^T, role 1: dK^T ; rows d, columns keys
+#pragma unroll
+    for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int c = 0; c < 16; c++) acc[db][c] = 0.f;
+    float dg_acc = 0.f;
+
+    // streamed tiles: 32 queries of one query head; iteration it = (query tile, head)
+    const int qt_first = j0 / kSaT, n_qt = (T + kSaT - 1) / kSaT;
+    const int n_it = (n_qt - qt_first) * kSaG;
+    const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
+    const int ld_row = 2 * ld_pair + ld_sel;
+    uint4 qreg, doreg;
+    uint2 qt0, qt1, dt0, dt1;
+    float lse_reg, dd_reg;
+    auto fetch = [&](int it) __attribute__((always_inline)) {
+        const int qt = qt_first + it / kSaG, hd = it % kSaG;
+        const int idx0 = qt * kSaT + 2 * ld_pair;
+        const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hq + (size_t)h * kSaG + hd;
+        const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hq + (size_t)h * kSaG + hd;
+        const char *qp0 = a.q + row0 * (kSaD * 2), *qp1 = a.q + row1 * (kSaD * 2);
+        const char *dp0 = a.dout + row0 * (kSaD * 2), *dp1 = a.dout + row1 * (kSaD * 2);
+        qreg = *reinterpret_cast<const uint4 *>((ld_sel ? qp1 : qp0) + ld_dc * 16);
+        doreg = *reinterpret_cast<const uint4 *>((ld_sel ? dp1 : dp0) + ld_dc * 16);
+        qt0 = *reinterpret_cast<const uint2 *>(qp0 + ld_dc * 16 + ld_sel * 8);
+        qt1 = *reinterpret_cast<const uint2 *>(qp1 + ld_dc * 16 + ld_sel * 8);
+        dt0 = *reinterpret_cast<const uint2 *>(dp0 + ld_dc * 16 + ld_sel * 8);
+        dt1 = *reinterpret_cast<const uint2 *>(dp1 + ld_dc * 16 + ld_sel * 8);
+        const bool real = idx0 + ld_sel < T;  // a row past the end gets weight exp2(-inf) = 0
+        const size_t rs = ld_sel ? row1 : row0;
+        lse_reg = real ? a.lse[rs] * 1.4426950408889634f : INFINITY;
+        dd_reg = real ? a.rowdot[rs] : 0.f;
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+        sa_put_rm(s_q[buf], ld_row, ld_dc, qreg);
+        sa_put_rm(s_do[buf], ld_row, ld_dc, doreg);
+        sa_put_tr(s_qt[buf], ld_pair, ld_dc, ld_sel, qt0, qt1);
+        sa_put_tr(s_dot[buf], ld_pair, ld_dc, ld_sel, dt0, dt1);
+        if (ld_dc == 0) { s_lse[buf][ld_row] = lse_reg; s_dd[buf][ld_row] = dd_reg; }
+    };
+
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int it = 0; it < n_it; it++) {
+        const int buf = it & 1;
+        const int i0 = (qt_first + it / kSaG) * kSaT;  // first query of the tile
+        // first product: rows = queries of the tile, columns = this wave's keys
+        const char *rm = role == 0 ? s_q[buf] : s_do[buf];
+        sa_bf16x8_t fa[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) fa[ks] = sa_get_rm(rm, qn, half, ks);
+        __builtin_amdgcn_sched_barrier(0);
+        if (it + 1 < n_it) fetch(it + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        sa_f32x16_t x;
+#pragma unroll
+        for (int c = 0; c < 16; c++) x[c] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) x = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], own[ks], x, 0, 0, 0);
+        // register c = 4j+i of a lane holds query i0 + 8j + 4*half + i
+        if (role == 0) {
+            // P = exp2(S * scale + bias - lse); to the partner wave through LDS
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float4 l4 = *reinterpret_cast<const float4 *>(&s_lse[buf][8 * j + 4 * half]);
+                const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const int ig = i0 + 8 * j + 4 * half + i;
+                    const float bias = (ig - jg < a.W) ? b_in : b_out;
+                    const float e = (jg <= ig) ? fmaf(x[4 * j + i], a.scale_log2e, bias) - ls[i] : -INFINITY;
+                    x[4 * j + i] = __builtin_amdgcn_exp2f(e);
+                    s_p[kb][4 * j + i][lane] = x[4 * j + i];
+                }
+            }
+        }
+        __syncthreads();
+        uint32_t pk[8];
+        if (role == 0) {
+#pragma unroll
+            for (int c = 0; c < 8; c++) pk[c] = sa_pack(x[2 * c], x[2 * c + 1]);
+        } else {
+            // dS = P (dP - D_i); the part of it where m_ij follows g_j adds up to dg_j (g_j + eps)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float4 d4 = *reinterpret_cast<const float4 *>(&s_dd[buf][8 * j + 4 * half]);
+                const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
+                float ds[4];
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const int ig = i0 + 8 * j + 4 * half + i;
+                    ds[i] = s_p[kb][4 * j + i][lane] * (x[4 * j + i] - dd[i]);
+                    const bool follows = (ig - jg < a.W) ? follows_in : follows_out;
+                    dg_acc += follows ? ds[i] : 0.f;
+                }
+                pk[2 * j] = sa_pack(ds[0], ds[1]);
+                pk[2 * j + 1] = sa_pack(ds[2], ds[3]);
+            }
+        }
+        // second product: rows = d, columns = keys, contraction over the 32 queries
+        const char *tr = role == 0 ? s_dot[buf] : s_qt[buf];
+#pragma unroll
+        for (int t2 = 0; t2 < 2; t2++) {
+            const uint4 p4 = make_uint4(pk[4 * t2], pk[4 * t2 + 1], pk[4 * t2 + 2], pk[4 * t2 + 3]);
+            const sa_bf16x8_t pv = __builtin_bit_cast(sa_bf16x8_t, p4);
+#pragma unroll
+            for (int db = 0; db < 4; db++)
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_tr(tr, qn, half, db, t2), pv, acc[db], 0, 0, 0);
+        }
+        if (it + 1 < n_it) stage(buf ^ 1);
+        __syncthreads();
+    }
+    if (jg < T) {
+        float *op = (role == 0 ? a.dv : a.dk) + krow * kSaD;
+        const float f = role == 0 ? 1.0f : a.scale;
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float4 w4 = make_float4(acc[db][4 * j] * f, acc[db][4 * j + 1] * f, acc[db][4 * j + 2] * f,
+                                              acc[db][4 * j + 3] * f);
+                *reinterpret_cast<float4 *>(op + 32 * db + 8 * j + 4 * half) = w4;
+            }
+    }
+    if (role == 1) {
+        const float tot = dg_acc + __shfl_xor(dg_acc, 32);
+        if (half == 0 && jg < T) a.dg[krow] = follows_out ? tot / (gj + a.eps) : 0.f;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+static bool soft_fill(SoftSeqs &cs, int n_seqs, const int32_t *n_tokens, int *max_t, int64_t *total) {
+    if (n_seqs < 0 || n_seqs > kMaxCallSeqs) return false;
+    cs.n = n_seqs;
+    int64_t tot = 0;
+    int mx = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        if (n_tokens[b] < 0) return false;
+        cs.ntok[b] = n_tokens[b];
+        cs.base[b] = (int32_t)tot;
+        tot += n_tokens[b];
+        if (tot >= ((int64_t)1 << 24)) return false;  // keeps every packed row index far inside 32 bits
+        mx = max(mx, n_tokens[b]);
+    }
+    *max_t = mx;
+    *total = tot;
+    return true;
+}
+
+size_t soft_attn_ws_bytes(int64_t total_tokens, int n_q_heads) {
+    return (size_t)((total_tokens * n_q_heads * 4 + 255) / 256) * 256;
+}
+
+hipError_t launch_soft_attn_fwd(int n_seqs, const int32_t *n_tokens, int Hq, int Hkv, int d, int W,
+                                const void *q, const void *k, const void *v, const float *g, float scale,
+                                float eps, float *out, float *lse, hipStream_t st) {
+    if (d != kSaD || Hq != Hkv * kSaG) return hipErrorNotSupported;
+    SoftSeqs cs;
+    int max_t;
+    int64_t total;
+    if (!soft_fill(cs, n_seqs, n_tokens, &max_t, &total)) return hipErrorInvalidValue;
+    if (max_t == 0) return hipSuccess;
+    SoftArgs a = {};
+    a.Hq = Hq; a.Hkv = Hkv; a.W = W;
+    a.scale = scale; a.scale_log2e = scale * 1.4426950408889634f; a.eps = eps;
+    a.q = (const char *)q; a.k = (const char *)k; a.v = (const char *)v; a.g = g;
+    a.out = out; a.lse = lse;
+    dim3 grid((max_t + kSaQ - 1) / kSaQ, Hkv, n_seqs);
+    hipLaunchKernelGGL(soft_attn_fwd_kernel, grid, dim3(512), 0, st, cs, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_soft_attn_bwd(int n_seqs, const int32_t *n_tokens, int Hq, int Hkv, int d, int W,
+                                const void *q, const void *k, const void *v, const float *g, float scale,
+                                float eps, const float *out, const float *lse, const void *dout, float *dq,
+                                float *dk, float *dv, float *dg, void *ws, hipStream_t st) {
+    if (d != kSaD || Hq != Hkv * kSaG) return hipErrorNotSupported;
+    SoftSeqs cs;
+    int max_t;
+    int64_t total;
+    if (!soft_fill(cs, n_seqs, n_tokens, &max_t, &total)) return hipErrorInvalidValue;
+    if (max_t == 0) return hipSuccess;
+    SoftArgs a = {};
+    a.Hq = Hq; a.Hkv = Hkv; a.W = W;
+    a.scale = scale; a.scale_log2e = scale * 1.4426950408889634f; a.eps = eps;
+    a.q = (const char *)q; a.k = (const char *)k; a.v = (const char *)v; a.g = g;
+    a.out = const_cast<float *>(out); a.lse = const_cast<float *>(lse);
+    a.dout = (const char *)dout;
+    a.rowdot = (float *)ws;
+    a.dq = dq; a.dk = dk; a.dv = dv; a.dg = dg;
+    const int64_t n_rows = total * Hq;
+    hipLaunchKernelGGL(soft_attn_rowdot_kernel, dim3((unsigned)((n_rows + 7) / 8)), dim3(256), 0, st, n_rows,
+                       a.dout, out, a.rowdot);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(soft_attn_bwd_dq_kernel, dim3((max_t + kSaQ - 1) / kSaQ, Hkv, n_seqs), dim3(512), 0, st, cs, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(soft_attn_bwd_dkv_kernel, dim3((max_t + kSaKB - 1) / kSaKB, Hkv, n_seqs), dim3(512), 0, st, cs, a);
+    return hipGetLastError();
+}
+
+}  // namespace wgkv

@@ -44,6 +44,14 @@ hipError_t launch_gate_mlp(int dtype, int64_t n_tokens, int n_kv_heads, int head
                            const void *w2, const float *b2, float eps, float *g_out, hipStream_t st);
 hipError_t launch_gate_linear(int dtype, int64_t n_tokens, int hidden_dim, int n_kv_heads,
                               const void *hidden, const void *w, float *g_out, hipStream_t st);
+size_t soft_attn_ws_bytes(int64_t total_tokens, int n_q_heads);
+hipError_t launch_soft_attn_fwd(int n_seqs, const int32_t *n_tokens, int Hq, int Hkv, int d, int W,
+                                const void *q, const void *k, const void *v, const float *g, float scale,
+                                float eps, float *out, float *lse, hipStream_t st);
+hipError_t launch_soft_attn_bwd(int n_seqs, const int32_t *n_tokens, int Hq, int Hkv, int d, int W,
+                                const void *q, const void *k, const void *v, const float *g, float scale,
+                                float eps, const float *out, const float *lse, const void *dout, float *dq,
+                                float *dk, float *dv, float *dg, void *ws, hipStream_t st);
 size_t attend_prefill_ws_bytes(const View &pv, int n_seqs, int64_t total_q);
 hipError_t launch_attend_prefill(const View &pv, const CallSeqs &cs, int layer, const void *q,
                                  const void *k, const void *v, const float *g, float tau,
@@ -276,6 +284,72 @@ int wgkv_gate_mlp_scores(int32_t dtype, int64_t n_tokens, int32_t n_kv_heads, in
     if ((((uintptr_t)k_dev | (uintptr_t)k_rope_dev | (uintptr_t)w1_dev) & 15) != 0) return WGKV_ERR_INVALID_ARG;
     return launch_gate_mlp(dtype, n_tokens, n_kv_heads, head_dim, width, k_dev, k_rope_dev, w1_dev,
                            b1_dev, w2_dev, b2_dev, eps, g_out_dev, (hipStream_t)stream) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
+}
+
+// Shape and argument checks shared by the two soft-attention entry points; *total gets the rows.
+static int soft_attn_check(int32_t dtype, int32_t n_seqs, const int32_t *n_tokens_host, int32_t n_q_heads,
+                           int32_t n_kv_heads, int32_t head_dim, int32_t w_local, float scale, float eps,
+                           int64_t *total) {
+    if (dtype != WGKV_BF16 || head_dim != 128 || n_kv_heads < 1 || n_kv_heads > 65535 ||
+        n_q_heads != 4 * n_kv_heads || w_local < 1 || n_seqs < 0 || n_seqs > WGKV_MAX_CALL_SEQS ||
+        (n_seqs > 0 && !n_tokens_host) || !std::isfinite(scale) || !(eps >= 0.f) || !std::isfinite(eps))
+        return WGKV_ERR_INVALID_ARG;
+    int64_t t = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        if (n_tokens_host[b] < 0) return WGKV_ERR_INVALID_ARG;
+        t += n_tokens_host[b];
+        if (t >= ((int64_t)1 << 24)) return WGKV_ERR_INVALID_ARG;
+    }
+    *total = t;
+    return WGKV_OK;
+}
+
+int wgkv_soft_attn_forward(int32_t dtype, int32_t n_seqs, const int32_t *n_tokens_host,
+                           int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                           int32_t w_local, const void *q_dev, const void *k_dev,
+                           const void *v_dev, const float *g_dev, float scale, float eps,
+                           float *out_dev, float *lse_dev, wgkv_stream stream) {
+    int64_t total = 0;
+    int rc = soft_attn_check(dtype, n_seqs, n_tokens_host, n_q_heads, n_kv_heads, head_dim, w_local, scale, eps, &total);
+    if (rc) return rc;
+    if (total == 0) return WGKV_OK;
+    if (!q_dev || !k_dev || !v_dev || !g_dev || !out_dev || !lse_dev) return WGKV_ERR_INVALID_ARG;
+    if ((((uintptr_t)q_dev | (uintptr_t)k_dev | (uintptr_t)v_dev | (uintptr_t)out_dev) & 15) != 0)
+        return WGKV_ERR_INVALID_ARG;
+    return launch_soft_attn_fwd(n_seqs, n_tokens_host, n_q_heads, n_kv_heads, head_dim, w_local, q_dev, k_dev,
+                                v_dev, g_dev, scale, eps, out_dev, lse_dev, (hipStream_t)stream) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
+}
+
+size_t wgkv_soft_attn_workspace_bytes(int64_t total_tokens, int32_t n_q_heads) {
+    if (total_tokens < 0 || n_q_heads < 1) return 0;
+    return soft_attn_ws_bytes(total_tokens, n_q_heads);
+}
+
+int wgkv_soft_attn_backward(int32_t dtype, int32_t n_seqs, const int32_t *n_tokens_host,
+                            int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                            int32_t w_local, const void *q_dev, const void *k_dev,
+                            const void *v_dev, const float *g_dev, float scale, float eps,
+                            const float *out_dev, const float *lse_dev, const void *dout_dev,
+                            float *dq_dev, float *dk_dev, float *dv_dev, float *dg_dev,
+                            void *workspace_dev, size_t workspace_bytes, wgkv_stream stream) {
+    int64_t total = 0;
+    int rc = soft_attn_check(dtype, n_seqs, n_tokens_host, n_q_heads, n_kv_heads, head_dim, w_local, scale, eps, &total);
+    if (rc) return rc;
+    if (total == 0) return WGKV_OK;
+    if (!q_dev || !k_dev || !v_dev || !g_dev || !out_dev || !lse_dev || !dout_dev || !dq_dev || !dk_dev ||
+        !dv_dev || !dg_dev || !workspace_dev)
+        return WGKV_ERR_INVALID_ARG;
+    if ((((uintptr_t)q_dev | (uintptr_t)k_dev | (uintptr_t)v_dev | (uintptr_t)out_dev | (uintptr_t)dout_dev |
+          (uintptr_t)dq_dev | (uintptr_t)dk_dev | (uintptr_t)dv_dev | (uintptr_t)workspace_dev) & 15) != 0)
+        return WGKV_ERR_INVALID_ARG;
+    if (workspace_bytes < soft_attn_ws_bytes(total, n_q_heads)) return WGKV_ERR_WORKSPACE;
+    return launch_soft_attn_bwd(n_seqs, n_tokens_host, n_q_heads, n_kv_heads, head_dim, w_local, q_dev, k_dev,
+                                v_dev, g_dev, scale, eps, out_dev, lse_dev, dout_dev, dq_dev, dk_dev, dv_dev,
+                                dg_dev, workspace_dev, (hipStream_t)stream) == hipSuccess
                ? WGKV_OK
                : WGKV_ERR_HIP;
 }

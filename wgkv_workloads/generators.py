@@ -15,7 +15,7 @@ from .configs import WorkloadConfig
 
 _PURPOSE = {"rates": 1, "scores": 2, "k": 3, "v": 4, "q": 5, "ctx": 6, "gate_w": 7, "hidden": 8,
             "dec_scores": 9, "dec_k": 10, "dec_v": 11, "k_pre": 12, "k_rope": 13, "mlp_w1": 14, "mlp_b1": 15,
-            "mlp_w2": 16, "mlp_b2": 17}
+            "mlp_w2": 16, "mlp_b2": 17, "dout": 18}
 
 
 def _rng(cfg: WorkloadConfig, purpose: str, *key) -> np.random.Generator:
