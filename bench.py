@@ -101,6 +101,10 @@ def main():
     ap.add_argument("--evict", action="store_true",
                     help="time the budgeted eviction (scoring from a 256-query observation window + removal of the "
                          "lowest 10 %) on one layer of the workload's batch with about 4.5K global entries per head")
+    ap.add_argument("--soft-attn", type=int, default=0, metavar="TOKENS",
+                    help="time the training-time Write-Gated Attention (forward + backward) of one layer on one "
+                         "sequence of TOKENS tokens with the workload's head shape (the paper trains on samples of "
+                         "4K to 32K tokens, batch size 1)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM counters)")
     args = ap.parse_args()
@@ -120,6 +124,8 @@ def main():
     cfg = wl.get_config(args.workload)
     if args.evict:
         return main_evict(args, cfg, torch, wg, wl, dev)
+    if args.soft_attn:
+        return main_soft_attn(args, cfg, torch, wg, wl, dev)
     if cfg.chunk:
         return main_prefill(args, cfg, torch, wg, wl, dev)
     B, L, Hq, Hk, d, W, P = cfg.batch, cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local, cfg.page_size
@@ -354,6 +360,67 @@ def main_evict(args, cfg, torch, wg, wl, dev):
                      "frac": tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "kernel": "evict_stats_mfma_kernel + evict_weights_mfma_kernel"},
         "cpu_baseline": None,
+    }
+    print(json.dumps(res), flush=True)
+
+
+def main_soft_attn(args, cfg, torch, wg, wl, dev):
+    """One layer of training-time Write-Gated Attention: forward, then backward, on one sequence."""
+    T, Hq, Hk, d, W = args.soft_attn, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.w_local
+    eps, scale = 1e-6, 1.0 / math.sqrt(d)
+    rates = wl.unit_rates(cfg)
+    q = wl.draw_normal(cfg, "q", (T, Hq, d), device=dev)
+    k = wl.draw_normal(cfg, "k", (T, Hk, d), device=dev)
+    v = wl.draw_normal(cfg, "v", (T, Hk, d), device=dev)
+    dout = wl.draw_normal(cfg, "dout", (T, Hq, d), device=dev)
+    g = wl.draw_scores(cfg, 0, 0, T, rates, device=dev)
+    steps, warmup = min(args.steps, 16), min(args.warmup, 2)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    for i in range(warmup + steps):
+        if i >= warmup:
+            ev[i - warmup][0].record()
+        out, lse = wg.soft_attn_forward(q, k, v, g, [T], W, scale, eps)
+        if i >= warmup:
+            ev[i - warmup][1].record()
+        grads = wg.soft_attn_backward(q, k, v, g, out, lse, dout, [T], W, scale, eps)
+        if i >= warmup:
+            ev[i - warmup][2].record()
+    torch.cuda.synchronize()
+    fwd = np.array([e[0].elapsed_time(e[1]) for e in ev])
+    bwd = np.array([e[1].elapsed_time(e[2]) for e in ev])
+    pairs = T * (T + 1) / 2.0 * Hq
+    # the method's products per (query, key, query head): two forward, five backward, 2 d flop each;
+    # the backward kernels here recompute the scores in both of them: seven products are executed
+    f_fwd, f_bwd = 4.0 * d * pairs, 10.0 * d * pairs
+    tf = (f_fwd + f_bwd) / ((fwd.mean() + bwd.mean()) * 1e-3) / 1e12
+    log(f"[bench] soft attention T={T}: forward {fwd.mean():.2f} ms ({f_fwd / fwd.mean() / 1e9:.0f} TFLOP/s), "
+        f"backward {bwd.mean():.2f} ms ({f_bwd / bwd.mean() / 1e9:.0f} TFLOP/s algorithmic)")
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import soft_attn_backward as o_bwd, soft_attn_forward as o_fwd
+        Ts = min(T, 2048)
+        f = lambda x: x[:Ts].float().cpu().numpy()
+        t0 = time.perf_counter()
+        o_fwd(f(q), f(k), f(v), f(g), W, scale, eps)
+        o_bwd(f(q), f(k), f(v), f(g), f(dout), W, scale, eps)
+        dt = time.perf_counter() - t0
+        sample_pairs = Ts * (Ts + 1) / 2.0 * Hq
+        cpu = {"value": dt * 1e3 * pairs / sample_pairs, "unit": "ms/step", "cores": min(os.cpu_count() or 1, 16),
+               "kind": "oracle", "sample": f"forward + backward of the first {Ts} tokens, all heads, {dt:.1f} s; "
+               f"scaled by the number of (query, key) pairs to {T} tokens (extrapolated)", "sample_seconds": dt}
+    res = {
+        "metric": "soft_attn_train_step_ms (one layer: Write-Gated Attention forward + backward, one sequence)",
+        "value": float(fwd.mean() + bwd.mean()), "unit": "ms/step", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": float(fwd.mean() + bwd.mean()), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} head shape, one sequence of {T} tokens", "q_heads": Hq, "kv_heads": Hk,
+                   "head_dim": d, "w_local": W, "eps": eps, "tokens": T, "forward_ms": float(fwd.mean()),
+                   "backward_ms": float(bwd.mean())},
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "soft_attn_fwd_kernel + soft_attn_bwd_*",
+                     "algorithmic_flops": f_fwd + f_bwd, "forward_tflops": f_fwd / fwd.mean() / 1e9,
+                     "backward_tflops": f_bwd / bwd.mean() / 1e9},
+        "cpu_baseline": cpu,
     }
     print(json.dumps(res), flush=True)
 

@@ -993,6 +993,129 @@ int orc_soft_attn_backward(int64_t T, int Hq, int Hkv, int d, int W, double scal
 }
 
 /*
+ * The same gradients for a sample of the outputs, for sequences too long for the full
+ * function: dQ of the query rows listed in `rows` (all query heads), and dK, dV, dg of the
+ * keys j >= j_first of kv head h (a tail of the sequence: only the queries i >= j see them,
+ * and each such query still needs its whole row of weights for lse_i and dO_i . o_i).
+ *   dQ_rows: [n_rows][Hq][d]   dK_tail, dV_tail: [T - j_first][d]   dg_tail: [T - j_first]
+ */
+int orc_soft_attn_backward_sampled(int64_t T, int Hq, int Hkv, int d, int W, double scale, double eps,
+                                   const float *Q, const float *K, const float *V, const float *g,
+                                   const float *dO, int64_t n_rows, const int64_t *rows, double *dQ_rows,
+                                   int h, int64_t j_first, double *dK_tail, double *dV_tail, double *dg_tail) {
+    if (T < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv || d < 1 || W < 1 || h < 0 || h >= Hkv || j_first < 0 || j_first > T)
+        return ORC_ERR_ARG;
+    const int G = Hq / Hkv;
+    int rc_all = ORC_OK;
+    /* ---- dQ of the sampled rows ---- */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < n_rows; r++) {
+        const int64_t i = rows[r];
+        if (i < 0 || i >= T) { rc_all = ORC_ERR_ARG; continue; }
+        double *p = (double *)malloc(sizeof(double) * (size_t)(i + 1));
+        double *o = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!p || !o) { free(p); free(o); rc_all = ORC_ERR_NOMEM; continue; }
+        for (int qh = 0; qh < Hq; qh++) {
+            const int hh = qh / G;
+            const float *qi = Q + ((size_t)i * Hq + qh) * d, *doi = dO + ((size_t)i * Hq + qh) * d;
+            double mx = -INFINITY;
+            for (int64_t j = 0; j <= i; j++) {
+                const size_t row = (size_t)j * Hkv + hh;
+                double dot = 0.0;
+                for (int e = 0; e < d; e++) dot += (double)qi[e] * (double)K[row * d + e];
+                double m = (i - j < W) ? 1.0 : 0.0;
+                if ((double)g[row] > m) m = (double)g[row];
+                p[j] = scale * dot + log(m + eps);
+                if (p[j] > mx) mx = p[j];
+            }
+            double den = 0.0;
+            for (int64_t j = 0; j <= i; j++) { p[j] = exp(p[j] - mx); den += p[j]; }
+            for (int e = 0; e < d; e++) o[e] = 0.0;
+            for (int64_t j = 0; j <= i; j++) {
+                p[j] /= den;
+                const float *vj = V + ((size_t)j * Hkv + hh) * d;
+                for (int e = 0; e < d; e++) o[e] += p[j] * (double)vj[e];
+            }
+            double Di = 0.0;
+            for (int e = 0; e < d; e++) Di += (double)doi[e] * o[e];
+            double *dq = dQ_rows + ((size_t)r * Hq + qh) * d;
+            for (int e = 0; e < d; e++) dq[e] = 0.0;
+            for (int64_t j = 0; j <= i; j++) {
+                const size_t row = (size_t)j * Hkv + hh;
+                double dP = 0.0;
+                for (int e = 0; e < d; e++) dP += (double)doi[e] * (double)V[row * d + e];
+                const double dS = p[j] * (dP - Di);
+                for (int e = 0; e < d; e++) dq[e] += scale * dS * (double)K[row * d + e];
+            }
+        }
+        free(p); free(o);
+    }
+    /* ---- dK, dV, dg of the tail keys of kv head h ---- */
+    const int64_t n = T - j_first;
+    for (size_t x = 0; x < (size_t)n * d; x++) { dK_tail[x] = 0.0; dV_tail[x] = 0.0; }
+    for (int64_t x = 0; x < n; x++) dg_tail[x] = 0.0;
+    if (n == 0) return rc_all;
+    double *PS = (double *)malloc(sizeof(double) * (size_t)n * (size_t)n);
+    double *DS = (double *)malloc(sizeof(double) * (size_t)n * (size_t)n);
+    if (!PS || !DS) { free(PS); free(DS); return ORC_ERR_NOMEM; }
+    for (int jq = 0; jq < G; jq++) {
+        const int qh = h * G + jq;
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t i = j_first; i < T; i++) {
+            double *p = (double *)malloc(sizeof(double) * (size_t)(i + 1));
+            double *o = (double *)malloc(sizeof(double) * (size_t)d);
+            if (!p || !o) { free(p); free(o); rc_all = ORC_ERR_NOMEM; continue; }
+            const float *qi = Q + ((size_t)i * Hq + qh) * d, *doi = dO + ((size_t)i * Hq + qh) * d;
+            double mx = -INFINITY;
+            for (int64_t j = 0; j <= i; j++) {
+                const size_t row = (size_t)j * Hkv + h;
+                double dot = 0.0;
+                for (int e = 0; e < d; e++) dot += (double)qi[e] * (double)K[row * d + e];
+                double m = (i - j < W) ? 1.0 : 0.0;
+                if ((double)g[row] > m) m = (double)g[row];
+                p[j] = scale * dot + log(m + eps);
+                if (p[j] > mx) mx = p[j];
+            }
+            double den = 0.0;
+            for (int64_t j = 0; j <= i; j++) { p[j] = exp(p[j] - mx); den += p[j]; }
+            for (int e = 0; e < d; e++) o[e] = 0.0;
+            for (int64_t j = 0; j <= i; j++) {
+                p[j] /= den;
+                const float *vj = V + ((size_t)j * Hkv + h) * d;
+                for (int e = 0; e < d; e++) o[e] += p[j] * (double)vj[e];
+            }
+            double Di = 0.0;
+            for (int e = 0; e < d; e++) Di += (double)doi[e] * o[e];
+            for (int64_t j = j_first; j <= i; j++) {
+                const float *vj = V + ((size_t)j * Hkv + h) * d;
+                double dP = 0.0;
+                for (int e = 0; e < d; e++) dP += (double)doi[e] * (double)vj[e];
+                PS[(size_t)(i - j_first) * n + (j - j_first)] = p[j];
+                DS[(size_t)(i - j_first) * n + (j - j_first)] = p[j] * (dP - Di);
+            }
+            free(p); free(o);
+        }
+        for (int64_t i = j_first; i < T; i++) {
+            const float *qi = Q + ((size_t)i * Hq + qh) * d, *doi = dO + ((size_t)i * Hq + qh) * d;
+            for (int64_t j = j_first; j <= i; j++) {
+                const size_t row = (size_t)j * Hkv + h;
+                const double pij = PS[(size_t)(i - j_first) * n + (j - j_first)];
+                const double dS = DS[(size_t)(i - j_first) * n + (j - j_first)];
+                double *dk = dK_tail + (size_t)(j - j_first) * d, *dv = dV_tail + (size_t)(j - j_first) * d;
+                for (int e = 0; e < d; e++) {
+                    dv[e] += pij * (double)doi[e];
+                    dk[e] += scale * dS * (double)qi[e];
+                }
+                const double ind = (i - j < W) ? 1.0 : 0.0;
+                if ((double)g[row] > ind) dg_tail[j - j_first] += dS / ((double)g[row] + eps);
+            }
+        }
+    }
+    free(PS); free(DS);
+    return rc_all;
+}
+
+/*
  * Sparsity term of the training objective (Sec. 3.3): the mean over all n scores of
  * g + g (1 - g), and its derivative (2 - 2 g) / n with respect to every score.
  */

@@ -92,6 +92,9 @@ def lib():
         L.orc_soft_attn_backward.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double,
                                              fp, fp, fp, fp, fp, dp, dp, dp, dp]
         L.orc_sparsity_loss.argtypes = [C.c_int64, fp, dp, dp]
+        L.orc_soft_attn_backward_sampled.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_double,
+                                                     fp, fp, fp, fp, fp, C.c_int64, C.POINTER(C.c_int64), dp,
+                                                     C.c_int, C.c_int64, dp, dp, dp]
         L.orc_linear_gate.argtypes = [C.c_int64, C.c_int, C.c_int, C.POINTER(C.c_float),
                                       C.POINTER(C.c_float), C.POINTER(C.c_double),
                                       C.POINTER(C.c_double)]
@@ -349,6 +352,27 @@ def soft_attn_backward(Q, K, V, g, dO, w_local, scale, eps):
                                       _p(K, C.c_float), _p(V, C.c_float), _p(g, C.c_float), _p(dO, C.c_float),
                                       _p(dQ, C.c_double), _p(dK, C.c_double), _p(dV, C.c_double),
                                       _p(dg, C.c_double))
+    if rc:
+        raise OracleError(rc)
+    return dQ, dK, dV, dg
+
+
+def soft_attn_backward_sampled(Q, K, V, g, dO, w_local, scale, eps, rows, h, j_first):
+    """The gradients of soft_attn_backward for a sample: dQ [len(rows), Hq, d] of the listed query rows, and
+    (dK, dV [T - j_first, d], dg [T - j_first]) of the keys j >= j_first of kv head h."""
+    Q = _f32(Q); K = _f32(K); V = _f32(V); g = _f32(g); dO = _f32(dO)
+    T, Hq, d = Q.shape
+    Hk = K.shape[1]
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    n = T - int(j_first)
+    dQ = np.zeros((len(rows), Hq, d), dtype=np.float64)
+    dK = np.zeros((n, d), dtype=np.float64)
+    dV = np.zeros((n, d), dtype=np.float64)
+    dg = np.zeros((n,), dtype=np.float64)
+    rc = lib().orc_soft_attn_backward_sampled(T, Hq, Hk, d, int(w_local), float(scale), float(eps), _p(Q, C.c_float),
+                                              _p(K, C.c_float), _p(V, C.c_float), _p(g, C.c_float), _p(dO, C.c_float),
+                                              len(rows), _p(rows, C.c_int64), _p(dQ, C.c_double), int(h), int(j_first),
+                                              _p(dK, C.c_double), _p(dV, C.c_double), _p(dg, C.c_double))
     if rc:
         raise OracleError(rc)
     return dQ, dK, dV, dg

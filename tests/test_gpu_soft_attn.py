@@ -10,7 +10,7 @@ import torch
 
 import paper_2512_17452_amd as wg
 import wgkv_workloads as wl
-from oracle import soft_attn_backward, soft_attn_forward
+from oracle import attend_soft, soft_attn_backward, soft_attn_backward_sampled, soft_attn_forward
 
 pytestmark = pytest.mark.gpu
 
@@ -113,6 +113,50 @@ def test_forward_and_backward_match_fp64(seed, n_tokens, Hk, W, eps, kind):
         tail = slice(r0 + max(T - W, 0), r0 + T)
         assert torch.all(dg[tail] == 0)
         r0 += T
+
+
+def test_full_training_length_on_sampled_outputs():
+    """The longest training sample (32K tokens, Llama-3.1-8B head shape, window 256), the launch
+    the benchmark times: sampled query rows of out and dq, the last 400 keys of one kv head for
+    dk, dv, dg (they include keys outside the window of later queries), and two identities that
+    hold at any size."""
+    dev = torch.device("cuda:0")
+    T, Hk, W, eps = 32768, 8, 256, 1e-6
+    Hq, scale = 4 * Hk, 1 / math.sqrt(128)
+    cfg = wl.get_config("llama8b_32layer_b8_128k")
+    q = wl.draw_normal(cfg, "q", (T, Hq, 128), device=dev)
+    k = wl.draw_normal(cfg, "k", (T, Hk, 128), device=dev)
+    v = wl.draw_normal(cfg, "v", (T, Hk, 128), device=dev)
+    dout = wl.draw_normal(cfg, "dout", (T, Hq, 128), device=dev)
+    g = wl.draw_scores(cfg, 0, 0, T, wl.unit_rates(cfg), device=dev)
+    out, lse = wg.soft_attn_forward(q, k, v, g, [T], W, scale, eps)
+    dq, dk, dv, dg = wg.soft_attn_backward(q, k, v, g, out, lse, dout, [T], W, scale, eps)
+    torch.cuda.synchronize()
+    f = lambda x: x.float().cpu().numpy()
+    qn, kn, vn, gn, dn = f(q), f(k), f(v), f(g), f(dout)
+    rows = [0, 255, 256, 4097, 20000, T - 1]
+    print("oracle: sampled rows", flush=True)
+    ref_out = attend_soft(kn, vn, gn, qn[rows], rows, W, scale, use_log=True, eps=eps)
+    _check("out rows", out[rows], ref_out, FWD_MAX, FWD_MEAN, False)
+    h, j_first = 3, T - 400
+    rq, rk, rv, rg = soft_attn_backward_sampled(qn, kn, vn, gn, dn, W, scale, eps, rows, h, j_first)
+    print("oracle: done", flush=True)
+    _check("dq rows", dq[rows], rq, BWD_MAX, BWD_MEAN, True)
+    _check("dk tail", dk[j_first:, h], rk, BWD_MAX, BWD_MEAN, True)
+    _check("dv tail", dv[j_first:, h], rv, BWD_MAX, BWD_MEAN, True)
+    assert np.abs(rg[: 400 - W]).max() > 0 and np.all(rg[400 - W:] == 0)
+    _check("dg tail", dg[j_first:, h], rg, BWD_MAX, BWD_MEAN, True)
+    # rows of weights sum to one: the dv of a kv head add up to the dout of its query heads
+    lhs = dv.double().sum(0)
+    rhs = dout.double().view(T, Hk, 4, 128).sum((0, 2))
+    assert (lhs - rhs).abs().max().item() <= 2e-3 * rhs.abs().max().item()
+    # the output sees q and k through q . k only
+    for hh in range(Hk):
+        a = (q[:, 4 * hh:4 * hh + 4].double() * dq[:, 4 * hh:4 * hh + 4].double()).sum().item()
+        b = (k[:, hh].double() * dk[:, hh].double()).sum().item()
+        unit = (q[:, 4 * hh:4 * hh + 4].double() * dq[:, 4 * hh:4 * hh + 4].double()).abs().sum().item()
+        assert abs(a - b) <= 1e-3 * unit, (hh, a, b, unit)
+    assert all(bool(torch.isfinite(x).all()) for x in (out, lse, dq, dk, dv, dg))
 
 
 def test_backward_is_the_same_on_every_run():

@@ -10,7 +10,8 @@ import pytest
 import torch
 import torch.nn.functional as F
 
-from oracle import attend_definition, soft_attn_backward, soft_attn_forward, sparsity_loss
+from oracle import (attend_definition, attend_soft, soft_attn_backward, soft_attn_backward_sampled, soft_attn_forward,
+                    sparsity_loss)
 
 
 def _inputs(seed, T, Hq, Hk, d, g_kind="uniform"):
@@ -159,6 +160,25 @@ def test_backward_identities():
     # a loss that ignores the output has zero gradients
     z = soft_attn_backward(Q, K, V, g, np.zeros_like(dO), W, scale, eps)
     assert all(np.all(x == 0) for x in z)
+
+
+def test_sampled_gradients_are_the_full_ones():
+    """The sampled form used at sizes the full function cannot reach gives the same numbers, and so
+    does the per-row forward used there (the library-pinned functions are the reference)."""
+    T, Hq, Hk, d, W, eps = 90, 8, 2, 16, 11, 1e-4
+    Q, K, V, g, dO = _inputs(9, T, Hq, Hk, d)
+    scale = 1 / math.sqrt(d)
+    dQ, dK, dV, dg = soft_attn_backward(Q, K, V, g, dO, W, scale, eps)
+    rows = [0, 10, 11, 57, 89]
+    for h, j_first in ((0, 60), (1, 0), (1, 89), (0, 90)):
+        sQ, sK, sV, sg = soft_attn_backward_sampled(Q, K, V, g, dO, W, scale, eps, rows, h, j_first)
+        np.testing.assert_allclose(sQ, dQ[rows], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(sK, dK[j_first:, h], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(sV, dV[j_first:, h], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(sg, dg[j_first:, h], rtol=1e-12, atol=1e-14)
+    out, _ = soft_attn_forward(Q, K, V, g, W, scale, eps)
+    np.testing.assert_allclose(attend_soft(K, V, g, Q[rows], rows, W, scale, use_log=True, eps=eps), out[rows],
+                               rtol=1e-12, atol=1e-14)
 
 
 def test_sparsity_loss_matches_library_differentiation():
