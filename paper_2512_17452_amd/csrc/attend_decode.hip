@@ -33,6 +33,10 @@ constexpr int kStagesFast = 4;   // tiles in flight per wave on the fast path
 // that is priced at 10 to 16 tiles.
 // The split charges it to the unit, as tiles in front of the first real one that nobody reads.
 constexpr int kUnitStartTiles = 12;
+// Blocks go to the XCDs round-robin, and in every launch measured the odd XCD of a pair streams
+// 4-5 % slower than the even one: the waves of an odd block get this many thousandths fewer
+// tiles, those of the even block before it as many more (flat optimum between 40 and 60).
+constexpr int kOddXcdSkewPermille = 40;
 
 struct AttendArgs {
     int layer;
@@ -153,8 +157,18 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
     const int n_waves = (int)gridDim.x * kAttnWaves;
     const int tpw = max(a.min_tpw, (total + n_waves - 1) / n_waves);
     const int wid = (int)blockIdx.x * kAttnWaves + wave;
-    const int T0 = wid * tpw;
-    const int T1 = min(total, T0 + tpw);
+    // shares: a pair of blocks (even, odd) covers 2 * kAttnWaves * tpw tiles, te per wave of the
+    // even block and to per wave of the odd one
+    const int skew = (gridDim.x % 2 == 0) ? tpw * kOddXcdSkewPermille / 1000 : 0;
+    const int te = tpw + skew, to = tpw - skew;
+    constexpr int PW = 2 * kAttnWaves;
+    auto wave_of = [&](int x) {  // the wave whose share holds tile x
+        const int pr = x / (PW * tpw), r = x % (PW * tpw);
+        return pr * PW + (r < kAttnWaves * te ? r / te : kAttnWaves + (r - kAttnWaves * te) / to);
+    };
+    const int widx = wid % PW;
+    const int T0 = (wid / PW) * (PW * tpw) + (widx < kAttnWaves ? widx * te : kAttnWaves * te + (widx - kAttnWaves) * to);
+    const int T1 = min(total, T0 + (widx < kAttnWaves ? te : to));
     if (T0 >= T1) return;
 
     // first unit of the share: the u with s_ts[u] <= T0 < s_ts[u+1]
@@ -527,7 +541,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
             }
         }
         // waves whose share overlaps this unit
-        const int w_first = (s_ts[u] + kUnitStartTiles) / tpw, w_last = (s_ts[u + 1] - 1) / tpw;
+        const int w_first = wave_of(s_ts[u] + kUnitStartTiles), w_last = wave_of(s_ts[u + 1] - 1);
         float *o = a.out + ((size_t)b * pv.Hq + (size_t)h * G) * D;
         if (w_first == w_last) {  // the unit lies inside this wave's share
             if (lane < LPT) {
