@@ -5,7 +5,7 @@
 // forward with the row log-sum-exp, and the gradients with respect to q, k, v and g.
 //
 //   soft_attn_fwd_kernel       block = 64 query positions x the 4 query heads of a kv head,
-//                              key tiles of 32 staged in LDS; S^T = K Q^T, O^T = V^T P^T
+//                              key tiles of 64 staged in LDS; S^T = K Q^T, O^T = V^T P^T
 //   soft_attn_rowdot_kernel    D_i = dO_i . O_i per (position, query head)
 //   soft_attn_bwd_dq_kernel    same blocking as the forward: S^T and dP^T = V dO^T per key tile,
 //                              dS^T = P^T (dP^T - D), dQ^T += K^T dS^T
@@ -102,11 +102,14 @@ __device__ __forceinline__ sa_bf16x8_t sa_get_tr(const char *tile, int qn, int h
 // ---------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------
+constexpr int kSaT2 = 64;   // keys per tile of the forward kernel
+constexpr int kSaTr2 = 136; // bytes per d row of its transposed V tile (128 + 8 pad)
+
 __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArgs a) {
-    __shared__ __attribute__((aligned(16))) char s_k[2][kSaT * kSaRm];
-    __shared__ __attribute__((aligned(16))) char s_vt[2][kSaD * kSaTr];
-    __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT];
-    __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT];
+    __shared__ __attribute__((aligned(16))) char s_k[2][kSaT2 * kSaRm];
+    __shared__ __attribute__((aligned(16))) char s_vt[2][kSaD * kSaTr2];
+    __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT2];
+    __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT2];
 
     const int b = blockIdx.z, h = blockIdx.y;
     const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;  // longest rows first
@@ -117,7 +120,7 @@ __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArg
     const int qn = lane & 31, half = lane >> 5;
     const int q0 = qt * kSaQ;
     const int i_end = min(T, q0 + kSaQ);
-    const int n_tiles = (i_end + kSaT - 1) / kSaT;
+    const int n_tiles = (i_end + kSaT2 - 1) / kSaT2;
 
     sa_bf16x8_t qv[8];
     const int qi = min(q0 + rb * 32 + qn, T - 1);
@@ -135,26 +138,53 @@ __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArg
 #pragma unroll
         for (int c = 0; c < 16; c++) o[db][c] = 0.f;
 
+    // staging: a thread carries two pairs of keys (pair ld_pair and ld_pair + 16)
     const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
-    const int ld_key = 2 * ld_pair + ld_sel;
     const int64_t v_delta = a.v - a.k;
-    uint4 kreg;
-    uint2 vreg0, vreg1;
-    float bin_reg, bout_reg;
+    uint4 kreg0, kreg1;
+    uint2 va0, va1, vb0, vb1;
+    float bin0, bout0, bin1, bout1;
     auto fetch = [&](int t) __attribute__((always_inline)) {
-        const int idx0 = t * kSaT + 2 * ld_pair;
-        const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hkv + h;
-        const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hkv + h;
-        const char *kp0 = a.k + row0 * (kSaD * 2), *kp1 = a.k + row1 * (kSaD * 2);
-        kreg = *reinterpret_cast<const uint4 *>((ld_sel ? kp1 : kp0) + ld_dc * 16);
-        vreg0 = *reinterpret_cast<const uint2 *>(kp0 + v_delta + ld_dc * 16 + ld_sel * 8);
-        vreg1 = *reinterpret_cast<const uint2 *>(kp1 + v_delta + ld_dc * 16 + ld_sel * 8);
-        sa_bias(a.g[ld_sel ? row1 : row0], a.eps, bin_reg, bout_reg);
+        {
+            const int idx0 = t * kSaT2 + 2 * ld_pair;
+            const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hkv + h;
+            const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hkv + h;
+            const char *kp0 = a.k + row0 * (kSaD * 2), *kp1 = a.k + row1 * (kSaD * 2);
+            kreg0 = *reinterpret_cast<const uint4 *>((ld_sel ? kp1 : kp0) + ld_dc * 16);
+            va0 = *reinterpret_cast<const uint2 *>(kp0 + v_delta + ld_dc * 16 + ld_sel * 8);
+            va1 = *reinterpret_cast<const uint2 *>(kp1 + v_delta + ld_dc * 16 + ld_sel * 8);
+            sa_bias(a.g[ld_sel ? row1 : row0], a.eps, bin0, bout0);
+        }
+        {
+            const int idx0 = t * kSaT2 + 32 + 2 * ld_pair;
+            const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hkv + h;
+            const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hkv + h;
+            const char *kp0 = a.k + row0 * (kSaD * 2), *kp1 = a.k + row1 * (kSaD * 2);
+            kreg1 = *reinterpret_cast<const uint4 *>((ld_sel ? kp1 : kp0) + ld_dc * 16);
+            vb0 = *reinterpret_cast<const uint2 *>(kp0 + v_delta + ld_dc * 16 + ld_sel * 8);
+            vb1 = *reinterpret_cast<const uint2 *>(kp1 + v_delta + ld_dc * 16 + ld_sel * 8);
+            sa_bias(a.g[ld_sel ? row1 : row0], a.eps, bin1, bout1);
+        }
+    };
+    auto put_tr2 = [&](char *tile, int pair, uint2 r0, uint2 r1) __attribute__((always_inline)) {
+        const uint32_t a0[2] = {r0.x, r0.y}, a1[2] = {r1.x, r1.y};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const uint32_t x0 = (e & 1) ? (a0[e >> 1] >> 16) : (a0[e >> 1] & 0xffffu);
+            const uint32_t x1 = (e & 1) ? (a1[e >> 1] & 0xffff0000u) : (a1[e >> 1] << 16);
+            *reinterpret_cast<uint32_t *>(tile + (ld_dc * 8 + ld_sel * 4 + e) * kSaTr2 + pair * 4) = x0 | x1;
+        }
     };
     auto stage = [&](int buf) __attribute__((always_inline)) {
-        sa_put_rm(s_k[buf], ld_key, ld_dc, kreg);
-        sa_put_tr(s_vt[buf], ld_pair, ld_dc, ld_sel, vreg0, vreg1);
-        if (ld_dc == 0) { s_bin[buf][ld_key] = bin_reg; s_bout[buf][ld_key] = bout_reg; }
+        const int key0 = 2 * ld_pair + ld_sel;
+        sa_put_rm(s_k[buf], key0, ld_dc, kreg0);
+        sa_put_rm(s_k[buf], key0 + 32, ld_dc, kreg1);
+        put_tr2(s_vt[buf], ld_pair, va0, va1);
+        put_tr2(s_vt[buf], ld_pair + 16, vb0, vb1);
+        if (ld_dc == 0) {
+            s_bin[buf][key0] = bin0; s_bout[buf][key0] = bout0;
+            s_bin[buf][key0 + 32] = bin1; s_bout[buf][key0 + 32] = bout1;
+        }
     };
 
     fetch(0);
@@ -162,59 +192,64 @@ __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArg
     __syncthreads();
     for (int t = 0; t < n_tiles; t++) {
         const int buf = t & 1;
-        sa_bf16x8_t ka[8];
+        // ---- S^T for the two halves of 32 keys ----
+        sa_f32x16_t s0, s1;
 #pragma unroll
-        for (int ks = 0; ks < 8; ks++) ka[ks] = sa_get_rm(s_k[buf], qn, half, ks);
-        __builtin_amdgcn_sched_barrier(0);
-        if (t + 1 < n_tiles) fetch(t + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        sa_f32x16_t s;
+        for (int c = 0; c < 16; c++) { s0[c] = 0.f; s1[c] = 0.f; }
+        {
+            sa_bf16x8_t ka[8];
 #pragma unroll
-        for (int c = 0; c < 16; c++) s[c] = 0.f;
+            for (int ks = 0; ks < 8; ks++) ka[ks] = sa_get_rm(s_k[buf], qn, half, ks);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 1 < n_tiles) fetch(t + 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ks = 0; ks < 8; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qv[ks], s, 0, 0, 0);
-        sa_bf16x8_t va[2][4];
+            for (int ks = 0; ks < 8; ks++) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qv[ks], s0, 0, 0, 0);
 #pragma unroll
-        for (int t2 = 0; t2 < 2; t2++)
+            for (int ks = 0; ks < 8; ks++) ka[ks] = sa_get_rm(s_k[buf], 32 + qn, half, ks);
 #pragma unroll
-            for (int db = 0; db < 4; db++) va[t2][db] = sa_get_tr(s_vt[buf], qn, half, db, t2);
-        __builtin_amdgcn_sched_barrier(0);
-        // register c = 4j+i of a lane holds key 8j + 4*half + i of the tile
-        const bool far = t * kSaT + kSaT - 1 <= q0 - a.W;  // every key outside every window of the block
-        float sc[16];
+            for (int ks = 0; ks < 8; ks++) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qv[ks], s1, 0, 0, 0);
+        }
+        // register c = 4j+i of s0 (s1) holds key 8j + 4*half + i (+ 32) of the tile
+        const bool far = t * kSaT2 + kSaT2 - 1 <= q0 - a.W;  // every key outside every window of the block
+        float sc[32];
         float mt = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const float4 bo4 = *reinterpret_cast<const float4 *>(&s_bout[buf][8 * j + 4 * half]);
-            const float bo[4] = {bo4.x, bo4.y, bo4.z, bo4.w};
-            if (far) {
+        for (int hf = 0; hf < 2; hf++)
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    sc[4 * j + i] = fmaf(s[4 * j + i], a.scale_log2e, bo[i]);
-                    mt = fmaxf(mt, sc[4 * j + i]);
-                }
-            } else {
-                const float4 bi4 = *reinterpret_cast<const float4 *>(&s_bin[buf][8 * j + 4 * half]);
-                const float bi[4] = {bi4.x, bi4.y, bi4.z, bi4.w};
+            for (int j = 0; j < 4; j++) {
+                const float4 bo4 = *reinterpret_cast<const float4 *>(&s_bout[buf][32 * hf + 8 * j + 4 * half]);
+                const float bo[4] = {bo4.x, bo4.y, bo4.z, bo4.w};
+                if (far) {
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    const int jg = t * kSaT + 8 * j + 4 * half + i;
-                    const float bias = (qi - jg < a.W) ? bi[i] : bo[i];
-                    const float x = (jg <= qi) ? fmaf(s[4 * j + i], a.scale_log2e, bias) : -INFINITY;
-                    sc[4 * j + i] = x;
-                    mt = fmaxf(mt, x);
+                    for (int i = 0; i < 4; i++) {
+                        const float sv = hf ? s1[4 * j + i] : s0[4 * j + i];
+                        sc[16 * hf + 4 * j + i] = fmaf(sv, a.scale_log2e, bo[i]);
+                        mt = fmaxf(mt, sc[16 * hf + 4 * j + i]);
+                    }
+                } else {
+                    const float4 bi4 = *reinterpret_cast<const float4 *>(&s_bin[buf][32 * hf + 8 * j + 4 * half]);
+                    const float bi[4] = {bi4.x, bi4.y, bi4.z, bi4.w};
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        const int jg = t * kSaT2 + 32 * hf + 8 * j + 4 * half + i;
+                        const float sv = hf ? s1[4 * j + i] : s0[4 * j + i];
+                        const float bias = (qi - jg < a.W) ? bi[i] : bo[i];
+                        const float x = (jg <= qi) ? fmaf(sv, a.scale_log2e, bias) : -INFINITY;
+                        sc[16 * hf + 4 * j + i] = x;
+                        mt = fmaxf(mt, x);
+                    }
                 }
             }
-        }
         mt = fmaxf(mt, __shfl_xor(mt, 32));
         const float mnew = fmaxf(m, mt);
         const float msafe = mnew == -INFINITY ? 0.f : mnew;
         const float corr = __builtin_amdgcn_exp2f(m - msafe);
-        uint32_t pb[8];
+        uint32_t pb[16];
         float ps = 0.f, px = 0.f;
         const sa_bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-        for (int c = 0; c < 8; c++) {
+        for (int c = 0; c < 16; c++) {
             const float p0 = __builtin_amdgcn_exp2f(sc[2 * c] - msafe), p1 = __builtin_amdgcn_exp2f(sc[2 * c + 1] - msafe);
             px += p0 + p1;
             pb[c] = sa_pack(p0, p1);
@@ -229,12 +264,19 @@ __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArg
                 for (int c = 0; c < 16; c++) o[db][c] *= corr;
         }
         m = mnew;
+        // ---- O^T += V^T P^T, four steps of 16 keys ----
 #pragma unroll
-        for (int t2 = 0; t2 < 2; t2++) {
+        for (int t2 = 0; t2 < 4; t2++) {
             const uint4 p4 = make_uint4(pb[4 * t2], pb[4 * t2 + 1], pb[4 * t2 + 2], pb[4 * t2 + 3]);
             const sa_bf16x8_t pbv = __builtin_bit_cast(sa_bf16x8_t, p4);
 #pragma unroll
-            for (int db = 0; db < 4; db++) o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t2][db], pbv, o[db], 0, 0, 0);
+            for (int db = 0; db < 4; db++) {
+                const char *vp = &s_vt[buf][(db * 32 + qn) * kSaTr2 + (16 * t2 + 4 * half) * 2];
+                const uint2 v0 = *reinterpret_cast<const uint2 *>(vp);
+                const uint2 v1 = *reinterpret_cast<const uint2 *>(vp + 16);
+                const uint4 u4 = make_uint4(v0.x, v0.y, v1.x, v1.y);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(sa_bf16x8_t, u4), pbv, o[db], 0, 0, 0);
+            }
         }
         if (t + 1 < n_tiles) stage(buf ^ 1);
         __syncthreads();
