@@ -168,6 +168,18 @@ int wgkv_soft_attn_backward(int32_t dtype, int32_t n_seqs, const int32_t *n_toke
                             float *dq_dev, float *dk_dev, float *dv_dev, float *dg_dev,
                             void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
 
+/* Sec. 3.3, sparsity term of the training objective over n scores out of n_total (the
+ * paper's L * H * T; a caller that holds the scores layer by layer adds up the calls):
+ *   *loss_dev = sum_x (g[x] + g[x] (1 - g[x])) / n_total,   dg_dev[x] = (2 - 2 g[x]) / n_total.
+ *   g_dev float [n]; loss_dev one float; dg_dev float [n] or NULL; workspace_dev at least
+ *   WGKV_SPARSITY_WS_BYTES bytes, contents undefined before and after.
+ * fp32 sums in a fixed order (the last stage in double): the value repeats bit for bit.
+ * Device buffers are the caller's; the call only enqueues work on `stream`.
+ * Errors: INVALID_ARG (n < 0, n > n_total, NULL), WORKSPACE, HIP. */
+#define WGKV_SPARSITY_WS_BYTES 4096
+int wgkv_sparsity_loss(const float *g_dev, int64_t n, int64_t n_total, float *loss_dev, float *dg_dev,
+                       void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
+
 /* Sec. 3.2, feature equation and gate equation (the Write-Gate MLP), per token t and
  * kv head h:  x = [RMSNorm(k[t][h]) ; RMSNorm(k_rope[t][h])],
  *             g[t][h] = sigmoid(W2[h] . GELU(W1[h] x + b1[h]) + b2[h]).

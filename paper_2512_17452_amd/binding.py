@@ -13,7 +13,7 @@ EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
     "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
     "wgkv_quest_select", "wgkv_attend_selected", "wgkv_soft_attn_forward", "wgkv_soft_attn_workspace_bytes",
-    "wgkv_soft_attn_backward", "wgkv_free_seq",
+    "wgkv_soft_attn_backward", "wgkv_sparsity_loss", "wgkv_free_seq",
     "wgkv_status", "wgkv_set_profile_events", "wgkv_destroy",
 ]
 
@@ -90,6 +90,7 @@ def load_library():
     L.wgkv_soft_attn_workspace_bytes.restype = sz
     L.wgkv_soft_attn_backward.argtypes = [i32, i32, pi32, i32, i32, i32, i32, vp, vp, vp, vp, f32, f32, vp, vp, vp,
                                           vp, vp, vp, vp, vp, sz, vp]
+    L.wgkv_sparsity_loss.argtypes = [vp, i64, i64, vp, vp, vp, sz, vp]
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
@@ -182,6 +183,22 @@ def soft_attn_backward(q, k, v, g, out, lse, dout, n_tokens, w_local, scale, eps
     if rc:
         raise WgkvError(rc, "wgkv_soft_attn_backward")
     return dq, dk, dv, dg
+
+
+def sparsity_loss(g, n_total=None, need_grad=True):
+    """wgkv_sparsity_loss: (loss float32 [1], dg float32 like g or None) of the scores g (float32, any shape)."""
+    import torch
+    L = load_library()
+    assert g.dtype == torch.float32 and g.is_contiguous()
+    n = g.numel()
+    loss = torch.empty(1, dtype=torch.float32, device=g.device)
+    dg = torch.empty_like(g) if need_grad else None
+    ws = torch.empty(4096, dtype=torch.uint8, device=g.device)
+    rc = L.wgkv_sparsity_loss(_ptr(g), n, int(n_total if n_total is not None else n), _ptr(loss), _ptr(dg), _ptr(ws),
+                              4096, _stream())
+    if rc:
+        raise WgkvError(rc, "wgkv_sparsity_loss")
+    return loss, dg
 
 
 def gate_mlp_scores(k, k_rope, w1, b1, w2, b2, eps=1e-6, out=None):

@@ -19,6 +19,7 @@
 // go through LDS in two forms: row-major (rows are the M side of a product over d) and
 // transposed (rows are d, for the products that contract over positions).  A lane of an
 // accumulator tile owns one column, so per-column quantities are plain scalars.
+#include <algorithm>
 #include <climits>
 
 #include "wgkv_dev.h"
@@ -680,6 +681,52 @@ hipError_t launch_soft_attn_bwd(int n_seqs, const int32_t *n_tokens, int Hq, int
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(soft_attn_bwd_dkv_kernel, dim3((max_t + kSaKB - 1) / kSaKB, Hkv, n_seqs), dim3(512), 0, st, cs, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sparsity term of the training objective (Sec. 3.3): sum over the given scores of
+// (g + g (1 - g)) / n_total and its derivative (2 - 2 g) / n_total.  Two launches with a fixed
+// order of additions (per-thread strided sums, block tree, then one thread over the blocks in
+// double), so the value repeats bit for bit.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSpBlocks = 1024;
+
+__global__ __launch_bounds__(256) void sparsity_partial_kernel(const float *g, int64_t n, float inv_n, float *dg,
+                                                               float *partial) {
+    __shared__ float s_red[256];
+    float acc = 0.f;
+    for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n; x += (int64_t)gridDim.x * 256) {
+        const float v = g[x];
+        acc += v + v * (1.0f - v);
+        if (dg) dg[x] = (2.0f - 2.0f * v) * inv_n;
+    }
+    s_red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) s_red[threadIdx.x] += s_red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = s_red[0];
+}
+
+__global__ void sparsity_final_kernel(const float *partial, int nb, double inv_n, float *loss) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    double t = 0.0;
+    for (int i = 0; i < nb; i++) t += (double)partial[i];
+    *loss = (float)(t * inv_n);
+}
+
+size_t sparsity_ws_bytes() { return kSpBlocks * sizeof(float); }
+
+hipError_t launch_sparsity_loss(const float *g, int64_t n, int64_t n_total, float *loss, float *dg, void *ws,
+                                hipStream_t st) {
+    const int nb = (int)std::min<int64_t>(kSpBlocks, std::max<int64_t>(1, (n + 255) / 256));
+    const double inv = 1.0 / (double)n_total;
+    hipLaunchKernelGGL(sparsity_partial_kernel, dim3(nb), dim3(256), 0, st, g, n, (float)inv, dg, (float *)ws);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(sparsity_final_kernel, dim3(1), dim3(64), 0, st, (const float *)ws, nb, inv, loss);
     return hipGetLastError();
 }
 

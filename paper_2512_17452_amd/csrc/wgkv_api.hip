@@ -52,6 +52,9 @@ hipError_t launch_soft_attn_bwd(int n_seqs, const int32_t *n_tokens, int Hq, int
                                 const void *q, const void *k, const void *v, const float *g, float scale,
                                 float eps, const float *out, const float *lse, const void *dout, float *dq,
                                 float *dk, float *dv, float *dg, void *ws, hipStream_t st);
+size_t sparsity_ws_bytes();
+hipError_t launch_sparsity_loss(const float *g, int64_t n, int64_t n_total, float *loss, float *dg, void *ws,
+                                hipStream_t st);
 size_t attend_prefill_ws_bytes(const View &pv, int n_seqs, int64_t total_q);
 hipError_t launch_attend_prefill(const View &pv, const CallSeqs &cs, int layer, const void *q,
                                  const void *k, const void *v, const float *g, float tau,
@@ -350,6 +353,16 @@ int wgkv_soft_attn_backward(int32_t dtype, int32_t n_seqs, const int32_t *n_toke
     return launch_soft_attn_bwd(n_seqs, n_tokens_host, n_q_heads, n_kv_heads, head_dim, w_local, q_dev, k_dev,
                                 v_dev, g_dev, scale, eps, out_dev, lse_dev, dout_dev, dq_dev, dk_dev, dv_dev,
                                 dg_dev, workspace_dev, (hipStream_t)stream) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
+}
+
+int wgkv_sparsity_loss(const float *g_dev, int64_t n, int64_t n_total, float *loss_dev, float *dg_dev,
+                       void *workspace_dev, size_t workspace_bytes, wgkv_stream stream) {
+    if (n < 0 || n_total < 1 || n > n_total || !loss_dev || !workspace_dev || (n > 0 && !g_dev))
+        return WGKV_ERR_INVALID_ARG;
+    if (workspace_bytes < sparsity_ws_bytes()) return WGKV_ERR_WORKSPACE;
+    return launch_sparsity_loss(g_dev, n, n_total, loss_dev, dg_dev, workspace_dev, (hipStream_t)stream) == hipSuccess
                ? WGKV_OK
                : WGKV_ERR_HIP;
 }

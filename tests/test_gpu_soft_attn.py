@@ -11,6 +11,7 @@ import torch
 import paper_2512_17452_amd as wg
 import wgkv_workloads as wl
 from oracle import attend_soft, soft_attn_backward, soft_attn_backward_sampled, soft_attn_forward
+from oracle import sparsity_loss as oracle_sparsity_loss
 
 pytestmark = pytest.mark.gpu
 
@@ -198,3 +199,20 @@ def test_argument_errors_are_reported_before_anything_runs():
                                    p(dout), p(dq), p(dk), p(dv), p(dg), p(ws), need - 1, st)
     assert rc == -6
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("n", [1, 255, 4097, 3_000_001])
+def test_sparsity_loss_and_its_gradient(n):
+    """Sec. 3.3 sparsity term: fp32 sums of n terms in [0, 1] against fp64 (relative 1e-6), the
+    gradient element by element (one multiply-add in fp32), a partial call with a larger
+    normaliser, and the same bits on a second run."""
+    dev = torch.device("cuda:0")
+    cfg = _cfg(20, 1)
+    g = torch.from_numpy(wl.draw_scores(cfg, 0, 0, n, wl.unit_rates(cfg))[:, 0].copy())
+    loss, dg = wg.sparsity_loss(g.to(dev))
+    ref, rdg = oracle_sparsity_loss(g.numpy())
+    assert abs(loss.item() - ref) <= 1e-6 * max(ref, 1e-30)
+    assert np.abs(dg.cpu().numpy().astype(np.float64) - rdg).max() <= 3e-7 / n
+    loss2, none = wg.sparsity_loss(g.to(dev), n_total=4 * n, need_grad=False)
+    assert none is None and abs(loss2.item() - ref / 4) <= 1e-6 * max(ref / 4, 1e-30)
+    assert torch.equal(wg.sparsity_loss(g.to(dev))[0], loss)
