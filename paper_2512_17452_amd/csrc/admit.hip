@@ -252,28 +252,53 @@ __global__ __launch_bounds__(256) void prefill_ring_kernel(View pv, CallSeqs cs,
 }
 
 // One block does the whole step: decisions and page hand-out first (they need a
-// prefix over units), then the row moves.
+// prefix over units), then the row moves.  The kernel is a chain of memory round trips, so
+// everything whose address is known early is asked for early: the new rows at once, the
+// victim's score and the page of its ring slot at the slot the host expects (checked against
+// the device's own token count, which decides), the page of the promotion target as soon as
+// the global length is there.  The row moves then only wait for the victim's row.
 __global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs, DecodeArgs a) {
     __shared__ int s_gold[kMaxCallUnits];   // G before the step, bit 31 = promote
+    __shared__ int s_lpage[kMaxCallUnits];  // page of the ring slot that is overwritten
+    __shared__ int s_gpage[kMaxCallUnits];  // page of global slot G (promoting units)
+    __shared__ int s_t[kMaxCallSeqs];       // token counts before the step
     __shared__ int s_tmp[20];
     __shared__ int s_err;
     const int n_units = cs.n * pv.Hkv;
+    const int lpr = pv.row_bytes >> 4, n_items = n_units * lpr;
+    uint4 kn = make_uint4(0, 0, 0, 0), vn = kn;  // this thread's first chunk of the new rows
+    if ((int)threadIdx.x < n_items) {
+        const size_t row = (size_t)(threadIdx.x / lpr) * pv.row_bytes + (threadIdx.x % lpr) * 16;
+        kn = *reinterpret_cast<const uint4 *>(a.k + row);
+        vn = *reinterpret_cast<const uint4 *>(a.v + row);
+    }
+    const int t_seq = ((int)threadIdx.x < cs.n) ? pv.seq_len[cs.sid[threadIdx.x] * pv.L + a.layer] : 0;
     if (threadIdx.x == 0) s_err = 0;
     __syncthreads();
     const int top = *pv.free_top;
     const int u = threadIdx.x;  // n_units <= 1024 = blockDim.x
-    int demand = 0, dl = 0, promote = 0, gold = 0, um = 0, slot = 0;
+    int demand = 0, dl = 0, promote = 0, gold = 0, um = 0, slot = 0, lpage = -1, gpage = -1;
     if (u < n_units) {
         // the token count comes from device memory, not from the launch arguments, so that a
         // captured launch can be replayed: every replay is one more token
-        const int b = u / pv.Hkv, h = u % pv.Hkv, t = pv.seq_len[cs.sid[b] * pv.L + a.layer];
+        const int b = u / pv.Hkv, h = u % pv.Hkv;
         um = unit_meta(pv, cs.sid[b], a.layer, h);
-        slot = t % pv.W;
+        const int slot_h = cs.t0[b] % pv.W;  // where the host's count puts the victim
+        const int t = pv.seq_len[cs.sid[b] * pv.L + a.layer];
         gold = pv.global_len[um];
-        promote = (t >= pv.W) && (pv.ring_g[(size_t)um * pv.W + slot] >= a.tau);
-        dl = (pv.local_pt[(size_t)um * pv.nlp] < 0) ? pv.nlp : 0;
+        const int lp0 = pv.local_pt[(size_t)um * pv.nlp];
+        float rg = pv.ring_g[(size_t)um * pv.W + slot_h];
+        lpage = pv.local_pt[(size_t)um * pv.nlp + (slot_h >> pv.logP)];
+        slot = t % pv.W;
+        if (slot != slot_h) {  // a replayed launch: the host's count is the one of the capture
+            rg = pv.ring_g[(size_t)um * pv.W + slot];
+            lpage = pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)];
+        }
+        promote = (t >= pv.W) && (rg >= a.tau);
+        dl = (lp0 < 0) ? pv.nlp : 0;
         const int need = promote && ((gold & (pv.P - 1)) == 0);
         if (need && (gold >> pv.logP) >= pv.maxgp) s_err = WGKV_ERR_PT_OVERFLOW;
+        else if (promote && !need) gpage = pv.global_pt[(size_t)um * pv.maxgp + (gold >> pv.logP)];
         demand = dl + need;
     }
     int total;
@@ -285,39 +310,49 @@ __global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs,
         return;
     }
     if (u < n_units) {
-        for (int i = 0; i < dl; i++) pv.local_pt[(size_t)um * pv.nlp + i] = pv.free_stack[top - 1 - (ubase + i)];
-        if (demand > dl) pv.global_pt[(size_t)um * pv.maxgp + (gold >> pv.logP)] = pv.free_stack[top - 1 - (ubase + dl)];
+        for (int i = 0; i < dl; i++) {
+            const int pg = pv.free_stack[top - 1 - (ubase + i)];
+            pv.local_pt[(size_t)um * pv.nlp + i] = pg;
+            if (i == (slot >> pv.logP)) lpage = pg;
+        }
+        if (demand > dl) {
+            gpage = pv.free_stack[top - 1 - (ubase + dl)];
+            pv.global_pt[(size_t)um * pv.maxgp + (gold >> pv.logP)] = gpage;
+        }
         if (promote) pv.global_len[um] = gold + 1;
         if (a.promoted_out) a.promoted_out[u] = (uint8_t)promote;
         s_gold[u] = (int)((unsigned)gold | ((unsigned)promote << 31));
+        s_lpage[u] = lpage;
+        s_gpage[u] = gpage;
     }
-    __shared__ int s_t[kMaxCallSeqs];
-    if (threadIdx.x < cs.n) s_t[threadIdx.x] = pv.seq_len[cs.sid[threadIdx.x] * pv.L + a.layer];
-    __syncthreads();  // every thread has read the old token counts
-    if (threadIdx.x < cs.n) pv.seq_len[cs.sid[threadIdx.x] * pv.L + a.layer] = s_t[threadIdx.x] + 1;
+    if ((int)threadIdx.x < cs.n) {
+        s_t[threadIdx.x] = t_seq;
+        pv.seq_len[cs.sid[threadIdx.x] * pv.L + a.layer] = t_seq + 1;  // every unit thread has its copy already
+    }
     if (threadIdx.x == 0) *pv.free_top = top - total;
-    __syncthreads();  // tables written above are read below by other threads
-    const int lpr = pv.row_bytes >> 4;
-    for (int c = threadIdx.x; c < n_units * lpr; c += blockDim.x) {
+    __syncthreads();  // the pages and counts of all units are in shared memory
+    for (int c = threadIdx.x; c < n_items; c += blockDim.x) {
         const int uu = c / lpr, sub = c % lpr;
         const int b = uu / pv.Hkv, h = uu % pv.Hkv;
         const int m = unit_meta(pv, cs.sid[b], a.layer, h);
         const int sl = s_t[b] % pv.W;
-        char *rp = page_ptr(pv, pv.local_pt[(size_t)m * pv.nlp + (sl >> pv.logP)]) +
-                   (size_t)(sl & (pv.P - 1)) * pv.row_bytes + sub * 16;
+        char *rp = page_ptr(pv, s_lpage[uu]) + (size_t)(sl & (pv.P - 1)) * pv.row_bytes + sub * 16;
         const int gi = s_gold[uu];
         if (gi < 0) {  // promote: ring row -> global slot G_old
             const int g0 = gi & 0x7fffffff;
-            char *dp = page_ptr(pv, pv.global_pt[(size_t)m * pv.maxgp + (g0 >> pv.logP)]) +
-                       (size_t)(g0 & (pv.P - 1)) * pv.row_bytes + sub * 16;
+            char *dp = page_ptr(pv, s_gpage[uu]) + (size_t)(g0 & (pv.P - 1)) * pv.row_bytes + sub * 16;
             const uint4 kk = *reinterpret_cast<const uint4 *>(rp);
             const uint4 vv = *reinterpret_cast<const uint4 *>(rp + pv.v_off);
             *reinterpret_cast<uint4 *>(dp) = kk;
             *reinterpret_cast<uint4 *>(dp + pv.v_off) = vv;
         }
-        const size_t row = (size_t)uu * pv.row_bytes + sub * 16;
-        *reinterpret_cast<uint4 *>(rp) = *reinterpret_cast<const uint4 *>(a.k + row);
-        *reinterpret_cast<uint4 *>(rp + pv.v_off) = *reinterpret_cast<const uint4 *>(a.v + row);
+        if (c != (int)threadIdx.x) {  // beyond the first 1024 chunks: not in registers yet
+            const size_t row = (size_t)uu * pv.row_bytes + sub * 16;
+            kn = *reinterpret_cast<const uint4 *>(a.k + row);
+            vn = *reinterpret_cast<const uint4 *>(a.v + row);
+        }
+        *reinterpret_cast<uint4 *>(rp) = kn;
+        *reinterpret_cast<uint4 *>(rp + pv.v_off) = vn;
         if (sub == 0) pv.ring_g[(size_t)m * pv.W + sl] = a.g[uu];
     }
 }
