@@ -362,38 +362,40 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
     const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
     const int ld_key = 2 * ld_pair + ld_sel;
     const int64_t v_delta = a.v - a.k;
-    uint4 kreg, vreg;
-    uint2 kt0, kt1;
-    float bin_reg, bout_reg;
-    auto fetch = [&](int t) __attribute__((always_inline)) {
+    // two sets of staging registers: a tile is requested two iterations before it is multiplied
+    struct StReg { uint4 kreg, vreg; uint2 kt0, kt1; float bin_reg, bout_reg; };
+    StReg r0, r1;
+    auto fetch = [&](int t, StReg &r) __attribute__((always_inline)) {
         const int idx0 = t * kSaT + 2 * ld_pair;
         const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hkv + h;
         const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hkv + h;
         const char *kp0 = a.k + row0 * (kSaD * 2), *kp1 = a.k + row1 * (kSaD * 2);
         const char *ks = ld_sel ? kp1 : kp0;
-        kreg = *reinterpret_cast<const uint4 *>(ks + ld_dc * 16);
-        vreg = *reinterpret_cast<const uint4 *>(ks + v_delta + ld_dc * 16);
-        kt0 = *reinterpret_cast<const uint2 *>(kp0 + ld_dc * 16 + ld_sel * 8);
-        kt1 = *reinterpret_cast<const uint2 *>(kp1 + ld_dc * 16 + ld_sel * 8);
-        sa_bias(a.g[ld_sel ? row1 : row0], a.eps, bin_reg, bout_reg);
+        r.kreg = *reinterpret_cast<const uint4 *>(ks + ld_dc * 16);
+        r.vreg = *reinterpret_cast<const uint4 *>(ks + v_delta + ld_dc * 16);
+        r.kt0 = *reinterpret_cast<const uint2 *>(kp0 + ld_dc * 16 + ld_sel * 8);
+        r.kt1 = *reinterpret_cast<const uint2 *>(kp1 + ld_dc * 16 + ld_sel * 8);
+        sa_bias(a.g[ld_sel ? row1 : row0], a.eps, r.bin_reg, r.bout_reg);
     };
-    auto stage = [&](int buf) __attribute__((always_inline)) {
-        sa_put_rm(s_k[buf], ld_key, ld_dc, kreg);
-        sa_put_rm(s_v[buf], ld_key, ld_dc, vreg);
-        sa_put_tr(s_kt[buf], ld_pair, ld_dc, ld_sel, kt0, kt1);
-        if (ld_dc == 0) { s_bin[buf][ld_key] = bin_reg; s_bout[buf][ld_key] = bout_reg; }
+    auto stage = [&](int buf, const StReg &r) __attribute__((always_inline)) {
+        sa_put_rm(s_k[buf], ld_key, ld_dc, r.kreg);
+        sa_put_rm(s_v[buf], ld_key, ld_dc, r.vreg);
+        sa_put_tr(s_kt[buf], ld_pair, ld_dc, ld_sel, r.kt0, r.kt1);
+        if (ld_dc == 0) { s_bin[buf][ld_key] = r.bin_reg; s_bout[buf][ld_key] = r.bout_reg; }
     };
 
-    fetch(0);
-    stage(0);
+    fetch(0, r0);
+    stage(0, r0);
+    if (n_tiles > 1) fetch(1, r1);
     __syncthreads();
-    for (int t = 0; t < n_tiles; t++) {
+    // one iteration: tile t is multiplied, tile t+2 is requested into rf, tile t+1 goes from rs to LDS
+    auto body = [&](int t, StReg &rf, const StReg &rs) __attribute__((always_inline)) {
         const int buf = t & 1;
         sa_bf16x8_t ka[8];
 #pragma unroll
         for (int ks = 0; ks < 8; ks++) ka[ks] = sa_get_rm(s_k[buf], qn, half, ks);
         __builtin_amdgcn_sched_barrier(0);
-        if (t + 1 < n_tiles) fetch(t + 1);
+        if (t + 2 < n_tiles) fetch(t + 2, rf);
         __builtin_amdgcn_sched_barrier(0);
         sa_f32x16_t s, dp;
 #pragma unroll
@@ -430,8 +432,16 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
             for (int db = 0; db < 4; db++)
                 dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_tr(s_kt[buf], qn, half, db, t2), dsv, dq[db], 0, 0, 0);
         }
-        if (t + 1 < n_tiles) stage(buf ^ 1);
+        if (t + 1 < n_tiles) stage(buf ^ 1, rs);
         __syncthreads();
+    };
+    {
+        int t = 0;
+        for (; t + 1 < n_tiles; t += 2) {
+            body(t, r0, r1);
+            body(t + 1, r1, r0);
+        }
+        if (t < n_tiles) body(t, r0, r1);
     }
     const int i = q0 + rb * 32 + qn;
     if (i < T) {
@@ -493,39 +503,42 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
     const int n_it = (n_qt - qt_first) * kSaG;
     const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
     const int ld_row = 2 * ld_pair + ld_sel;
-    uint4 qreg, doreg;
-    uint2 qt0, qt1, dt0, dt1;
-    float lse_reg, dd_reg;
-    auto fetch = [&](int it) __attribute__((always_inline)) {
+    // two sets of staging registers: the loads of a tile are issued two iterations before the
+    // tile is multiplied (one iteration is shorter than the latency of a load under this traffic)
+    struct StReg { uint4 qreg, doreg; uint2 qt0, qt1, dt0, dt1; float lse_reg, dd_reg; };
+    StReg r0, r1;
+    auto fetch = [&](int it, StReg &r) __attribute__((always_inline)) {
         const int qt = qt_first + it / kSaG, hd = it % kSaG;
         const int idx0 = qt * kSaT + 2 * ld_pair;
         const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hq + (size_t)h * kSaG + hd;
         const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hq + (size_t)h * kSaG + hd;
         const char *qp0 = a.q + row0 * (kSaD * 2), *qp1 = a.q + row1 * (kSaD * 2);
         const char *dp0 = a.dout + row0 * (kSaD * 2), *dp1 = a.dout + row1 * (kSaD * 2);
-        qreg = *reinterpret_cast<const uint4 *>((ld_sel ? qp1 : qp0) + ld_dc * 16);
-        doreg = *reinterpret_cast<const uint4 *>((ld_sel ? dp1 : dp0) + ld_dc * 16);
-        qt0 = *reinterpret_cast<const uint2 *>(qp0 + ld_dc * 16 + ld_sel * 8);
-        qt1 = *reinterpret_cast<const uint2 *>(qp1 + ld_dc * 16 + ld_sel * 8);
-        dt0 = *reinterpret_cast<const uint2 *>(dp0 + ld_dc * 16 + ld_sel * 8);
-        dt1 = *reinterpret_cast<const uint2 *>(dp1 + ld_dc * 16 + ld_sel * 8);
+        r.qreg = *reinterpret_cast<const uint4 *>((ld_sel ? qp1 : qp0) + ld_dc * 16);
+        r.doreg = *reinterpret_cast<const uint4 *>((ld_sel ? dp1 : dp0) + ld_dc * 16);
+        r.qt0 = *reinterpret_cast<const uint2 *>(qp0 + ld_dc * 16 + ld_sel * 8);
+        r.qt1 = *reinterpret_cast<const uint2 *>(qp1 + ld_dc * 16 + ld_sel * 8);
+        r.dt0 = *reinterpret_cast<const uint2 *>(dp0 + ld_dc * 16 + ld_sel * 8);
+        r.dt1 = *reinterpret_cast<const uint2 *>(dp1 + ld_dc * 16 + ld_sel * 8);
         const bool real = idx0 + ld_sel < T;  // a row past the end gets weight exp2(-inf) = 0
         const size_t rs = ld_sel ? row1 : row0;
-        lse_reg = real ? a.lse[rs] * 1.4426950408889634f : INFINITY;
-        dd_reg = real ? a.rowdot[rs] : 0.f;
+        r.lse_reg = real ? a.lse[rs] * 1.4426950408889634f : INFINITY;
+        r.dd_reg = real ? a.rowdot[rs] : 0.f;
     };
-    auto stage = [&](int buf) __attribute__((always_inline)) {
-        sa_put_rm(s_q[buf], ld_row, ld_dc, qreg);
-        sa_put_rm(s_do[buf], ld_row, ld_dc, doreg);
-        sa_put_tr(s_qt[buf], ld_pair, ld_dc, ld_sel, qt0, qt1);
-        sa_put_tr(s_dot[buf], ld_pair, ld_dc, ld_sel, dt0, dt1);
-        if (ld_dc == 0) { s_lse[buf][ld_row] = lse_reg; s_dd[buf][ld_row] = dd_reg; }
+    auto stage = [&](int buf, const StReg &r) __attribute__((always_inline)) {
+        sa_put_rm(s_q[buf], ld_row, ld_dc, r.qreg);
+        sa_put_rm(s_do[buf], ld_row, ld_dc, r.doreg);
+        sa_put_tr(s_qt[buf], ld_pair, ld_dc, ld_sel, r.qt0, r.qt1);
+        sa_put_tr(s_dot[buf], ld_pair, ld_dc, ld_sel, r.dt0, r.dt1);
+        if (ld_dc == 0) { s_lse[buf][ld_row] = r.lse_reg; s_dd[buf][ld_row] = r.dd_reg; }
     };
 
-    fetch(0);
-    stage(0);
+    fetch(0, r0);
+    stage(0, r0);
+    fetch(1, r1);  // n_it >= 4
     __syncthreads();
-    for (int it = 0; it < n_it; it++) {
+    // one iteration: tile `it` is multiplied, tile it+2 is requested into rf, tile it+1 goes from rs to LDS
+    auto body = [&](int it, StReg &rf, const StReg &rs) __attribute__((always_inline)) {
         const int buf = it & 1;
         const int i0 = (qt_first + it / kSaG) * kSaT;  // first query of the tile
         // first product: rows = queries of the tile, columns = this wave's keys
@@ -534,7 +547,7 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
 #pragma unroll
         for (int ks = 0; ks < 8; ks++) fa[ks] = sa_get_rm(rm, qn, half, ks);
         __builtin_amdgcn_sched_barrier(0);
-        if (it + 1 < n_it) fetch(it + 1);
+        if (it + 2 < n_it) fetch(it + 2, rf);
         __builtin_amdgcn_sched_barrier(0);
         sa_f32x16_t x;
 #pragma unroll
@@ -591,8 +604,12 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
             for (int db = 0; db < 4; db++)
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_tr(tr, qn, half, db, t2), pv, acc[db], 0, 0, 0);
         }
-        if (it + 1 < n_it) stage(buf ^ 1);
+        if (it + 1 < n_it) stage(buf ^ 1, rs);
         __syncthreads();
+    };
+    for (int it = 0; it < n_it; it += 2) {  // n_it is a multiple of 4
+        body(it, r0, r1);
+        body(it + 1, r1, r0);
     }
     if (jg < T) {
         float *op = (role == 0 ? a.dv : a.dk) + krow * kSaD;
