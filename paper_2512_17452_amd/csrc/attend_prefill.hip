@@ -94,9 +94,9 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
     // threads with ld_sel = 0 carry the K chunk of key 2j and the V chunks of both keys' low
     // half (d chunk ld_dc, elements 0..3); ld_sel = 1: K of key 2j+1 and elements 4..7
     const int ld_key = 2 * ld_pair + ld_sel;
-    uint4 kreg;
-    uint2 vreg[2];
-    int lo_reg, hi_reg;
+    // two sets of staging registers: a tile is requested two iterations before it is multiplied
+    struct StReg { uint4 kreg; uint2 vreg0, vreg1; int lo_reg, hi_reg; };
+    StReg r0, r1;
     // Page ids live in registers, one per lane, so that the address of a key row never
     // waits for a page-table load: 64 consecutive entries of the global table (reloaded
     // every 64 pages) and the whole local table when it has at most 64 entries.
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
     const int lpreg = (lp_in_reg && lane < pv.nlp) ? pv.local_pt[(size_t)um * pv.nlp + lane] : 0;
     const int slot0 = t0 > pv.W ? t0 % pv.W : 0;  // ring slot of the oldest position
     const int64_t v_delta_chunk = a.v - a.k;
-    auto fetch = [&](int t) {
+    auto fetch = [&](int t, StReg &r) __attribute__((always_inline)) {
         const char *kp[2];
         int64_t v_delta;
         int lo[2] = {INT_MAX, INT_MAX}, hi[2] = {INT_MAX, INT_MAX};  // invisible unless shown otherwise
@@ -152,12 +152,12 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
             }
             v_delta = v_delta_chunk;
         }
-        kreg = *reinterpret_cast<const uint4 *>((ld_sel ? kp[1] : kp[0]) + ld_dc * 16);
+        r.kreg = *reinterpret_cast<const uint4 *>((ld_sel ? kp[1] : kp[0]) + ld_dc * 16);
         // V: the same 8-byte half chunk of both keys of the pair
-        vreg[0] = *reinterpret_cast<const uint2 *>(kp[0] + v_delta + ld_dc * 16 + ld_sel * 8);
-        vreg[1] = *reinterpret_cast<const uint2 *>(kp[1] + v_delta + ld_dc * 16 + ld_sel * 8);
-        lo_reg = ld_sel ? lo[1] : lo[0];
-        hi_reg = ld_sel ? hi[1] : hi[0];
+        r.vreg0 = *reinterpret_cast<const uint2 *>(kp[0] + v_delta + ld_dc * 16 + ld_sel * 8);
+        r.vreg1 = *reinterpret_cast<const uint2 *>(kp[1] + v_delta + ld_dc * 16 + ld_sel * 8);
+        r.lo_reg = ld_sel ? lo[1] : lo[0];
+        r.hi_reg = ld_sel ? hi[1] : hi[0];
     };
     // Full tiles of the global cache, pages of at least 4 tokens: the four keys a wave
     // stages share a page, so the page base is scalar and a lane only adds a fixed offset.
@@ -165,23 +165,23 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
     const uint32_t lean_row = (uint32_t)((2 * ld_pair) & (pv.P - 1));
     const uint32_t lean_k_off = (lean_row + ld_sel) * (kPfD * 2) + ld_dc * 16;
     const uint32_t lean_v_off = lean_row * (kPfD * 2) + pv.v_off + ld_dc * 16 + ld_sel * 8;
-    auto fetch_lean = [&](int t) {
+    auto fetch_lean = [&](int t, StReg &r) __attribute__((always_inline)) {
         if (((t * kPfKT + kPfKT - 1) >> pv.logP) >= pt_base + 64) {
             pt_base = (t * kPfKT) >> pv.logP;
             ptreg = (pt_base + lane < pv.maxgp) ? pv.global_pt[(size_t)um * pv.maxgp + pt_base + lane] : 0;
         }
         const int pg = __builtin_amdgcn_readlane(ptreg, ((t * kPfKT + 4 * wave) >> pv.logP) - pt_base);
         const char *sb = page_ptr(pv, pg) + (size_t)((t * kPfKT) & (pv.P - 1)) * (kPfD * 2);
-        kreg = *reinterpret_cast<const uint4 *>(sb + lean_k_off);
-        vreg[0] = *reinterpret_cast<const uint2 *>(sb + lean_v_off);
-        vreg[1] = *reinterpret_cast<const uint2 *>(sb + lean_v_off + kPfD * 2);
-        lo_reg = INT_MIN;
-        hi_reg = INT_MAX;
+        r.kreg = *reinterpret_cast<const uint4 *>(sb + lean_k_off);
+        r.vreg0 = *reinterpret_cast<const uint2 *>(sb + lean_v_off);
+        r.vreg1 = *reinterpret_cast<const uint2 *>(sb + lean_v_off + kPfD * 2);
+        r.lo_reg = INT_MIN;
+        r.hi_reg = INT_MAX;
     };
-    auto stage = [&](int buf) {
-        *reinterpret_cast<uint4 *>(&s_k[buf][ld_key * kPfKStride + ld_dc * 16]) = kreg;
+    auto stage = [&](int buf, const StReg &r) __attribute__((always_inline)) {
+        *reinterpret_cast<uint4 *>(&s_k[buf][ld_key * kPfKStride + ld_dc * 16]) = r.kreg;
         // transposed V: row d, columns (key 2j, key 2j+1) as one 32-bit word
-        const uint32_t a0[2] = {vreg[0].x, vreg[0].y}, a1[2] = {vreg[1].x, vreg[1].y};
+        const uint32_t a0[2] = {r.vreg0.x, r.vreg0.y}, a1[2] = {r.vreg1.x, r.vreg1.y};
 #pragma unroll
         for (int e = 0; e < 4; e++) {
             const uint32_t x0 = (e & 1) ? (a0[e >> 1] >> 16) : (a0[e >> 1] & 0xffffu);
@@ -189,15 +189,21 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
             const int dd = ld_dc * 8 + ld_sel * 4 + e;
             *reinterpret_cast<uint32_t *>(&s_vt[buf][dd * kPfVStride + ld_pair * 4]) = x0 | x1;
         }
-        if (ld_dc == 0) { s_lo[buf][ld_key] = lo_reg; s_hi[buf][ld_key] = hi_reg; }
+        if (ld_dc == 0) { s_lo[buf][ld_key] = r.lo_reg; s_hi[buf][ld_key] = r.hi_reg; }
     };
 
     const int n_plain = gl / kPfKT;  // full tiles of the global cache: no mask
-    fetch(0);
-    stage(0);
+    auto fetch_any = [&](int t, StReg &r) __attribute__((always_inline)) {
+        if (lean_ok && t < n_plain) fetch_lean(t, r);
+        else fetch(t, r);
+    };
+    fetch_any(0, r0);
+    stage(0, r0);
+    if (n_tiles > 1) fetch_any(1, r1);
     __syncthreads();
 
-    for (int t = 0; t < n_tiles; t++) {
+    // one iteration: tile t is multiplied, tile t+2 is requested into rf, tile t+1 goes from rs to LDS
+    auto body = [&](int t, StReg &rf, const StReg &rs) __attribute__((always_inline)) {
         const int buf = t & 1;
         // LDS latency is the scarce thing here: the eight K fragments are requested at once,
         // the address arithmetic and global loads of the next tile run while they arrive,
@@ -207,10 +213,7 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
         for (int ks = 0; ks < 8; ks++)
             ka[ks] = *reinterpret_cast<const pf_bf16x8_t *>(&s_k[buf][qn * kPfKStride + (ks * 16 + half * 8) * 2]);
         __builtin_amdgcn_sched_barrier(0);
-        if (t + 1 < n_tiles) {  // in flight while this tile is multiplied
-            if (lean_ok && t + 1 < n_plain) fetch_lean(t + 1);
-            else fetch(t + 1);
-        }
+        if (t + 2 < n_tiles) fetch_any(t + 2, rf);  // in flight while this tile and the next are multiplied
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- S^T = K Q^T : rows = keys of the tile, columns = this wave's queries ----
@@ -287,8 +290,16 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
             for (int db = 0; db < 4; db++)
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t2][db], pbv, o[db], 0, 0, 0);
         }
-        if (t + 1 < n_tiles) stage(buf ^ 1);
+        if (t + 1 < n_tiles) stage(buf ^ 1, rs);
         __syncthreads();
+    };
+    {
+        int t = 0;
+        for (; t + 1 < n_tiles; t += 2) {
+            body(t, r0, r1);
+            body(t + 1, r1, r0);
+        }
+        if (t < n_tiles) body(t, r0, r1);
     }
 
     // ---- normalise and write: register c = 4j+i of o[db] is d = 32*db + 8j + 4*half + i ----
