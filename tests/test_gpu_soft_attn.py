@@ -84,6 +84,7 @@ CASES = [
     (4, [100, 0, 77], 2, 32, 1e-3, "ends"),  # packed sequences, an empty one, scores of exactly 0 and 1
     (5, [513], 1, 100, 1e-6, "ends"),        # window not a multiple of the tile, keys far outside it
     (6, [64, 128], 1, 1, 1e-6, "law"),       # window of one: only the token itself is unweighted
+    (9, [200], 1, 16, 0.0, "ends"),          # eps = 0: a score of exactly 0 removes the key outside the window
 ]
 
 
