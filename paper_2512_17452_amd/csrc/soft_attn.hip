@@ -16,9 +16,9 @@
 //
 // All products are v_mfma_f32_32x32x16_bf16 with fp32 accumulation; every operand that is
 // reused over the whole loop (the block's own rows) sits in registers, the streamed tiles
-// go through LDS in two forms: row-major (rows are the M side of a product over d) and
-// transposed (rows are d, for the products that contract over positions).  A lane of an
-// accumulator tile owns one column, so per-column quantities are plain scalars.
+// go through LDS row-major once: products over d read rows of the staged tile, products that
+// contract over positions read its columns with the transposing LDS load (ds_read_b64_tr_b16).
+// A lane of an accumulator tile owns one column, so per-column quantities are plain scalars.
 #include <algorithm>
 #include <climits>
 
@@ -36,7 +36,6 @@ constexpr int kSaQ = 64;        // query positions per block (forward, dQ)
 constexpr int kSaT = 32;        // positions per streamed tile
 constexpr int kSaKB = 128;      // keys per block (dK/dV)
 constexpr int kSaRm = 272;      // bytes per row of a row-major tile in LDS (256 + 16 pad)
-constexpr int kSaTr = 72;       // bytes per d row of a transposed tile (64 + 8 pad)
 
 struct SoftSeqs {
     int32_t n;
@@ -74,29 +73,27 @@ __device__ __forceinline__ void sa_bias(float gj, float eps, float &b_in, float 
 __device__ __forceinline__ void sa_put_rm(char *tile, int row, int dc, uint4 x) {
     *reinterpret_cast<uint4 *>(tile + row * kSaRm + dc * 16) = x;
 }
-// The same four elements (8 bytes) of rows 2p and 2p+1 go to the transposed tile as four 32-bit
-// words (row 2p in the low half): element e of the chunk is d = dc * 8 + sel * 4 + e.
-__device__ __forceinline__ void sa_put_tr(char *tile, int pair, int dc, int sel, uint2 r0, uint2 r1) {
-    const uint32_t a0[2] = {r0.x, r0.y}, a1[2] = {r1.x, r1.y};
-#pragma unroll
-    for (int e = 0; e < 4; e++) {
-        const uint32_t x0 = (e & 1) ? (a0[e >> 1] >> 16) : (a0[e >> 1] & 0xffffu);
-        const uint32_t x1 = (e & 1) ? (a1[e >> 1] & 0xffff0000u) : (a1[e >> 1] << 16);
-        *reinterpret_cast<uint32_t *>(tile + (dc * 8 + sel * 4 + e) * kSaTr + pair * 4) = x0 | x1;
-    }
-}
 // A operand of a product over d: row qn of a row-major tile, d slice ks.
 __device__ __forceinline__ sa_bf16x8_t sa_get_rm(const char *tile, int qn, int half, int ks) {
     return *reinterpret_cast<const sa_bf16x8_t *>(tile + qn * kSaRm + (ks * 16 + half * 8) * 2);
 }
-// A operand of a product over the 32 positions of a tile: d row db*32+qn of a transposed tile;
-// the lane's 8 contraction slots are positions 16*t2 + 4*half + {0..3} and + 8 more, which is
-// where the accumulator layout of the first product leaves this lane's values.
-__device__ __forceinline__ sa_bf16x8_t sa_get_tr(const char *tile, int qn, int half, int db, int t2) {
-    const char *p = tile + (db * 32 + qn) * kSaTr + (16 * t2 + 4 * half) * 2;
-    const uint2 v0 = *reinterpret_cast<const uint2 *>(p);
-    const uint2 v1 = *reinterpret_cast<const uint2 *>(p + 16);
-    const uint4 u4 = make_uint4(v0.x, v0.y, v1.x, v1.y);
+// A operand of a product that contracts over the rows of a row-major tile (rows are positions,
+// columns d): the output row of this lane is d = db*32 + qn, its 8 contraction slots are tile rows
+// r0 + 4*half + {0..3} and r0 + 8 + 4*half + {0..3}, which is where the accumulator layout of the
+// first product leaves this lane's values.  ds_read_b64_tr_b16 transposes inside groups of 16
+// lanes: lane i of a group receives element i%4 of the 8 bytes addressed by lanes i/4, 4 + i/4,
+// 8 + i/4 and 12 + i/4.  So lane s of a group addresses (row s/4 of the four, columns 4*(s%4)..+3 of
+// the group's 16) and ends up with the four rows at its own column.
+typedef short sa_s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ sa_bf16x8_t sa_get_cols(const char *tile, int lane, int db, int r0) {
+    const int half = lane >> 5;
+    const char *p = tile + (r0 + 4 * half + ((lane & 15) >> 2)) * kSaRm +
+                    (db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    typedef sa_s16x4_t __attribute__((address_space(3))) *lds_ptr_t;
+    const sa_s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
+    const sa_s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 8 * kSaRm));
+    const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+    const uint4 u4 = make_uint4(l2.x, l2.y, h2.x, h2.y);
     return __builtin_bit_cast(sa_bf16x8_t, u4);
 }
 
@@ -104,11 +101,10 @@ __device__ __forceinline__ sa_bf16x8_t sa_get_tr(const char *tile, int qn, int h
 // forward
 // ---------------------------------------------------------------------------------------------
 constexpr int kSaT2 = 64;   // keys per tile of the forward kernel
-constexpr int kSaTr2 = 136; // bytes per d row of its transposed V tile (128 + 8 pad)
 
 __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArgs a) {
     __shared__ __attribute__((aligned(16))) char s_k[2][kSaT2 * kSaRm];
-    __shared__ __attribute__((aligned(16))) char s_vt[2][kSaD * kSaTr2];
+    __shared__ __attribute__((aligned(16))) char s_v[2][kSaT2 * kSaRm];
     __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT2];
     __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT2];
 
@@ -139,52 +135,30 @@ __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArg
 #pragma unroll
         for (int c = 0; c < 16; c++) o[db][c] = 0.f;
 
-    // staging: a thread carries two pairs of keys (pair ld_pair and ld_pair + 16)
-    const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
+    // staging: thread -> (keys ld_key and ld_key + 32 of the tile, 16-byte chunk)
+    const int ld_key = threadIdx.x >> 4, ld_dc = threadIdx.x & 15;
     const int64_t v_delta = a.v - a.k;
-    uint4 kreg0, kreg1;
-    uint2 va0, va1, vb0, vb1;
+    uint4 kreg0, kreg1, vreg0, vreg1;
     float bin0, bout0, bin1, bout1;
     auto fetch = [&](int t) __attribute__((always_inline)) {
-        {
-            const int idx0 = t * kSaT2 + 2 * ld_pair;
-            const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hkv + h;
-            const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hkv + h;
-            const char *kp0 = a.k + row0 * (kSaD * 2), *kp1 = a.k + row1 * (kSaD * 2);
-            kreg0 = *reinterpret_cast<const uint4 *>((ld_sel ? kp1 : kp0) + ld_dc * 16);
-            va0 = *reinterpret_cast<const uint2 *>(kp0 + v_delta + ld_dc * 16 + ld_sel * 8);
-            va1 = *reinterpret_cast<const uint2 *>(kp1 + v_delta + ld_dc * 16 + ld_sel * 8);
-            sa_bias(a.g[ld_sel ? row1 : row0], a.eps, bin0, bout0);
-        }
-        {
-            const int idx0 = t * kSaT2 + 32 + 2 * ld_pair;
-            const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hkv + h;
-            const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hkv + h;
-            const char *kp0 = a.k + row0 * (kSaD * 2), *kp1 = a.k + row1 * (kSaD * 2);
-            kreg1 = *reinterpret_cast<const uint4 *>((ld_sel ? kp1 : kp0) + ld_dc * 16);
-            vb0 = *reinterpret_cast<const uint2 *>(kp0 + v_delta + ld_dc * 16 + ld_sel * 8);
-            vb1 = *reinterpret_cast<const uint2 *>(kp1 + v_delta + ld_dc * 16 + ld_sel * 8);
-            sa_bias(a.g[ld_sel ? row1 : row0], a.eps, bin1, bout1);
-        }
-    };
-    auto put_tr2 = [&](char *tile, int pair, uint2 r0, uint2 r1) __attribute__((always_inline)) {
-        const uint32_t a0[2] = {r0.x, r0.y}, a1[2] = {r1.x, r1.y};
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-            const uint32_t x0 = (e & 1) ? (a0[e >> 1] >> 16) : (a0[e >> 1] & 0xffffu);
-            const uint32_t x1 = (e & 1) ? (a1[e >> 1] & 0xffff0000u) : (a1[e >> 1] << 16);
-            *reinterpret_cast<uint32_t *>(tile + (ld_dc * 8 + ld_sel * 4 + e) * kSaTr2 + pair * 4) = x0 | x1;
-        }
+        const size_t row0 = (size_t)(base + min(t * kSaT2 + ld_key, T - 1)) * a.Hkv + h;
+        const size_t row1 = (size_t)(base + min(t * kSaT2 + 32 + ld_key, T - 1)) * a.Hkv + h;
+        const char *kp0 = a.k + row0 * (kSaD * 2) + ld_dc * 16, *kp1 = a.k + row1 * (kSaD * 2) + ld_dc * 16;
+        kreg0 = *reinterpret_cast<const uint4 *>(kp0);
+        kreg1 = *reinterpret_cast<const uint4 *>(kp1);
+        vreg0 = *reinterpret_cast<const uint4 *>(kp0 + v_delta);
+        vreg1 = *reinterpret_cast<const uint4 *>(kp1 + v_delta);
+        sa_bias(a.g[row0], a.eps, bin0, bout0);
+        sa_bias(a.g[row1], a.eps, bin1, bout1);
     };
     auto stage = [&](int buf) __attribute__((always_inline)) {
-        const int key0 = 2 * ld_pair + ld_sel;
-        sa_put_rm(s_k[buf], key0, ld_dc, kreg0);
-        sa_put_rm(s_k[buf], key0 + 32, ld_dc, kreg1);
-        put_tr2(s_vt[buf], ld_pair, va0, va1);
-        put_tr2(s_vt[buf], ld_pair + 16, vb0, vb1);
+        sa_put_rm(s_k[buf], ld_key, ld_dc, kreg0);
+        sa_put_rm(s_k[buf], ld_key + 32, ld_dc, kreg1);
+        sa_put_rm(s_v[buf], ld_key, ld_dc, vreg0);
+        sa_put_rm(s_v[buf], ld_key + 32, ld_dc, vreg1);
         if (ld_dc == 0) {
-            s_bin[buf][key0] = bin0; s_bout[buf][key0] = bout0;
-            s_bin[buf][key0 + 32] = bin1; s_bout[buf][key0 + 32] = bout1;
+            s_bin[buf][ld_key] = bin0; s_bout[buf][ld_key] = bout0;
+            s_bin[buf][ld_key + 32] = bin1; s_bout[buf][ld_key + 32] = bout1;
         }
     };
 
@@ -271,13 +245,8 @@ __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArg
             const uint4 p4 = make_uint4(pb[4 * t2], pb[4 * t2 + 1], pb[4 * t2 + 2], pb[4 * t2 + 3]);
             const sa_bf16x8_t pbv = __builtin_bit_cast(sa_bf16x8_t, p4);
 #pragma unroll
-            for (int db = 0; db < 4; db++) {
-                const char *vp = &s_vt[buf][(db * 32 + qn) * kSaTr2 + (16 * t2 + 4 * half) * 2];
-                const uint2 v0 = *reinterpret_cast<const uint2 *>(vp);
-                const uint2 v1 = *reinterpret_cast<const uint2 *>(vp + 16);
-                const uint4 u4 = make_uint4(v0.x, v0.y, v1.x, v1.y);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(sa_bf16x8_t, u4), pbv, o[db], 0, 0, 0);
-            }
+            for (int db = 0; db < 4; db++)
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols(s_v[buf], lane, db, 16 * t2), pbv, o[db], 0, 0, 0);
         }
         if (t + 1 < n_tiles) stage(buf ^ 1);
         __syncthreads();
@@ -325,7 +294,6 @@ __global__ __launch_bounds__(256) void soft_attn_rowdot_kernel(int64_t n_rows, c
 __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, SoftArgs a) {
     __shared__ __attribute__((aligned(16))) char s_k[2][kSaT * kSaRm];
     __shared__ __attribute__((aligned(16))) char s_v[2][kSaT * kSaRm];
-    __shared__ __attribute__((aligned(16))) char s_kt[2][kSaD * kSaTr];
     __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT];
     __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT];
 
@@ -359,28 +327,21 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
 #pragma unroll
         for (int c = 0; c < 16; c++) dq[db][c] = 0.f;
 
-    const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
-    const int ld_key = 2 * ld_pair + ld_sel;
+    const int ld_key = threadIdx.x >> 4, ld_dc = threadIdx.x & 15;  // thread -> (key of the tile, 16-byte chunk)
     const int64_t v_delta = a.v - a.k;
     // two sets of staging registers: a tile is requested two iterations before it is multiplied
-    struct StReg { uint4 kreg, vreg; uint2 kt0, kt1; float bin_reg, bout_reg; };
+    struct StReg { uint4 kreg, vreg; float bin_reg, bout_reg; };
     StReg r0, r1;
     auto fetch = [&](int t, StReg &r) __attribute__((always_inline)) {
-        const int idx0 = t * kSaT + 2 * ld_pair;
-        const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hkv + h;
-        const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hkv + h;
-        const char *kp0 = a.k + row0 * (kSaD * 2), *kp1 = a.k + row1 * (kSaD * 2);
-        const char *ks = ld_sel ? kp1 : kp0;
-        r.kreg = *reinterpret_cast<const uint4 *>(ks + ld_dc * 16);
-        r.vreg = *reinterpret_cast<const uint4 *>(ks + v_delta + ld_dc * 16);
-        r.kt0 = *reinterpret_cast<const uint2 *>(kp0 + ld_dc * 16 + ld_sel * 8);
-        r.kt1 = *reinterpret_cast<const uint2 *>(kp1 + ld_dc * 16 + ld_sel * 8);
-        sa_bias(a.g[ld_sel ? row1 : row0], a.eps, r.bin_reg, r.bout_reg);
+        const size_t row = (size_t)(base + min(t * kSaT + ld_key, T - 1)) * a.Hkv + h;
+        const char *kp = a.k + row * (kSaD * 2) + ld_dc * 16;
+        r.kreg = *reinterpret_cast<const uint4 *>(kp);
+        r.vreg = *reinterpret_cast<const uint4 *>(kp + v_delta);
+        sa_bias(a.g[row], a.eps, r.bin_reg, r.bout_reg);
     };
     auto stage = [&](int buf, const StReg &r) __attribute__((always_inline)) {
         sa_put_rm(s_k[buf], ld_key, ld_dc, r.kreg);
         sa_put_rm(s_v[buf], ld_key, ld_dc, r.vreg);
-        sa_put_tr(s_kt[buf], ld_pair, ld_dc, ld_sel, r.kt0, r.kt1);
         if (ld_dc == 0) { s_bin[buf][ld_key] = r.bin_reg; s_bout[buf][ld_key] = r.bout_reg; }
     };
 
@@ -430,7 +391,7 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
             const sa_bf16x8_t dsv = __builtin_bit_cast(sa_bf16x8_t, p4);
 #pragma unroll
             for (int db = 0; db < 4; db++)
-                dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_tr(s_kt[buf], qn, half, db, t2), dsv, dq[db], 0, 0, 0);
+                dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols(s_k[buf], lane, db, 16 * t2), dsv, dq[db], 0, 0, 0);
         }
         if (t + 1 < n_tiles) stage(buf ^ 1, rs);
         __syncthreads();
@@ -463,8 +424,6 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
 __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, SoftArgs a) {
     __shared__ __attribute__((aligned(16))) char s_q[2][kSaT * kSaRm];
     __shared__ __attribute__((aligned(16))) char s_do[2][kSaT * kSaRm];
-    __shared__ __attribute__((aligned(16))) char s_qt[2][kSaD * kSaTr];
-    __shared__ __attribute__((aligned(16))) char s_dot[2][kSaD * kSaTr];
     __shared__ __attribute__((aligned(16))) float s_lse[2][kSaT];
     __shared__ __attribute__((aligned(16))) float s_dd[2][kSaT];
     __shared__ float s_p[4][16][64];  // P of one (32 keys x 32 queries) tile, lane-private slots
@@ -501,35 +460,24 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
     // streamed tiles: 32 queries of one query head; iteration it = (query tile, head)
     const int qt_first = j0 / kSaT, n_qt = (T + kSaT - 1) / kSaT;
     const int n_it = (n_qt - qt_first) * kSaG;
-    const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
-    const int ld_row = 2 * ld_pair + ld_sel;
+    const int ld_row = threadIdx.x >> 4, ld_dc = threadIdx.x & 15;  // thread -> (row of the tile, 16-byte chunk)
     // two sets of staging registers: the loads of a tile are issued two iterations before the
     // tile is multiplied (one iteration is shorter than the latency of a load under this traffic)
-    struct StReg { uint4 qreg, doreg; uint2 qt0, qt1, dt0, dt1; float lse_reg, dd_reg; };
+    struct StReg { uint4 qreg, doreg; float lse_reg, dd_reg; };
     StReg r0, r1;
     auto fetch = [&](int it, StReg &r) __attribute__((always_inline)) {
         const int qt = qt_first + it / kSaG, hd = it % kSaG;
-        const int idx0 = qt * kSaT + 2 * ld_pair;
-        const size_t row0 = (size_t)(base + min(idx0, T - 1)) * a.Hq + (size_t)h * kSaG + hd;
-        const size_t row1 = (size_t)(base + min(idx0 + 1, T - 1)) * a.Hq + (size_t)h * kSaG + hd;
-        const char *qp0 = a.q + row0 * (kSaD * 2), *qp1 = a.q + row1 * (kSaD * 2);
-        const char *dp0 = a.dout + row0 * (kSaD * 2), *dp1 = a.dout + row1 * (kSaD * 2);
-        r.qreg = *reinterpret_cast<const uint4 *>((ld_sel ? qp1 : qp0) + ld_dc * 16);
-        r.doreg = *reinterpret_cast<const uint4 *>((ld_sel ? dp1 : dp0) + ld_dc * 16);
-        r.qt0 = *reinterpret_cast<const uint2 *>(qp0 + ld_dc * 16 + ld_sel * 8);
-        r.qt1 = *reinterpret_cast<const uint2 *>(qp1 + ld_dc * 16 + ld_sel * 8);
-        r.dt0 = *reinterpret_cast<const uint2 *>(dp0 + ld_dc * 16 + ld_sel * 8);
-        r.dt1 = *reinterpret_cast<const uint2 *>(dp1 + ld_dc * 16 + ld_sel * 8);
-        const bool real = idx0 + ld_sel < T;  // a row past the end gets weight exp2(-inf) = 0
-        const size_t rs = ld_sel ? row1 : row0;
-        r.lse_reg = real ? a.lse[rs] * 1.4426950408889634f : INFINITY;
-        r.dd_reg = real ? a.rowdot[rs] : 0.f;
+        const int idx = qt * kSaT + ld_row;
+        const size_t row = (size_t)(base + min(idx, T - 1)) * a.Hq + (size_t)h * kSaG + hd;
+        r.qreg = *reinterpret_cast<const uint4 *>(a.q + row * (kSaD * 2) + ld_dc * 16);
+        r.doreg = *reinterpret_cast<const uint4 *>(a.dout + row * (kSaD * 2) + ld_dc * 16);
+        const bool real = idx < T;  // a row past the end gets weight exp2(-inf) = 0
+        r.lse_reg = real ? a.lse[row] * 1.4426950408889634f : INFINITY;
+        r.dd_reg = real ? a.rowdot[row] : 0.f;
     };
     auto stage = [&](int buf, const StReg &r) __attribute__((always_inline)) {
         sa_put_rm(s_q[buf], ld_row, ld_dc, r.qreg);
         sa_put_rm(s_do[buf], ld_row, ld_dc, r.doreg);
-        sa_put_tr(s_qt[buf], ld_pair, ld_dc, ld_sel, r.qt0, r.qt1);
-        sa_put_tr(s_dot[buf], ld_pair, ld_dc, ld_sel, r.dt0, r.dt1);
         if (ld_dc == 0) { s_lse[buf][ld_row] = r.lse_reg; s_dd[buf][ld_row] = r.dd_reg; }
     };
 
@@ -594,15 +542,16 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
                 pk[2 * j + 1] = sa_pack(ds[2], ds[3]);
             }
         }
-        // second product: rows = d, columns = keys, contraction over the 32 queries
-        const char *tr = role == 0 ? s_dot[buf] : s_qt[buf];
+        // second product: rows = d, columns = keys, contraction over the 32 queries (the rows of
+        // the staged tile, read column-wise)
+        const char *tr = role == 0 ? s_do[buf] : s_q[buf];
 #pragma unroll
         for (int t2 = 0; t2 < 2; t2++) {
             const uint4 p4 = make_uint4(pk[4 * t2], pk[4 * t2 + 1], pk[4 * t2 + 2], pk[4 * t2 + 3]);
             const sa_bf16x8_t pv = __builtin_bit_cast(sa_bf16x8_t, p4);
 #pragma unroll
             for (int db = 0; db < 4; db++)
-                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_tr(tr, qn, half, db, t2), pv, acc[db], 0, 0, 0);
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols(tr, lane, db, 16 * t2), pv, acc[db], 0, 0, 0);
         }
         if (it + 1 < n_it) stage(buf ^ 1, rs);
         __syncthreads();
