@@ -12,7 +12,8 @@
 // One block owns 64 chunk positions of one (sequence, kv head); its eight waves are
 // (query head of the group) x (row block of 32 positions), so a K/V tile staged in LDS
 // feeds all of them and two waves share each SIMD.
-// Everything is computed transposed, S^T = K Q^T and O^T = V^T P^T with
+// K and V tiles are staged row-major; the V^T operand is read from the V tile with the
+// transposing LDS load.  Everything is computed transposed, S^T = K Q^T and O^T = V^T P^T with
 // v_mfma_f32_32x32x16_bf16: a lane then owns one query column, so the running max,
 // the denominator and the rescale factor are plain per-lane scalars, and the
 // probabilities leave the first product already in the operand layout of the second.
@@ -29,8 +30,10 @@ typedef __attribute__((ext_vector_type(16))) float pf_f32x16_t;
 constexpr int kPfD = 128;         // head_dim
 constexpr int kPfQ = 64;          // chunk positions per block (2 row blocks of 32)
 constexpr int kPfKT = 32;         // keys per tile
-constexpr int kPfKStride = 272;   // bytes per key row of the K tile in LDS (256 + 16 pad)
-constexpr int kPfVStride = 72;    // bytes per d row of the transposed V tile (64 + 8 pad)
+constexpr int kPfKStride = 272;   // bytes per key row of the K tile in LDS (256 + 16 pad): rows are read whole
+constexpr int kPfVStride = 320;   // bytes per key row of the V tile (256 + 64 pad): columns are read, four
+                                  // rows and 64 bytes of each at a time per half wave, which this stride
+                                  // spreads over all banks
 
 struct PrefillAttnArgs {
     int layer;
@@ -41,6 +44,24 @@ struct PrefillAttnArgs {
     float *out;
 };
 
+// A operand of O^T += V^T P^T from the row-major V tile: the output row of this lane is
+// d = db*32 + qn, its 8 contraction slots are keys r0 + 4*half + {0..3} and r0 + 8 + 4*half + {0..3}
+// of the tile.  ds_read_b64_tr_b16 transposes inside groups of 16 lanes: lane i of a group receives
+// element i%4 of the 8 bytes addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4, so lane s of a
+// group addresses (key s/4 of the four, columns 4*(s%4)..+3 of the group's 16).
+typedef short pf_s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ pf_bf16x8_t pf_get_cols(const char *tile, int lane, int db, int r0) {
+    const int half = lane >> 5;
+    const char *p = tile + (r0 + 4 * half + ((lane & 15) >> 2)) * kPfVStride +
+                    (db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    typedef pf_s16x4_t __attribute__((address_space(3))) *lds_ptr_t;
+    const pf_s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
+    const pf_s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 8 * kPfVStride));
+    const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+    const uint4 u4 = make_uint4(l2.x, l2.y, h2.x, h2.y);
+    return __builtin_bit_cast(pf_bf16x8_t, u4);
+}
+
 __device__ __forceinline__ uint32_t pf_pack(float lo, float hi) {
     pf_bf16x2_t t = {(__bf16)lo, (__bf16)hi};
     return __builtin_bit_cast(uint32_t, t);
@@ -48,7 +69,7 @@ __device__ __forceinline__ uint32_t pf_pack(float lo, float hi) {
 
 __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs cs, PrefillAttnArgs a) {
     __shared__ __attribute__((aligned(16))) char s_k[2][kPfKT * kPfKStride];
-    __shared__ __attribute__((aligned(16))) char s_vt[2][kPfD * kPfVStride];
+    __shared__ __attribute__((aligned(16))) char s_v[2][kPfKT * kPfVStride];
     __shared__ __attribute__((aligned(16))) int s_lo[2][kPfKT];
     __shared__ __attribute__((aligned(16))) int s_hi[2][kPfKT];
 
@@ -87,16 +108,12 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
 #pragma unroll
         for (int c = 0; c < 16; c++) o[db][c] = 0.f;
 
-    // ---- staging of a key tile: thread -> (pair of keys 2j, 2j+1; 16-byte d chunk) ----
-    // the two V rows of a pair are interleaved element-wise so that the transposed tile is
-    // written with 32-bit stores
-    const int ld_pair = threadIdx.x >> 5, ld_dc = threadIdx.x & 15, ld_sel = (threadIdx.x >> 4) & 1;
-    // threads with ld_sel = 0 carry the K chunk of key 2j and the V chunks of both keys' low
-    // half (d chunk ld_dc, elements 0..3); ld_sel = 1: K of key 2j+1 and elements 4..7
-    const int ld_key = 2 * ld_pair + ld_sel;
+    // ---- staging of a key tile: thread -> (key of the tile, 16-byte d chunk), K and V row-major ----
+    const int ld_key = threadIdx.x >> 4, ld_dc = threadIdx.x & 15;
     // two sets of staging registers: a tile is requested two iterations before it is multiplied
-    struct StReg { uint4 kreg; uint2 vreg0, vreg1; int lo_reg, hi_reg; };
-    StReg r0, r1;
+    // (plain variables passed one by one: a struct of them ends up in scratch memory)
+    uint4 k0r, v0r, k1r, v1r;
+    int lo0r, hi0r, lo1r, hi1r;
     // Page ids live in registers, one per lane, so that the address of a key row never
     // waits for a page-table load: 64 consecutive entries of the global table (reloaded
     // every 64 pages) and the whole local table when it has at most 64 entries.
@@ -106,104 +123,84 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
     const int lpreg = (lp_in_reg && lane < pv.nlp) ? pv.local_pt[(size_t)um * pv.nlp + lane] : 0;
     const int slot0 = t0 > pv.W ? t0 % pv.W : 0;  // ring slot of the oldest position
     const int64_t v_delta_chunk = a.v - a.k;
-    auto fetch = [&](int t, StReg &r) __attribute__((always_inline)) {
-        const char *kp[2];
+    auto fetch = [&](int t, uint4 &r_k, uint4 &r_v, int &r_lo, int &r_hi) __attribute__((always_inline)) {
+        const char *kp;
         int64_t v_delta;
-        int lo[2] = {INT_MAX, INT_MAX}, hi[2] = {INT_MAX, INT_MAX};  // invisible unless shown otherwise
+        int lo = INT_MAX, hi = INT_MAX;  // invisible unless shown otherwise
         if (t < n_g) {  // global cache: visible to every query
             if (((t * kPfKT + kPfKT - 1) >> pv.logP) >= pt_base + 64) {
                 pt_base = (t * kPfKT) >> pv.logP;
                 ptreg = (pt_base + lane < pv.maxgp) ? pv.global_pt[(size_t)um * pv.maxgp + pt_base + lane] : 0;
             }
-#pragma unroll
-            for (int e = 0; e < 2; e++) {
-                const int idx = t * kPfKT + 2 * ld_pair + e, idc = min(idx, gl - 1);
-                const int pg = __shfl(ptreg, (idc >> pv.logP) - pt_base);
-                kp[e] = page_ptr(pv, pg) + (size_t)(idc & (pv.P - 1)) * (kPfD * 2);
-                if (idx < gl) lo[e] = INT_MIN;
-            }
+            const int idx = t * kPfKT + ld_key, idc = min(idx, gl - 1);
+            const int pg = __shfl(ptreg, (idc >> pv.logP) - pt_base);
+            kp = page_ptr(pv, pg) + (size_t)(idc & (pv.P - 1)) * (kPfD * 2);
+            if (idx < gl) lo = INT_MIN;
             v_delta = pv.v_off;
         } else if (t < n_g + n_r) {  // ring, oldest position first
-#pragma unroll
-            for (int e = 0; e < 2; e++) {
-                const int idx = (t - n_g) * kPfKT + 2 * ld_pair + e, idc = min(idx, w_eff - 1);
-                int slot = slot0 + idc;
-                slot = slot >= pv.W ? slot - pv.W : slot;
-                const int pos = t0 - w_eff + idc;
-                const int pg = lp_in_reg ? __shfl(lpreg, slot >> pv.logP)
-                                         : pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)];
-                kp[e] = page_ptr(pv, pg) + (size_t)(slot & (pv.P - 1)) * (kPfD * 2);
-                if (idx < w_eff) {
-                    lo[e] = pos;
-                    hi[e] = (pv.ring_g[(size_t)um * pv.W + slot] >= a.tau) ? INT_MAX : pos + pv.W - 1;
-                }
+            const int idx = (t - n_g) * kPfKT + ld_key, idc = min(idx, w_eff - 1);
+            int slot = slot0 + idc;
+            slot = slot >= pv.W ? slot - pv.W : slot;
+            const int pos = t0 - w_eff + idc;
+            const int pg = lp_in_reg ? __shfl(lpreg, slot >> pv.logP)
+                                     : pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)];
+            kp = page_ptr(pv, pg) + (size_t)(slot & (pv.P - 1)) * (kPfD * 2);
+            if (idx < w_eff) {
+                lo = pos;
+                hi = (pv.ring_g[(size_t)um * pv.W + slot] >= a.tau) ? INT_MAX : pos + pv.W - 1;
             }
             v_delta = pv.v_off;
         } else {  // this chunk
-#pragma unroll
-            for (int e = 0; e < 2; e++) {
-                const int idx = (t - n_g - n_r) * kPfKT + 2 * ld_pair + e, idc = min(idx, T - 1);
-                const size_t row = (size_t)(base + idc) * pv.Hkv + h;
-                kp[e] = a.k + row * (kPfD * 2);
-                if (idx < T) {
-                    lo[e] = t0 + idx;
-                    hi[e] = (a.g[row] >= a.tau) ? INT_MAX : t0 + idx + pv.W - 1;
-                }
+            const int idx = (t - n_g - n_r) * kPfKT + ld_key, idc = min(idx, T - 1);
+            const size_t row = (size_t)(base + idc) * pv.Hkv + h;
+            kp = a.k + row * (kPfD * 2);
+            if (idx < T) {
+                lo = t0 + idx;
+                hi = (a.g[row] >= a.tau) ? INT_MAX : t0 + idx + pv.W - 1;
             }
             v_delta = v_delta_chunk;
         }
-        r.kreg = *reinterpret_cast<const uint4 *>((ld_sel ? kp[1] : kp[0]) + ld_dc * 16);
-        // V: the same 8-byte half chunk of both keys of the pair
-        r.vreg0 = *reinterpret_cast<const uint2 *>(kp[0] + v_delta + ld_dc * 16 + ld_sel * 8);
-        r.vreg1 = *reinterpret_cast<const uint2 *>(kp[1] + v_delta + ld_dc * 16 + ld_sel * 8);
-        r.lo_reg = ld_sel ? lo[1] : lo[0];
-        r.hi_reg = ld_sel ? hi[1] : hi[0];
+        r_k = *reinterpret_cast<const uint4 *>(kp + ld_dc * 16);
+        r_v = *reinterpret_cast<const uint4 *>(kp + v_delta + ld_dc * 16);
+        r_lo = lo;
+        r_hi = hi;
     };
     // Full tiles of the global cache, pages of at least 4 tokens: the four keys a wave
     // stages share a page, so the page base is scalar and a lane only adds a fixed offset.
     const bool lean_ok = pv.P >= 4;
-    const uint32_t lean_row = (uint32_t)((2 * ld_pair) & (pv.P - 1));
-    const uint32_t lean_k_off = (lean_row + ld_sel) * (kPfD * 2) + ld_dc * 16;
-    const uint32_t lean_v_off = lean_row * (kPfD * 2) + pv.v_off + ld_dc * 16 + ld_sel * 8;
-    auto fetch_lean = [&](int t, StReg &r) __attribute__((always_inline)) {
+    const uint32_t lean_k_off = (uint32_t)(ld_key & (pv.P - 1)) * (kPfD * 2) + ld_dc * 16;
+    auto fetch_lean = [&](int t, uint4 &r_k, uint4 &r_v, int &r_lo, int &r_hi) __attribute__((always_inline)) {
         if (((t * kPfKT + kPfKT - 1) >> pv.logP) >= pt_base + 64) {
             pt_base = (t * kPfKT) >> pv.logP;
             ptreg = (pt_base + lane < pv.maxgp) ? pv.global_pt[(size_t)um * pv.maxgp + pt_base + lane] : 0;
         }
         const int pg = __builtin_amdgcn_readlane(ptreg, ((t * kPfKT + 4 * wave) >> pv.logP) - pt_base);
+        // inside its page the tile begins at row (32 t) mod P (0 unless a page holds several tiles)
         const char *sb = page_ptr(pv, pg) + (size_t)((t * kPfKT) & (pv.P - 1)) * (kPfD * 2);
-        r.kreg = *reinterpret_cast<const uint4 *>(sb + lean_k_off);
-        r.vreg0 = *reinterpret_cast<const uint2 *>(sb + lean_v_off);
-        r.vreg1 = *reinterpret_cast<const uint2 *>(sb + lean_v_off + kPfD * 2);
-        r.lo_reg = INT_MIN;
-        r.hi_reg = INT_MAX;
+        r_k = *reinterpret_cast<const uint4 *>(sb + lean_k_off);
+        r_v = *reinterpret_cast<const uint4 *>(sb + lean_k_off + pv.v_off);
+        r_lo = INT_MIN;
+        r_hi = INT_MAX;
     };
-    auto stage = [&](int buf, const StReg &r) __attribute__((always_inline)) {
-        *reinterpret_cast<uint4 *>(&s_k[buf][ld_key * kPfKStride + ld_dc * 16]) = r.kreg;
-        // transposed V: row d, columns (key 2j, key 2j+1) as one 32-bit word
-        const uint32_t a0[2] = {r.vreg0.x, r.vreg0.y}, a1[2] = {r.vreg1.x, r.vreg1.y};
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-            const uint32_t x0 = (e & 1) ? (a0[e >> 1] >> 16) : (a0[e >> 1] & 0xffffu);
-            const uint32_t x1 = (e & 1) ? (a1[e >> 1] & 0xffff0000u) : (a1[e >> 1] << 16);
-            const int dd = ld_dc * 8 + ld_sel * 4 + e;
-            *reinterpret_cast<uint32_t *>(&s_vt[buf][dd * kPfVStride + ld_pair * 4]) = x0 | x1;
-        }
-        if (ld_dc == 0) { s_lo[buf][ld_key] = r.lo_reg; s_hi[buf][ld_key] = r.hi_reg; }
+    auto stage = [&](int buf, const uint4 &r_k, const uint4 &r_v, int r_lo, int r_hi) __attribute__((always_inline)) {
+        *reinterpret_cast<uint4 *>(&s_k[buf][ld_key * kPfKStride + ld_dc * 16]) = r_k;
+        *reinterpret_cast<uint4 *>(&s_v[buf][ld_key * kPfVStride + ld_dc * 16]) = r_v;
+        if (ld_dc == 0) { s_lo[buf][ld_key] = r_lo; s_hi[buf][ld_key] = r_hi; }
     };
 
     const int n_plain = gl / kPfKT;  // full tiles of the global cache: no mask
-    auto fetch_any = [&](int t, StReg &r) __attribute__((always_inline)) {
-        if (lean_ok && t < n_plain) fetch_lean(t, r);
-        else fetch(t, r);
+    auto fetch_any = [&](int t, uint4 &r_k, uint4 &r_v, int &r_lo, int &r_hi) __attribute__((always_inline)) {
+        if (lean_ok && t < n_plain) fetch_lean(t, r_k, r_v, r_lo, r_hi);
+        else fetch(t, r_k, r_v, r_lo, r_hi);
     };
-    fetch_any(0, r0);
-    stage(0, r0);
-    if (n_tiles > 1) fetch_any(1, r1);
+    fetch_any(0, k0r, v0r, lo0r, hi0r);
+    stage(0, k0r, v0r, lo0r, hi0r);
+    if (n_tiles > 1) fetch_any(1, k1r, v1r, lo1r, hi1r);
     __syncthreads();
 
     // one iteration: tile t is multiplied, tile t+2 is requested into rf, tile t+1 goes from rs to LDS
-    auto body = [&](int t, StReg &rf, const StReg &rs) __attribute__((always_inline)) {
+    auto body = [&](int t, uint4 &f_k, uint4 &f_v, int &f_lo, int &f_hi, const uint4 &s_kk, const uint4 &s_vv,
+                    const int &s_lo_, const int &s_hi_) __attribute__((always_inline)) {
         const int buf = t & 1;
         // LDS latency is the scarce thing here: the eight K fragments are requested at once,
         // the address arithmetic and global loads of the next tile run while they arrive,
@@ -213,7 +210,7 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
         for (int ks = 0; ks < 8; ks++)
             ka[ks] = *reinterpret_cast<const pf_bf16x8_t *>(&s_k[buf][qn * kPfKStride + (ks * 16 + half * 8) * 2]);
         __builtin_amdgcn_sched_barrier(0);
-        if (t + 2 < n_tiles) fetch_any(t + 2, rf);  // in flight while this tile and the next are multiplied
+        if (t + 2 < n_tiles) fetch_any(t + 2, f_k, f_v, f_lo, f_hi);  // in flight while this tile and the next are multiplied
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- S^T = K Q^T : rows = keys of the tile, columns = this wave's queries ----
@@ -222,18 +219,12 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
         for (int c = 0; c < 16; c++) s[c] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qv[ks], s, 0, 0, 0);
-        // the lane's 8 contraction slots of V^T are keys 16*t2 + 4*half + {0..3} and + 8 more
+        // V^T fragments read column-wise from the row-major V tile
         pf_bf16x8_t va[2][4];
 #pragma unroll
         for (int t2 = 0; t2 < 2; t2++)
 #pragma unroll
-            for (int db = 0; db < 4; db++) {
-                const char *vp = &s_vt[buf][(db * 32 + qn) * kPfVStride + (16 * t2 + 4 * half) * 2];
-                const uint2 v0 = *reinterpret_cast<const uint2 *>(vp);
-                const uint2 v1 = *reinterpret_cast<const uint2 *>(vp + 16);
-                const uint4 u4 = make_uint4(v0.x, v0.y, v1.x, v1.y);
-                va[t2][db] = __builtin_bit_cast(pf_bf16x8_t, u4);
-            }
+            for (int db = 0; db < 4; db++) va[t2][db] = pf_get_cols(s_v[buf], lane, db, 16 * t2);
         __builtin_amdgcn_sched_barrier(0);
         // register c = 4j+i of a lane holds key 8j + 4*half + i of the tile
         const bool plain = t < n_plain;
@@ -290,16 +281,16 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
             for (int db = 0; db < 4; db++)
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t2][db], pbv, o[db], 0, 0, 0);
         }
-        if (t + 1 < n_tiles) stage(buf ^ 1, rs);
+        if (t + 1 < n_tiles) stage(buf ^ 1, s_kk, s_vv, s_lo_, s_hi_);
         __syncthreads();
     };
     {
         int t = 0;
         for (; t + 1 < n_tiles; t += 2) {
-            body(t, r0, r1);
-            body(t + 1, r1, r0);
+            body(t, k0r, v0r, lo0r, hi0r, k1r, v1r, lo1r, hi1r);
+            body(t + 1, k1r, v1r, lo1r, hi1r, k0r, v0r, lo0r, hi0r);
         }
-        if (t < n_tiles) body(t, r0, r1);
+        if (t < n_tiles) body(t, k0r, v0r, lo0r, hi0r, k1r, v1r, lo1r, hi1r);
     }
 
     // ---- normalise and write: register c = 4j+i of o[db] is d = 32*db + 8j + 4*half + i ----
