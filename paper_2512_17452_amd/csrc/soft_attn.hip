@@ -35,7 +35,9 @@ constexpr int kSaG = 4;         // query heads per kv head
 constexpr int kSaQ = 64;        // query positions per block (forward, dQ)
 constexpr int kSaT = 32;        // positions per streamed tile
 constexpr int kSaKB = 128;      // keys per block (dK/dV)
-constexpr int kSaRm = 272;      // bytes per row of a row-major tile in LDS (256 + 16 pad)
+constexpr int kSaRm = 272;      // bytes per row of a tile in LDS whose rows are read whole (256 + 16 pad)
+constexpr int kSaCm = 320;      // bytes per row of a tile that is only read column-wise (256 + 64 pad): four
+                                // rows and 64 bytes of each per half wave, spread over all banks
 
 struct SoftSeqs {
     int32_t n;
@@ -85,13 +87,14 @@ __device__ __forceinline__ sa_bf16x8_t sa_get_rm(const char *tile, int qn, int h
 // 8 + i/4 and 12 + i/4.  So lane s of a group addresses (row s/4 of the four, columns 4*(s%4)..+3 of
 // the group's 16) and ends up with the four rows at its own column.
 typedef short sa_s16x4_t __attribute__((ext_vector_type(4)));
+template <int STRIDE = kSaRm>
 __device__ __forceinline__ sa_bf16x8_t sa_get_cols(const char *tile, int lane, int db, int r0) {
     const int half = lane >> 5;
-    const char *p = tile + (r0 + 4 * half + ((lane & 15) >> 2)) * kSaRm +
+    const char *p = tile + (r0 + 4 * half + ((lane & 15) >> 2)) * STRIDE +
                     (db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
     typedef sa_s16x4_t __attribute__((address_space(3))) *lds_ptr_t;
     const sa_s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
-    const sa_s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 8 * kSaRm));
+    const sa_s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 8 * STRIDE));
     const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
     const uint4 u4 = make_uint4(l2.x, l2.y, h2.x, h2.y);
     return __builtin_bit_cast(sa_bf16x8_t, u4);
@@ -104,7 +107,7 @@ constexpr int kSaT2 = 64;   // keys per tile of the forward kernel
 
 __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArgs a) {
     __shared__ __attribute__((aligned(16))) char s_k[2][kSaT2 * kSaRm];
-    __shared__ __attribute__((aligned(16))) char s_v[2][kSaT2 * kSaRm];
+    __shared__ __attribute__((aligned(16))) char s_v[2][kSaT2 * kSaCm];
     __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT2];
     __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT2];
 
@@ -154,8 +157,8 @@ __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArg
     auto stage = [&](int buf) __attribute__((always_inline)) {
         sa_put_rm(s_k[buf], ld_key, ld_dc, kreg0);
         sa_put_rm(s_k[buf], ld_key + 32, ld_dc, kreg1);
-        sa_put_rm(s_v[buf], ld_key, ld_dc, vreg0);
-        sa_put_rm(s_v[buf], ld_key + 32, ld_dc, vreg1);
+        *reinterpret_cast<uint4 *>(&s_v[buf][ld_key * kSaCm + ld_dc * 16]) = vreg0;
+        *reinterpret_cast<uint4 *>(&s_v[buf][(ld_key + 32) * kSaCm + ld_dc * 16]) = vreg1;
         if (ld_dc == 0) {
             s_bin[buf][ld_key] = bin0; s_bout[buf][ld_key] = bout0;
             s_bin[buf][ld_key + 32] = bin1; s_bout[buf][ld_key + 32] = bout1;
@@ -246,7 +249,7 @@ __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArg
             const sa_bf16x8_t pbv = __builtin_bit_cast(sa_bf16x8_t, p4);
 #pragma unroll
             for (int db = 0; db < 4; db++)
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols(s_v[buf], lane, db, 16 * t2), pbv, o[db], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols<kSaCm>(s_v[buf], lane, db, 16 * t2), pbv, o[db], 0, 0, 0);
         }
         if (t + 1 < n_tiles) stage(buf ^ 1);
         __syncthreads();
@@ -293,6 +296,7 @@ __global__ __launch_bounds__(256) void soft_attn_rowdot_kernel(int64_t n_rows, c
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, SoftArgs a) {
     __shared__ __attribute__((aligned(16))) char s_k[2][kSaT * kSaRm];
+    __shared__ __attribute__((aligned(16))) char s_kc[2][kSaT * kSaCm];  // the same tile at the stride of column reads
     __shared__ __attribute__((aligned(16))) char s_v[2][kSaT * kSaRm];
     __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT];
     __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT];
@@ -341,6 +345,7 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
     };
     auto stage = [&](int buf, const StReg &r) __attribute__((always_inline)) {
         sa_put_rm(s_k[buf], ld_key, ld_dc, r.kreg);
+        *reinterpret_cast<uint4 *>(&s_kc[buf][ld_key * kSaCm + ld_dc * 16]) = r.kreg;
         sa_put_rm(s_v[buf], ld_key, ld_dc, r.vreg);
         if (ld_dc == 0) { s_bin[buf][ld_key] = r.bin_reg; s_bout[buf][ld_key] = r.bout_reg; }
     };
@@ -391,7 +396,7 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
             const sa_bf16x8_t dsv = __builtin_bit_cast(sa_bf16x8_t, p4);
 #pragma unroll
             for (int db = 0; db < 4; db++)
-                dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols(s_k[buf], lane, db, 16 * t2), dsv, dq[db], 0, 0, 0);
+                dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols<kSaCm>(s_kc[buf], lane, db, 16 * t2), dsv, dq[db], 0, 0, 0);
         }
         if (t + 1 < n_tiles) stage(buf ^ 1, rs);
         __syncthreads();
@@ -424,6 +429,8 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
 __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, SoftArgs a) {
     __shared__ __attribute__((aligned(16))) char s_q[2][kSaT * kSaRm];
     __shared__ __attribute__((aligned(16))) char s_do[2][kSaT * kSaRm];
+    __shared__ __attribute__((aligned(16))) char s_qc[2][kSaT * kSaCm];   // the same tiles at the stride of column reads
+    __shared__ __attribute__((aligned(16))) char s_doc[2][kSaT * kSaCm];
     __shared__ __attribute__((aligned(16))) float s_lse[2][kSaT];
     __shared__ __attribute__((aligned(16))) float s_dd[2][kSaT];
     __shared__ float s_p[4][16][64];  // P of one (32 keys x 32 queries) tile, lane-private slots
@@ -478,6 +485,8 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
     auto stage = [&](int buf, const StReg &r) __attribute__((always_inline)) {
         sa_put_rm(s_q[buf], ld_row, ld_dc, r.qreg);
         sa_put_rm(s_do[buf], ld_row, ld_dc, r.doreg);
+        *reinterpret_cast<uint4 *>(&s_qc[buf][ld_row * kSaCm + ld_dc * 16]) = r.qreg;
+        *reinterpret_cast<uint4 *>(&s_doc[buf][ld_row * kSaCm + ld_dc * 16]) = r.doreg;
         if (ld_dc == 0) { s_lse[buf][ld_row] = r.lse_reg; s_dd[buf][ld_row] = r.dd_reg; }
     };
 
@@ -544,14 +553,14 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
         }
         // second product: rows = d, columns = keys, contraction over the 32 queries (the rows of
         // the staged tile, read column-wise)
-        const char *tr = role == 0 ? s_do[buf] : s_q[buf];
+        const char *tr = role == 0 ? s_doc[buf] : s_qc[buf];
 #pragma unroll
         for (int t2 = 0; t2 < 2; t2++) {
             const uint4 p4 = make_uint4(pk[4 * t2], pk[4 * t2 + 1], pk[4 * t2 + 2], pk[4 * t2 + 3]);
             const sa_bf16x8_t pv = __builtin_bit_cast(sa_bf16x8_t, p4);
 #pragma unroll
             for (int db = 0; db < 4; db++)
-                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols(tr, lane, db, 16 * t2), pv, acc[db], 0, 0, 0);
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols<kSaCm>(tr, lane, db, 16 * t2), pv, acc[db], 0, 0, 0);
         }
         if (it + 1 < n_it) stage(buf ^ 1, rs);
         __syncthreads();
