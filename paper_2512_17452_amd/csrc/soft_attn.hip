@@ -10,8 +10,8 @@
 //   soft_attn_bwd_dq_kernel    same blocking as the forward: S^T and dP^T = V dO^T per key tile,
 //                              dS^T = P^T (dP^T - D), dQ^T += K^T dS^T
 //   soft_attn_bwd_dkv_kernel   block = 128 keys of a kv head; its waves are (32 keys) x (role):
-//                              role 0 recomputes S = Q K^T and P and accumulates dV^T += dO^T P,
-//                              role 1 computes dP = dO V^T, takes P through LDS, forms dS and
+//                              role 0 recomputes S = Q K^T and P and accumulates dV^T += dO^T P;
+//                              role 1, one tile behind, computes dP = dO V^T, takes P through LDS, forms dS and
 //                              accumulates dK^T += Q^T dS and the sum that becomes dg
 //
 // All products are v_mfma_f32_32x32x16_bf16 with fp32 accumulation; every operand that is
@@ -427,13 +427,17 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
 // backward, dK / dV / dg: columns of every tile are this wave's 32 keys
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, SoftArgs a) {
-    __shared__ __attribute__((aligned(16))) char s_q[2][kSaT * kSaRm];
-    __shared__ __attribute__((aligned(16))) char s_do[2][kSaT * kSaRm];
-    __shared__ __attribute__((aligned(16))) char s_qc[2][kSaT * kSaCm];   // the same tiles at the stride of column reads
-    __shared__ __attribute__((aligned(16))) char s_doc[2][kSaT * kSaCm];
+    // Role 0 works on tile `it` while role 1 works on tile it-1 (it gets P of that tile from role 0
+    // through LDS, written one iteration earlier): one barrier per iteration, and the two waves of
+    // a SIMD never wait for each other inside one.  What role 0 reads needs two buffers (in use,
+    // being staged), what role 1 reads needs three (in use, waiting, being staged).
+    __shared__ __attribute__((aligned(16))) char s_q[2][kSaT * kSaRm];     // role 0: rows (S = Q K^T)
+    __shared__ __attribute__((aligned(16))) char s_doc[2][kSaT * kSaCm];   // role 0: columns (dV^T += dO^T P)
+    __shared__ __attribute__((aligned(16))) char s_do[3][kSaT * kSaRm];    // role 1: rows (dP = dO V^T)
+    __shared__ __attribute__((aligned(16))) char s_qc[3][kSaT * kSaCm];    // role 1: columns (dK^T += Q^T dS)
     __shared__ __attribute__((aligned(16))) float s_lse[2][kSaT];
-    __shared__ __attribute__((aligned(16))) float s_dd[2][kSaT];
-    __shared__ float s_p[4][16][64];  // P of one (32 keys x 32 queries) tile, lane-private slots
+    __shared__ __attribute__((aligned(16))) float s_dd[3][kSaT];
+    __shared__ float s_p[2][4][16][64];  // P of a (32 keys x 32 queries) tile per key sub-tile, lane-private slots
 
     const int b = blockIdx.z, h = blockIdx.y, kbk = blockIdx.x;  // early key blocks have the most queries: first
     const int T = cs.ntok[b], base = cs.base[b];
@@ -482,92 +486,98 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
         r.lse_reg = real ? a.lse[row] * 1.4426950408889634f : INFINITY;
         r.dd_reg = real ? a.rowdot[row] : 0.f;
     };
-    auto stage = [&](int buf, const StReg &r) __attribute__((always_inline)) {
-        sa_put_rm(s_q[buf], ld_row, ld_dc, r.qreg);
-        sa_put_rm(s_do[buf], ld_row, ld_dc, r.doreg);
-        *reinterpret_cast<uint4 *>(&s_qc[buf][ld_row * kSaCm + ld_dc * 16]) = r.qreg;
-        *reinterpret_cast<uint4 *>(&s_doc[buf][ld_row * kSaCm + ld_dc * 16]) = r.doreg;
-        if (ld_dc == 0) { s_lse[buf][ld_row] = r.lse_reg; s_dd[buf][ld_row] = r.dd_reg; }
+    auto stage = [&](int b2, int b3, const StReg &r) __attribute__((always_inline)) {
+        sa_put_rm(s_q[b2], ld_row, ld_dc, r.qreg);
+        sa_put_rm(s_do[b3], ld_row, ld_dc, r.doreg);
+        *reinterpret_cast<uint4 *>(&s_qc[b3][ld_row * kSaCm + ld_dc * 16]) = r.qreg;
+        *reinterpret_cast<uint4 *>(&s_doc[b2][ld_row * kSaCm + ld_dc * 16]) = r.doreg;
+        if (ld_dc == 0) { s_lse[b2][ld_row] = r.lse_reg; s_dd[b3][ld_row] = r.dd_reg; }
     };
 
     fetch(0, r0);
-    stage(0, r0);
+    stage(0, 0, r0);
     fetch(1, r1);  // n_it >= 4
     __syncthreads();
-    // one iteration: tile `it` is multiplied, tile it+2 is requested into rf, tile it+1 goes from rs to LDS
+    int b3 = 0;  // it % 3
+    // one iteration: role 0 multiplies tile `it`, role 1 tile it-1; tile it+2 is requested into rf,
+    // tile it+1 goes from rs to LDS
     auto body = [&](int it, StReg &rf, const StReg &rs) __attribute__((always_inline)) {
-        const int buf = it & 1;
-        const int i0 = (qt_first + it / kSaG) * kSaT;  // first query of the tile
+        const int b3p = b3 == 0 ? 2 : b3 - 1, b3n = b3 == 2 ? 0 : b3 + 1;
+        const int mine = role == 0 ? it : it - 1;               // the tile this wave multiplies
+        const bool active = role == 0 ? it < n_it : it >= 1;    // wave-uniform
+        const int i0 = (qt_first + mine / kSaG) * kSaT;         // first query of that tile
         // first product: rows = queries of the tile, columns = this wave's keys
-        const char *rm = role == 0 ? s_q[buf] : s_do[buf];
+        const char *rm = role == 0 ? s_q[it & 1] : s_do[b3p];
         sa_bf16x8_t fa[8];
+        if (active) {
 #pragma unroll
-        for (int ks = 0; ks < 8; ks++) fa[ks] = sa_get_rm(rm, qn, half, ks);
+            for (int ks = 0; ks < 8; ks++) fa[ks] = sa_get_rm(rm, qn, half, ks);
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (it + 2 < n_it) fetch(it + 2, rf);
         __builtin_amdgcn_sched_barrier(0);
-        sa_f32x16_t x;
+        if (active) {
+            sa_f32x16_t x;
 #pragma unroll
-        for (int c = 0; c < 16; c++) x[c] = 0.f;
+            for (int c = 0; c < 16; c++) x[c] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ks++) x = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], own[ks], x, 0, 0, 0);
-        // register c = 4j+i of a lane holds query i0 + 8j + 4*half + i
-        if (role == 0) {
-            // P = exp2(S * scale + bias - lse); to the partner wave through LDS
+            for (int ks = 0; ks < 8; ks++) x = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], own[ks], x, 0, 0, 0);
+            // register c = 4j+i of a lane holds query i0 + 8j + 4*half + i
+            uint32_t pk[8];
+            if (role == 0) {
+                // P = exp2(S * scale + bias - lse); a copy goes to the partner wave through LDS
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const float4 l4 = *reinterpret_cast<const float4 *>(&s_lse[buf][8 * j + 4 * half]);
-                const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
+                for (int j = 0; j < 4; j++) {
+                    const float4 l4 = *reinterpret_cast<const float4 *>(&s_lse[it & 1][8 * j + 4 * half]);
+                    const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    const int ig = i0 + 8 * j + 4 * half + i;
-                    const float bias = (ig - jg < a.W) ? b_in : b_out;
-                    const float e = (jg <= ig) ? fmaf(x[4 * j + i], a.scale_log2e, bias) - ls[i] : -INFINITY;
-                    x[4 * j + i] = __builtin_amdgcn_exp2f(e);
-                    s_p[kb][4 * j + i][lane] = x[4 * j + i];
+                    for (int i = 0; i < 4; i++) {
+                        const int ig = i0 + 8 * j + 4 * half + i;
+                        const float bias = (ig - jg < a.W) ? b_in : b_out;
+                        const float e = (jg <= ig) ? fmaf(x[4 * j + i], a.scale_log2e, bias) - ls[i] : -INFINITY;
+                        x[4 * j + i] = __builtin_amdgcn_exp2f(e);
+                        s_p[it & 1][kb][4 * j + i][lane] = x[4 * j + i];
+                    }
+                }
+#pragma unroll
+                for (int c = 0; c < 8; c++) pk[c] = sa_pack(x[2 * c], x[2 * c + 1]);
+            } else {
+                // dS = P (dP - D_i); the part of it where m_ij follows g_j adds up to dg_j (g_j + eps)
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    const float4 d4 = *reinterpret_cast<const float4 *>(&s_dd[b3p][8 * j + 4 * half]);
+                    const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
+                    float ds[4];
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        const int ig = i0 + 8 * j + 4 * half + i;
+                        ds[i] = s_p[mine & 1][kb][4 * j + i][lane] * (x[4 * j + i] - dd[i]);
+                        const bool follows = (ig - jg < a.W) ? follows_in : follows_out;
+                        dg_acc += follows ? ds[i] : 0.f;
+                    }
+                    pk[2 * j] = sa_pack(ds[0], ds[1]);
+                    pk[2 * j + 1] = sa_pack(ds[2], ds[3]);
                 }
             }
-        }
-        __syncthreads();
-        uint32_t pk[8];
-        if (role == 0) {
+            // second product: rows = d, columns = keys, contraction over the 32 queries (the rows of
+            // the staged tile, read column-wise)
+            const char *tr = role == 0 ? s_doc[it & 1] : s_qc[b3p];
 #pragma unroll
-            for (int c = 0; c < 8; c++) pk[c] = sa_pack(x[2 * c], x[2 * c + 1]);
-        } else {
-            // dS = P (dP - D_i); the part of it where m_ij follows g_j adds up to dg_j (g_j + eps)
+            for (int t2 = 0; t2 < 2; t2++) {
+                const uint4 p4 = make_uint4(pk[4 * t2], pk[4 * t2 + 1], pk[4 * t2 + 2], pk[4 * t2 + 3]);
+                const sa_bf16x8_t pv = __builtin_bit_cast(sa_bf16x8_t, p4);
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const float4 d4 = *reinterpret_cast<const float4 *>(&s_dd[buf][8 * j + 4 * half]);
-                const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
-                float ds[4];
-#pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    const int ig = i0 + 8 * j + 4 * half + i;
-                    ds[i] = s_p[kb][4 * j + i][lane] * (x[4 * j + i] - dd[i]);
-                    const bool follows = (ig - jg < a.W) ? follows_in : follows_out;
-                    dg_acc += follows ? ds[i] : 0.f;
-                }
-                pk[2 * j] = sa_pack(ds[0], ds[1]);
-                pk[2 * j + 1] = sa_pack(ds[2], ds[3]);
+                for (int db = 0; db < 4; db++)
+                    acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols<kSaCm>(tr, lane, db, 16 * t2), pv, acc[db], 0, 0, 0);
             }
         }
-        // second product: rows = d, columns = keys, contraction over the 32 queries (the rows of
-        // the staged tile, read column-wise)
-        const char *tr = role == 0 ? s_doc[buf] : s_qc[buf];
-#pragma unroll
-        for (int t2 = 0; t2 < 2; t2++) {
-            const uint4 p4 = make_uint4(pk[4 * t2], pk[4 * t2 + 1], pk[4 * t2 + 2], pk[4 * t2 + 3]);
-            const sa_bf16x8_t pv = __builtin_bit_cast(sa_bf16x8_t, p4);
-#pragma unroll
-            for (int db = 0; db < 4; db++)
-                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa_get_cols<kSaCm>(tr, lane, db, 16 * t2), pv, acc[db], 0, 0, 0);
-        }
-        if (it + 1 < n_it) stage(buf ^ 1, rs);
+        if (it + 1 < n_it) stage((it + 1) & 1, b3n, rs);
         __syncthreads();
+        b3 = b3n;
     };
-    for (int it = 0; it < n_it; it += 2) {  // n_it is a multiple of 4
+    for (int it = 0; it <= n_it; it += 2) {  // n_it is a multiple of 4; one more turn for role 1's last tile
         body(it, r0, r1);
-        body(it + 1, r1, r0);
+        if (it + 1 <= n_it) body(it + 1, r1, r0);
     }
     if (jg < T) {
         float *op = (role == 0 ? a.dv : a.dk) + krow * kSaD;
