@@ -117,33 +117,62 @@ __global__ __launch_bounds__(256) void quest_score_kernel(View pv, CallSeqs cs, 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane & 15, slot = lane >> 4, cpr = (int)(pv.row_bytes / 16);
     const int n_iter = (n_pages + gridDim.x * 16 - 1) / (gridDim.x * 16);  // the same for every lane: no divergence
-    for (int it = 0; it < n_iter; it++) {
-        const int p = (it * gridDim.x + blockIdx.x) * 16 + wave * 4 + slot;
-        const bool live = p < n_pages;
-        const int page = pv.global_pt[(size_t)um * pv.maxgp + (live ? p : 0)];
-        const char *lo_row = a.lm + (size_t)page * 2 * pv.row_bytes, *hi_row = lo_row + pv.row_bytes;
-        float best = -INFINITY;
-        for (int g = 0; g < pv.G; g++) {
-            float sum = 0.f;
-            for (int c = sub; c < cpr; c += 16) {
-                const uint4 lo4 = *reinterpret_cast<const uint4 *>(lo_row + c * 16);
-                const uint4 hi4 = *reinterpret_cast<const uint4 *>(hi_row + c * 16);
-                const uint32_t *lw = reinterpret_cast<const uint32_t *>(&lo4), *hw = reinterpret_cast<const uint32_t *>(&hi4);
-                const float *qg = s_q + g * pv.d + c * EPC;
+    // four pages per lane group in flight: their page ids first, then both landmark rows of all four,
+    // each read once for the whole group of query heads (at most 8 of them)
+    constexpr int PF = 4, GMAX = 8;
+    for (int it0 = 0; it0 < n_iter; it0 += PF) {
+        int pidx[PF], page[PF];
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    if (DT == WGKV_F32) {
-                        sum += fmaxf(qg[i] * __uint_as_float(lw[i]), qg[i] * __uint_as_float(hw[i]));
-                    } else {
-                        sum += fmaxf(qg[2 * i] * __uint_as_float(lw[i] << 16), qg[2 * i] * __uint_as_float(hw[i] << 16));
-                        sum += fmaxf(qg[2 * i + 1] * __uint_as_float(lw[i] & 0xffff0000u),
-                                     qg[2 * i + 1] * __uint_as_float(hw[i] & 0xffff0000u));
+        for (int k = 0; k < PF; k++) {
+            pidx[k] = ((it0 + k) * gridDim.x + blockIdx.x) * 16 + wave * 4 + slot;
+            page[k] = pv.global_pt[(size_t)um * pv.maxgp + (pidx[k] < n_pages ? pidx[k] : 0)];
+        }
+        float acc[GMAX][PF];
+#pragma unroll
+        for (int g = 0; g < GMAX; g++)
+#pragma unroll
+            for (int k = 0; k < PF; k++) acc[g][k] = 0.f;
+        for (int c = sub; c < cpr; c += 16) {  // one turn for 256-byte rows
+            uint4 lo4[PF], hi4[PF];
+#pragma unroll
+            for (int k = 0; k < PF; k++) {
+                const char *lo_row = a.lm + (size_t)page[k] * 2 * pv.row_bytes;
+                lo4[k] = *reinterpret_cast<const uint4 *>(lo_row + c * 16);
+                hi4[k] = *reinterpret_cast<const uint4 *>(lo_row + pv.row_bytes + c * 16);
+            }
+#pragma unroll
+            for (int g = 0; g < GMAX; g++) {
+                if (g < pv.G) {
+                    const float *qg = s_q + g * pv.d + c * EPC;
+                    float qv[EPC];
+#pragma unroll
+                    for (int i = 0; i < EPC; i++) qv[i] = qg[i];
+#pragma unroll
+                    for (int k = 0; k < PF; k++) {
+                        const uint32_t lw[4] = {lo4[k].x, lo4[k].y, lo4[k].z, lo4[k].w};
+                        const uint32_t hw[4] = {hi4[k].x, hi4[k].y, hi4[k].z, hi4[k].w};
+#pragma unroll
+                        for (int i = 0; i < 4; i++) {
+                            if (DT == WGKV_F32) {
+                                acc[g][k] += fmaxf(qv[i] * __uint_as_float(lw[i]), qv[i] * __uint_as_float(hw[i]));
+                            } else {
+                                acc[g][k] += fmaxf(qv[2 * i] * __uint_as_float(lw[i] << 16), qv[2 * i] * __uint_as_float(hw[i] << 16));
+                                acc[g][k] += fmaxf(qv[2 * i + 1] * __uint_as_float(lw[i] & 0xffff0000u),
+                                                   qv[2 * i + 1] * __uint_as_float(hw[i] & 0xffff0000u));
+                            }
+                        }
                     }
                 }
             }
-            best = fmaxf(best, group_sum<16>(sum));
         }
-        if (live && sub == 0) a.scores[(size_t)u * a.score_stride + p] = best;
+#pragma unroll
+        for (int k = 0; k < PF; k++) {
+            float best = -INFINITY;
+#pragma unroll
+            for (int g = 0; g < GMAX; g++)
+                if (g < pv.G) best = fmaxf(best, group_sum<16>(acc[g][k]));
+            if (it0 + k < n_iter && pidx[k] < n_pages && sub == 0) a.scores[(size_t)u * a.score_stride + pidx[k]] = best;
+        }
     }
 }
 
@@ -257,8 +286,12 @@ hipError_t launch_quest_select(const View &pv, const CallSeqs &cs, int layer, co
     a.budget_pages = budget_pages;
     a.sel_pages = sel_pages;
     a.sel_count = sel_count;
-    int bx = (int)((max_pages + 3) / 4);
-    bx = bx < 1 ? 1 : (bx > 64 ? 64 : bx);
+    // 16 pages per block and turn, four turns in flight; no more blocks than are resident at once
+    // (three per compute unit at this register count), so that there is a single round of them
+    int bx = (int)((max_pages + 63) / 64);
+    const int cap = n_units > 0 ? (768 / n_units > 1 ? 768 / n_units : 1) : 1;
+    bx = bx < 1 ? 1 : (bx > cap ? cap : bx);
+    bx = bx > 64 ? 64 : bx;
     const dim3 grid(bx, n_units);
     const size_t smem = (size_t)pv.G * pv.d * sizeof(float);
     if (pv.dtype == WGKV_F32) hipLaunchKernelGGL(quest_score_kernel<WGKV_F32>, grid, dim3(256), smem, st, pv, cs, a);
