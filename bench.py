@@ -406,7 +406,8 @@ def main_soft_attn(args, cfg, torch, wg, wl, dev):
         dt = time.perf_counter() - t0
         sample_pairs = Ts * (Ts + 1) / 2.0 * Hq
         cpu = {"value": dt * 1e3 * pairs / sample_pairs, "unit": "ms/step", "cores": min(os.cpu_count() or 1, 16),
-               "kind": "oracle", "sample": f"forward + backward of the first {Ts} tokens, all heads, {dt:.1f} s; "
+               "kind": "oracle", "sample": f"forward + backward of the first {Ts} tokens, all heads, {dt:.1f} s "
+               f"(forward: all host threads over query rows; backward: one thread per kv head, {Hk} of them); "
                f"scaled by the number of (query, key) pairs to {T} tokens (extrapolated)", "sample_seconds": dt}
     res = {
         "metric": "soft_attn_train_step_ms (one layer: Write-Gated Attention forward + backward, one sequence)",
