@@ -112,7 +112,10 @@ def _flow(B, lens, chunk, W, P, hidden_dim, seed, tau=0.5, use_gate=True, check_
     return pool, orc, worst, near
 
 
-@pytest.mark.parametrize("chunk,W,P", [(384, 256, 16), (64, 32, 16), (100, 256, 32), (1, 16, 16), (257, 64, 16)])
+@pytest.mark.parametrize("chunk,W,P", [(384, 256, 16), (64, 32, 16), (100, 256, 32), (1, 16, 16), (257, 64, 16),
+                                       # page sizes around the tile of 32 keys: several pages per tile (4, 8), a page
+                                       # of several tiles (64, 128), pages too small for the scalar page base (1, 2)
+                                       (200, 64, 4), (150, 64, 8), (200, 128, 64), (96, 128, 128), (64, 16, 2), (40, 16, 1)])
 def test_chunked_prefill_every_row(chunk, W, P):
     lens = [min(1536, 12 * chunk + 5), min(900, 7 * chunk)] if chunk > 1 else [70, 33]
     _, _, worst, near = _flow(2, lens, chunk, W, P, hidden_dim=256, seed=1000 + chunk)
