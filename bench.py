@@ -85,6 +85,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--workload", default="llama8b_32layer_b8_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--event-every", type=int, default=8, metavar="N",
+                    help="HIP events go around every N-th launch of the attention kernel, rotating over the layers "
+                         "(a pair of event records costs about 3 us of GPU time, which would add 6 %% to the step "
+                         "if every launch carried one)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the per-kernel HIP events (roofline.achieved becomes null)")
     ap.add_argument("--ctx-scale", type=float, default=1.0, help="shrink contexts (debugging only)")
@@ -199,8 +203,14 @@ def main():
                                               _p(sel_scores), pg_stride, _p(sel_pages), _p(sel_count),
                                               wg.binding._stream()), "wgkv_quest_select")
             if events is not None:
-                i = (st - args.warmup) * L + l
-                pool.set_profile_events(events.ev[2 * i], events.ev[2 * i + 1])
+                if (st + l) % args.event_every == 0 and sampled[0] < n_sampled_max:
+                    i = sampled[0]
+                    sampled[0] += 1
+                    pool.set_profile_events(events.ev[2 * i], events.ev[2 * i + 1])
+                    armed[0] = True
+                elif armed[0]:
+                    pool.set_profile_events(None, None)
+                    armed[0] = False
             if sel_b:
                 pool.attend_selected(l, seqs, q_new[l], sel_pages, sel_count, out[l], scale)
             else:
@@ -225,7 +235,9 @@ def main():
         pool.status()                                             # capturing ran nothing: the host counts are reset to the device's
     meta = pool.meta()
     sl0, gl0 = meta["seq_len"].cpu().numpy(), meta["global_len"].cpu().numpy()
-    events = None if args.no_kernel_events else HipEvents(2 * args.steps * L)
+    n_sampled_max = args.steps * L // max(args.event_every, 1) + L
+    sampled, armed = [0], [False]
+    events = None if args.no_kernel_events else HipEvents(2 * n_sampled_max)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -256,7 +268,7 @@ def main():
                 "traffic": None, "kernel": "attend_decode_kernel",
                 "algorithmic_bytes_per_launch": bytes_per_launch}
     if events is not None:
-        durs = np.array([events.elapsed_ms(events.ev[2 * i], events.ev[2 * i + 1]) for i in range(args.steps * L)])
+        durs = np.array([events.elapsed_ms(events.ev[2 * i], events.ev[2 * i + 1]) for i in range(sampled[0])])
         avg_us = float(durs.mean() * 1e3)
         roofline.update({"achieved": bytes_per_launch / (avg_us * 1e-6) / 1e9,
                          "frac": bytes_per_launch / (avg_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
