@@ -36,6 +36,7 @@ constexpr int kPfVStride = 320;   // bytes per key row of the V tile (256 + 64 p
                                   // spreads over all banks
 
 struct PrefillAttnArgs {
+    int nx;                 // blocks per (sequence, kv head) of the launch
     int layer;
     float tau;
     float scale_log2e;
@@ -73,7 +74,9 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
     __shared__ __attribute__((aligned(16))) int s_lo[2][kPfKT];
     __shared__ __attribute__((aligned(16))) int s_hi[2][kPfKT];
 
-    const int b = blockIdx.z, h = blockIdx.y, qt = blockIdx.x;
+    int bx, h, b;
+    xcd_item(a.nx, pv.Hkv, cs.n, bx, h, b);
+    const int qt = a.nx - 1 - bx;  // later positions see more keys: first
     const int T = cs.ntok[b], t0 = cs.t0[b], base = cs.base[b];
     if (qt * kPfQ >= T) return;  // block-uniform
     const int sid = cs.sid[b];
@@ -334,8 +337,8 @@ hipError_t launch_attend_prefill(const View &pv, const CallSeqs &cs, int layer, 
     int max_t = 0;
     for (int b = 0; b < cs.n; b++) max_t = max(max_t, cs.ntok[b]);
     if (max_t == 0) return hipSuccess;
-    dim3 grid((max_t + kPfQ - 1) / kPfQ, pv.Hkv, cs.n);
-    hipLaunchKernelGGL(attend_prefill_kernel, grid, dim3(512), 0, st, pv, cs, a);
+    a.nx = (max_t + kPfQ - 1) / kPfQ;
+    hipLaunchKernelGGL(attend_prefill_kernel, dim3(a.nx * pv.Hkv * cs.n), dim3(512), 0, st, pv, cs, a);
     return hipGetLastError();
 }
 

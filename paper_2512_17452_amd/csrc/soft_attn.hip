@@ -46,6 +46,7 @@ struct SoftSeqs {
 };
 
 struct SoftArgs {
+    int nx;                 // blocks per (sequence, kv head) of the launch
     int Hq, Hkv, W;
     float scale_log2e;      // scale * log2(e): scores are kept in base-2 units
     float scale;
@@ -111,8 +112,9 @@ __global__ __launch_bounds__(512) void soft_attn_fwd_kernel(SoftSeqs cs, SoftArg
     __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT2];
     __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT2];
 
-    const int b = blockIdx.z, h = blockIdx.y;
-    const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;  // longest rows first
+    int bx, h, b;
+    xcd_item(a.nx, a.Hkv, cs.n, bx, h, b);
+    const int qt = a.nx - 1 - bx;  // longest rows first
     const int T = cs.ntok[b], base = cs.base[b];
     if (qt * kSaQ >= T) return;  // block-uniform
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -301,8 +303,9 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
     __shared__ __attribute__((aligned(16))) float s_bin[2][kSaT];
     __shared__ __attribute__((aligned(16))) float s_bout[2][kSaT];
 
-    const int b = blockIdx.z, h = blockIdx.y;
-    const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;
+    int bx, h, b;
+    xcd_item(a.nx, a.Hkv, cs.n, bx, h, b);
+    const int qt = a.nx - 1 - bx;
     const int T = cs.ntok[b], base = cs.base[b];
     if (qt * kSaQ >= T) return;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -439,7 +442,8 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
     __shared__ __attribute__((aligned(16))) float s_dd[3][kSaT];
     __shared__ float s_p[2][4][16][64];  // P of a (32 keys x 32 queries) tile per key sub-tile, lane-private slots
 
-    const int b = blockIdx.z, h = blockIdx.y, kbk = blockIdx.x;  // early key blocks have the most queries: first
+    int kbk, h, b;  // early key blocks have the most queries: first
+    xcd_item(a.nx, a.Hkv, cs.n, kbk, h, b);
     const int T = cs.ntok[b], base = cs.base[b];
     const int j0 = kbk * kSaKB;
     if (j0 >= T) return;
@@ -634,8 +638,8 @@ hipError_t launch_soft_attn_fwd(int n_seqs, const int32_t *n_tokens, int Hq, int
     a.scale = scale; a.scale_log2e = scale * 1.4426950408889634f; a.eps = eps;
     a.q = (const char *)q; a.k = (const char *)k; a.v = (const char *)v; a.g = g;
     a.out = out; a.lse = lse;
-    dim3 grid((max_t + kSaQ - 1) / kSaQ, Hkv, n_seqs);
-    hipLaunchKernelGGL(soft_attn_fwd_kernel, grid, dim3(512), 0, st, cs, a);
+    a.nx = (max_t + kSaQ - 1) / kSaQ;
+    hipLaunchKernelGGL(soft_attn_fwd_kernel, dim3(a.nx * Hkv * n_seqs), dim3(512), 0, st, cs, a);
     return hipGetLastError();
 }
 
@@ -662,10 +666,12 @@ hipError_t launch_soft_attn_bwd(int n_seqs, const int32_t *n_tokens, int Hq, int
                        a.dout, out, a.rowdot);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(soft_attn_bwd_dq_kernel, dim3((max_t + kSaQ - 1) / kSaQ, Hkv, n_seqs), dim3(512), 0, st, cs, a);
+    a.nx = (max_t + kSaQ - 1) / kSaQ;
+    hipLaunchKernelGGL(soft_attn_bwd_dq_kernel, dim3(a.nx * Hkv * n_seqs), dim3(512), 0, st, cs, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(soft_attn_bwd_dkv_kernel, dim3((max_t + kSaKB - 1) / kSaKB, Hkv, n_seqs), dim3(512), 0, st, cs, a);
+    a.nx = (max_t + kSaKB - 1) / kSaKB;
+    hipLaunchKernelGGL(soft_attn_bwd_dkv_kernel, dim3(a.nx * Hkv * n_seqs), dim3(512), 0, st, cs, a);
     return hipGetLastError();
 }
 

@@ -43,6 +43,28 @@ __device__ __forceinline__ char *page_ptr(const View &pv, int page) {
     return pv.pool + (uint64_t)(uint32_t)page * pv.page_bytes;
 }
 
+// Work items (x, head, z) of a 1-D launch of nx * nh * nz blocks.  Blocks go to the 8 XCDs
+// round-robin by their index, and each XCD has its own L2: when the heads divide evenly, an XCD
+// gets all blocks of its heads and of no others, so the blocks that stream the same K/V (or Q/dO)
+// tiles of a head share one L2 instead of pulling eight copies through eight of them.  Inside an
+// XCD the order is z, head, x ascending (callers put the heaviest x first).
+__device__ __forceinline__ void xcd_item(int nx, int nh, int nz, int &x, int &h, int &z) {
+    constexpr int kXcds = 8;
+    const int n = (int)blockIdx.x;
+    (void)nz;
+    if (nh % kXcds == 0) {
+        const int xcd = n % kXcds, r = n / kXcds, hpx = nh / kXcds;
+        z = r / (hpx * nx);
+        const int rem = r - z * hpx * nx;
+        h = xcd + kXcds * (rem / nx);
+        x = rem % nx;
+    } else {
+        x = n % nx;
+        h = (n / nx) % nh;
+        z = n / (nx * nh);
+    }
+}
+
 // ---- wave64 cross-lane helpers (DPP where the pattern allows) ----
 
 template <int CTRL>
