@@ -37,6 +37,7 @@ constexpr int kPfVStride = 320;   // bytes per key row of the V tile (256 + 64 p
 
 struct PrefillAttnArgs {
     int nx;                 // blocks per (sequence, kv head) of the launch
+    const int32_t *order;   // [n_units] (sequence, kv head) units, the one with the longest global cache first
     int layer;
     float tau;
     float scale_log2e;
@@ -74,9 +75,15 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
     __shared__ __attribute__((aligned(16))) int s_lo[2][kPfKT];
     __shared__ __attribute__((aligned(16))) int s_hi[2][kPfKT];
 
-    int bx, h, b;
-    xcd_item(a.nx, pv.Hkv, cs.n, bx, h, b);
-    const int qt = a.nx - 1 - bx;  // later positions see more keys: first
+    // Blocks are handed out in the order of their index and go to the 8 XCDs round-robin: all
+    // blocks of the unit with the longest global cache come first, its latest positions (which see
+    // the most chunk keys) at the front, then the next unit.  Admission is head-specific, so units
+    // differ several-fold in work: with the long ones at the front the launch does not end on a
+    // late-started long one, and every unit is spread evenly over the XCDs (giving each XCD whole
+    // heads, for the sake of its L2, leaves the XCDs as unbalanced as the heads are).
+    const int unit = a.order[blockIdx.x / a.nx];
+    const int b = unit / pv.Hkv, h = unit % pv.Hkv;
+    const int qt = a.nx - 1 - (int)(blockIdx.x % a.nx);
     const int T = cs.ntok[b], t0 = cs.t0[b], base = cs.base[b];
     if (qt * kPfQ >= T) return;  // block-uniform
     const int sid = cs.sid[b];
@@ -315,15 +322,28 @@ __global__ __launch_bounds__(512) void attend_prefill_kernel(View pv, CallSeqs c
     }
 }
 
+// Units of the call by descending length of their global cache (equal lengths: lower unit first).
+__global__ __launch_bounds__(1024) void prefill_order_kernel(View pv, CallSeqs cs, int layer, int32_t *order) {
+    __shared__ int s_len[kMaxCallUnits];
+    const int n_units = cs.n * pv.Hkv, u = threadIdx.x;
+    if (u < n_units) s_len[u] = pv.global_len[unit_meta(pv, cs.sid[u / pv.Hkv], layer, u % pv.Hkv)];
+    __syncthreads();
+    if (u < n_units) {
+        const int mine = s_len[u];
+        int rank = 0;
+        for (int v = 0; v < n_units; v++) rank += (s_len[v] > mine || (s_len[v] == mine && v < u)) ? 1 : 0;
+        order[rank] = u;
+    }
+}
+
 size_t attend_prefill_ws_bytes(const View &pv, int n_seqs, int64_t total_q) {
     (void)pv; (void)n_seqs; (void)total_q;
-    return 256;  // the kernel keeps everything in registers and LDS
+    return 256 + sizeof(int32_t) * kMaxCallUnits;  // the order of the units; everything else stays in registers and LDS
 }
 
 hipError_t launch_attend_prefill(const View &pv, const CallSeqs &cs, int layer, const void *q,
                                  const void *k, const void *v, const float *g, float tau,
                                  float scale, float *out, void *ws, hipStream_t st) {
-    (void)ws;
     if (pv.dtype != WGKV_BF16 || pv.d != kPfD || pv.G != 4) return hipErrorNotSupported;
     PrefillAttnArgs a;
     a.layer = layer;
@@ -338,6 +358,10 @@ hipError_t launch_attend_prefill(const View &pv, const CallSeqs &cs, int layer, 
     for (int b = 0; b < cs.n; b++) max_t = max(max_t, cs.ntok[b]);
     if (max_t == 0) return hipSuccess;
     a.nx = (max_t + kPfQ - 1) / kPfQ;
+    a.order = (const int32_t *)ws;
+    hipLaunchKernelGGL(prefill_order_kernel, dim3(1), dim3(1024), 0, st, pv, cs, layer, (int32_t *)ws);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(attend_prefill_kernel, dim3(a.nx * pv.Hkv * cs.n), dim3(512), 0, st, pv, cs, a);
     return hipGetLastError();
 }
