@@ -86,6 +86,30 @@ constexpr int kDppShr4 = 0x114;       // lane i reads lane i-4
 constexpr int kDppRor4 = 0x124;       // rotate the row of 16 by 4
 constexpr int kDppRor8 = 0x128;       // rotate by 8: lane i <-> i^8
 
+// v_permlane32_swap / v_permlane16_swap exchange halves (quarters) of two registers
+// inside the vector unit, without the LDS crossbar that ds_bpermute goes through.
+// swap32(a, b): lanes 0-31 get (a[l], a[l+32]), lanes 32-63 get (b[l-32], b[l]);
+// swap16(a, b): rows 0 and 2 of 16 lanes get (a[l], a[l+16]), rows 1 and 3 get (b[l-16], b[l]).
+// With a == b every lane holds its own value and that of lane l^32 (l^16); with two
+// different values, adding the pair halves two partial sums into one per lane.
+struct LanePair {
+    float a, b;
+};
+// (Written as assembly: with the compiler builtins of this toolchain, arithmetic on the
+// two results reads the first one twice.  The s_nop covers the wait states the
+// instruction needs after a vector write of its operands.)
+__device__ __forceinline__ LanePair swap32(float a, float b) {
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return {a, b};
+}
+__device__ __forceinline__ LanePair swap16(float a, float b) {
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return {a, b};
+}
+__device__ __forceinline__ float sum_xor32(float x) { const LanePair r = swap32(x, x); return r.a + r.b; }
+__device__ __forceinline__ float sum_xor16(float x) { const LanePair r = swap16(x, x); return r.a + r.b; }
+__device__ __forceinline__ float max_xor32(float x) { const LanePair r = swap32(x, x); return fmaxf(r.a, r.b); }
+
 // Sum over aligned groups of N consecutive lanes; every lane of the group gets the total.
 template <int N>
 __device__ __forceinline__ float group_sum(float x) {
@@ -94,8 +118,8 @@ __device__ __forceinline__ float group_sum(float x) {
     if (N >= 4) x += dpp_f<kDppXor2>(x);
     if (N >= 8) x += dpp_f<kDppHalfMirror>(x);
     if (N >= 16) x += dpp_f<kDppMirror>(x);
-    if (N >= 32) x += __shfl_xor(x, 16);
-    if (N >= 64) x += __shfl_xor(x, 32);
+    if (N >= 32) x = sum_xor16(x);
+    if (N >= 64) x = sum_xor32(x);
     return x;
 }
 
