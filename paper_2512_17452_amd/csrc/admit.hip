@@ -14,7 +14,9 @@
 
 namespace wgkv {
 
-constexpr int kPrefillBlk = 1024;  // leaving tokens per block (256 threads x 4)
+constexpr int kPrefillBlk = 512;   // leaving tokens per block of 256 threads
+constexpr int kTok = kPrefillBlk / 256;  // tokens per thread
+constexpr int kPlanThreads = 1024; // the one block of prefill_plan_kernel
 
 struct PrefillArgs {
     int layer;
@@ -68,10 +70,10 @@ __global__ __launch_bounds__(256) void prefill_count_kernel(View pv, CallSeqs cs
     const int t0 = cs.t0[b], T = cs.ntok[b], base = cs.base[b];
     const int um = unit_meta(pv, cs.sid[b], a.layer, h);
     const int lo = max(0, t0 - pv.W), hi = max(0, t0 + T - pv.W), n_leave = hi - lo;
-    const int i0 = blockIdx.x * kPrefillBlk + threadIdx.x * 4;
+    const int i0 = blockIdx.x * kPrefillBlk + threadIdx.x * kTok;
     if (a.admit_out) {
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
+        for (int j = 0; j < kTok; j++) {
             int i = i0 + j;
             if (i < T) {
                 size_t row = (size_t)(base + i) * pv.Hkv + h;
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(256) void prefill_count_kernel(View pv, CallSeqs cs
     if (blockIdx.x * kPrefillBlk >= n_leave) return;  // block-uniform
     int c = 0;
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
+    for (int j = 0; j < kTok; j++) {
         int i = i0 + j;
         if (i < n_leave) c += (int)(leaving_score(pv, a, um, h, lo + i, t0, base) >= a.tau);
     }
@@ -93,19 +95,30 @@ __global__ __launch_bounds__(256) void prefill_count_kernel(View pv, CallSeqs cs
     if (threadIdx.x == 0) a.cnt[(size_t)u * a.nblk_max + blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
 }
 
-__global__ __launch_bounds__(256) void prefill_plan_kernel(View pv, CallSeqs cs, PrefillArgs a) {
+__global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(View pv, CallSeqs cs, PrefillArgs a) {
     __shared__ int s_adm[kMaxCallUnits];
     __shared__ int s_gold[kMaxCallUnits];
     __shared__ int s_base[kMaxCallUnits];
     __shared__ int s_dl[kMaxCallUnits];
+    __shared__ int s_um[kMaxCallUnits];
     __shared__ int s_tmp[20];
     __shared__ int s_err;
     const int n_units = cs.n * pv.Hkv;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    constexpr int NW = kPlanThreads / 64;
     if (threadIdx.x == 0) s_err = 0;
+    // what phase B needs of the first kPlanThreads units is asked for now: the kernel is a
+    // chain of round trips on cold metadata, and these do not depend on phase A
+    int um0 = 0, gold0 = 0, lp00 = 0;
+    if ((int)threadIdx.x < n_units) {
+        um0 = unit_meta(pv, cs.sid[threadIdx.x / pv.Hkv], a.layer, threadIdx.x % pv.Hkv);
+        gold0 = pv.global_len[um0];
+        lp00 = pv.local_pt[(size_t)um0 * pv.nlp];
+    }
+    const int top = *pv.free_top;
     __syncthreads();
     // A: one wave per unit turns block counts into exclusive offsets
-    for (int u = w; u < n_units; u += 4) {
+    for (int u = w; u < n_units; u += NW) {
         const int b = u / pv.Hkv;
         const int t0 = cs.t0[b], T = cs.ntok[b];
         const int n_leave = max(0, t0 + T - pv.W) - max(0, t0 - pv.W);
@@ -123,22 +136,23 @@ __global__ __launch_bounds__(256) void prefill_plan_kernel(View pv, CallSeqs cs,
     }
     __syncthreads();
     // B: page demand of every unit, prefix over units in call order
-    const int top = *pv.free_top;
     int carry = 0;
-    for (int u0 = 0; u0 < n_units; u0 += 256) {
+    for (int u0 = 0; u0 < n_units; u0 += kPlanThreads) {
         const int u = u0 + threadIdx.x;
         int demand = 0;
         if (u < n_units) {
             const int b = u / pv.Hkv, h = u % pv.Hkv;
-            const int um = unit_meta(pv, cs.sid[b], a.layer, h);
-            const int gold = pv.global_len[um];
+            const int um = u0 == 0 ? um0 : unit_meta(pv, cs.sid[b], a.layer, h);
+            const int gold = u0 == 0 ? gold0 : pv.global_len[um];
+            const int lp0 = u0 == 0 ? lp00 : pv.local_pt[(size_t)um * pv.nlp];
             const int gnew = gold + s_adm[u];
-            const int dl = (cs.ntok[b] > 0 && pv.local_pt[(size_t)um * pv.nlp] < 0) ? pv.nlp : 0;
+            const int dl = (cs.ntok[b] > 0 && lp0 < 0) ? pv.nlp : 0;
             const int pages_new = (gnew + pv.P - 1) >> pv.logP;
             if (pages_new > pv.maxgp) s_err = WGKV_ERR_PT_OVERFLOW;
             demand = dl + pages_new - ((gold + pv.P - 1) >> pv.logP);
             s_gold[u] = gold;
             s_dl[u] = dl;
+            s_um[u] = um;
         }
         int total;
         int ex = block_excl_scan(demand, s_tmp, &total);
@@ -155,33 +169,55 @@ __global__ __launch_bounds__(256) void prefill_plan_kernel(View pv, CallSeqs cs,
         }
         return;
     }
-    // C: page-table entries, one wave per unit
-    for (int u = w; u < n_units; u += 4) {
-        const int b = u / pv.Hkv, h = u % pv.Hkv;
-        const int um = unit_meta(pv, cs.sid[b], a.layer, h);
-        const int gold = s_gold[u], dl = s_dl[u], ubase = s_base[u];
-        for (int i = lane; i < dl; i += 64) pv.local_pt[(size_t)um * pv.nlp + i] = pv.free_stack[top - 1 - (ubase + i)];
-        const int first = (gold + pv.P - 1) >> pv.logP;
-        const int n_new = ((gold + s_adm[u] + pv.P - 1) >> pv.logP) - first;
-        for (int j = lane; j < n_new; j += 64)
-            pv.global_pt[(size_t)um * pv.maxgp + first + j] = pv.free_stack[top - 1 - (ubase + dl + j)];
+    // C: page-table entries.  Page f of the call (in unit order) is free_stack[top-1-f] whatever
+    // unit it goes to, so the hand-out is one flat loop over all threads, four loads in flight per
+    // thread; the owner of f is the last unit whose base is <= f (units without demand share
+    // their base with the next one and are never picked).
+    for (int f0 = 0; f0 < carry; f0 += kPlanThreads * 4) {
+        int pg[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const int f = f0 + k * kPlanThreads + (int)threadIdx.x;
+            pg[k] = pv.free_stack[top - 1 - min(f, carry - 1)];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const int f = f0 + k * kPlanThreads + (int)threadIdx.x;
+            if (f < carry) {
+                int lo_u = 0, hi_u = n_units - 1;  // invariant: s_base[lo_u] <= f
+                while (lo_u < hi_u) {
+                    const int mid = (lo_u + hi_u + 1) >> 1;
+                    if (s_base[mid] <= f) lo_u = mid; else hi_u = mid - 1;
+                }
+                const int u = lo_u, i = f - s_base[u], dl = s_dl[u], um = s_um[u];
+                if (i < dl) pv.local_pt[(size_t)um * pv.nlp + i] = pg[k];
+                else pv.global_pt[(size_t)um * pv.maxgp + ((s_gold[u] + pv.P - 1) >> pv.logP) + (i - dl)] = pg[k];
+            }
+        }
     }
     // D: lengths
-    for (int u = threadIdx.x; u < n_units; u += 256) {
+    for (int u = threadIdx.x; u < n_units; u += kPlanThreads) {
         const int b = u / pv.Hkv, h = u % pv.Hkv;
         const int um = unit_meta(pv, cs.sid[b], a.layer, h);
         pv.global_len[um] = s_gold[u] + s_adm[u];
         a.plan[1 + u] = s_gold[u];
     }
-    for (int b = threadIdx.x; b < cs.n; b += 256) pv.seq_len[cs.sid[b] * pv.L + a.layer] = cs.t0[b] + cs.ntok[b];
+    for (int b = threadIdx.x; b < cs.n; b += kPlanThreads) pv.seq_len[cs.sid[b] * pv.L + a.layer] = cs.t0[b] + cs.ntok[b];
     if (threadIdx.x == 0) {
         *pv.free_top = top - carry;
         a.plan[0] = 0;
     }
 }
 
+constexpr int kScatterBatch = 8;  // rows a thread has in flight in the copy loop
+
+// The copy is a chain of round trips if done row by row (page id, then the row, then the
+// store), so the destination page ids of the block go to LDS once (its rows land in one
+// contiguous range of the global cache) and a thread requests 8 rows before it stores any.
 __global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs cs, PrefillArgs a) {
-    __shared__ int s_src[kPrefillBlk];
+    __shared__ int s_src[kPrefillBlk];  // admitted leaving tokens of the block, in order
+    __shared__ int s_rpg[kPrefillBlk];  // ring page of the token if its row sits in the ring, else -1
+    __shared__ int s_gp[kPrefillBlk];   // pages of the destination range
     __shared__ int s_tmp[20];
     if (a.plan[0] != 0) return;
     const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
@@ -189,45 +225,73 @@ __global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs 
     const int um = unit_meta(pv, cs.sid[b], a.layer, h);
     const int lo = max(0, t0 - pv.W), hi = max(0, t0 + T - pv.W), n_leave = hi - lo;
     if (blockIdx.x * kPrefillBlk >= n_leave) return;
-    const int i0 = blockIdx.x * kPrefillBlk + threadIdx.x * 4;
-    int f[4], c = 0;
+    const int dst0 = a.plan[1 + u] + a.cnt[(size_t)u * a.nblk_max + blockIdx.x];
+    const int i0 = blockIdx.x * kPrefillBlk + threadIdx.x * kTok;
+    int f[kTok], rpg[kTok], c = 0;
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
+    for (int j = 0; j < kTok; j++) {
         int i = i0 + j;
         f[j] = (i < n_leave) ? (int)(leaving_score(pv, a, um, h, lo + i, t0, base) >= a.tau) : 0;
+        rpg[j] = -1;
+        if (f[j] && lo + i < t0)  // fed by an earlier call: the row sits in the ring
+            rpg[j] = pv.local_pt[(size_t)um * pv.nlp + (((lo + i) % pv.W) >> pv.logP)];
         c += f[j];
     }
     int n_adm;
     int rank = block_excl_scan(c, s_tmp, &n_adm);
 #pragma unroll
-    for (int j = 0; j < 4; j++)
-        if (f[j]) s_src[rank++] = i0 + j;
+    for (int j = 0; j < kTok; j++)
+        if (f[j]) {
+            s_src[rank] = i0 + j;
+            s_rpg[rank++] = rpg[j];
+        }
+    const int pg_first = dst0 >> pv.logP;
+    const int n_pg = n_adm > 0 ? ((dst0 + n_adm - 1) >> pv.logP) - pg_first + 1 : 0;  // <= kPrefillBlk
+    for (int i = threadIdx.x; i < n_pg; i += 256) s_gp[i] = pv.global_pt[(size_t)um * pv.maxgp + pg_first + i];
     __syncthreads();
     // copy the admitted rows: lpr lanes of 16 bytes per row, K and V
     const int lpr = pv.row_bytes >> 4;
     const int rows_per_pass = 256 / lpr;
     const int sub = threadIdx.x % lpr;
-    const int dst0 = a.plan[1 + u] + a.cnt[(size_t)u * a.nblk_max + blockIdx.x];
-    for (int r = threadIdx.x / lpr; r < n_adm; r += rows_per_pass) {
-        const int p = lo + s_src[r];
-        const char *ks, *vs;
-        if (p < t0) {
-            const int slot = p % pv.W;
-            const char *pg = page_ptr(pv, pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)]);
-            ks = pg + (size_t)(slot & (pv.P - 1)) * pv.row_bytes;
-            vs = ks + pv.v_off;
-        } else {
-            const size_t row = ((size_t)(base + p - t0) * pv.Hkv + h) * pv.row_bytes;
-            ks = a.k + row;
-            vs = a.v + row;
+    const size_t sub16 = (size_t)sub * 16;
+    auto src_of = [&](int r, const char *&ks, const char *&vs) __attribute__((always_inline)) {
+        ks = a.k;  // a row past the end reads the first row of the call and drops it
+        vs = a.v;
+        if (r < n_adm) {
+            const int p = lo + s_src[r], pgid = s_rpg[r];
+            if (pgid >= 0) {
+                const int slot = p % pv.W;
+                ks = page_ptr(pv, pgid) + (size_t)(slot & (pv.P - 1)) * pv.row_bytes;
+                vs = ks + pv.v_off;
+            } else {
+                const size_t row = ((size_t)(base + p - t0) * pv.Hkv + h) * pv.row_bytes;
+                ks = a.k + row;
+                vs = a.v + row;
+            }
         }
-        const int dst = dst0 + r;
-        char *dp = page_ptr(pv, pv.global_pt[(size_t)um * pv.maxgp + (dst >> pv.logP)]) +
-                   (size_t)(dst & (pv.P - 1)) * pv.row_bytes;
-        const uint4 kk = *reinterpret_cast<const uint4 *>(ks + sub * 16);
-        const uint4 vv = *reinterpret_cast<const uint4 *>(vs + sub * 16);
-        *reinterpret_cast<uint4 *>(dp + sub * 16) = kk;
-        *reinterpret_cast<uint4 *>(dp + pv.v_off + sub * 16) = vv;
+    };
+    auto put = [&](int r, const uint4 &kk, const uint4 &vv) __attribute__((always_inline)) {
+        if (r < n_adm) {
+            const int dst = dst0 + r;
+            char *dp = page_ptr(pv, s_gp[(dst >> pv.logP) - pg_first]) + (size_t)(dst & (pv.P - 1)) * pv.row_bytes;
+            *reinterpret_cast<uint4 *>(dp + sub16) = kk;
+            *reinterpret_cast<uint4 *>(dp + pv.v_off + sub16) = vv;
+        }
+    };
+    static_assert(kScatterBatch == 8, "the copy loop is written out for 8 rows");
+    const int rp = rows_per_pass;
+    for (int r0 = threadIdx.x / lpr; r0 < n_adm; r0 += rp * kScatterBatch) {
+        const char *k0, *k1, *k2, *k3, *k4, *k5, *k6, *k7, *v0, *v1, *v2, *v3, *v4, *v5, *v6, *v7;
+        src_of(r0, k0, v0); src_of(r0 + rp, k1, v1); src_of(r0 + 2 * rp, k2, v2); src_of(r0 + 3 * rp, k3, v3);
+        src_of(r0 + 4 * rp, k4, v4); src_of(r0 + 5 * rp, k5, v5); src_of(r0 + 6 * rp, k6, v6); src_of(r0 + 7 * rp, k7, v7);
+#define WGKV_LD(p) (*reinterpret_cast<const uint4 *>((p) + sub16))
+        const uint4 a0 = WGKV_LD(k0), b0 = WGKV_LD(v0), a1 = WGKV_LD(k1), b1 = WGKV_LD(v1), a2 = WGKV_LD(k2),
+                    b2 = WGKV_LD(v2), a3 = WGKV_LD(k3), b3 = WGKV_LD(v3), a4 = WGKV_LD(k4), b4 = WGKV_LD(v4),
+                    a5 = WGKV_LD(k5), b5 = WGKV_LD(v5), a6 = WGKV_LD(k6), b6 = WGKV_LD(v6), a7 = WGKV_LD(k7),
+                    b7 = WGKV_LD(v7);
+#undef WGKV_LD
+        put(r0, a0, b0); put(r0 + rp, a1, b1); put(r0 + 2 * rp, a2, b2); put(r0 + 3 * rp, a3, b3);
+        put(r0 + 4 * rp, a4, b4); put(r0 + 5 * rp, a5, b5); put(r0 + 6 * rp, a6, b6); put(r0 + 7 * rp, a7, b7);
     }
 }
 
@@ -420,7 +484,7 @@ hipError_t launch_prefill(const View &pv, const CallSeqs &cs, int layer, float t
     int gx = a.nblk_max;
     if (admit_out) gx = max(gx, (max_T + kPrefillBlk - 1) / kPrefillBlk);
     hipLaunchKernelGGL(prefill_count_kernel, dim3(gx, n_units), dim3(256), 0, st, pv, cs, a);
-    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(256), 0, st, pv, cs, a);
+    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, pv, cs, a);
     if (nblk_leave_max > 0)
         hipLaunchKernelGGL(prefill_scatter_kernel, dim3(a.nblk_max, n_units), dim3(256), 0, st, pv, cs, a);
     if (max_ring_rows > 0) {

@@ -65,7 +65,7 @@ using namespace wgkv;
 
 namespace {
 
-constexpr int kPrefillBlkHost = 1024;   // must match kPrefillBlk in admit.hip
+constexpr int kPrefillBlkHost = 512;    // must match kPrefillBlk in admit.hip
 constexpr int kAttnGridMax = 2048;      // upper bound on the decode-attention grid (blocks of 4 waves)
 constexpr int kAttnMinTilesPerWave = 16;  // below that a share is shorter than the fold of its partial
 
