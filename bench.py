@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the per-kernel HIP events (roofline.achieved becomes null)")
     ap.add_argument("--ctx-scale", type=float, default=1.0, help="shrink contexts (debugging only)")
+    ap.add_argument("--ctx-fixed", type=int, default=0, metavar="TOKENS",
+                    help="decode workloads: every sequence gets exactly this context instead of the workload's "
+                         "draw (the supplementary fixed point: 131072 for llama8b_32layer_b8_128k)")
     ap.add_argument("--gate", choices=["linear", "mlp"], default="linear",
                     help="chunked-prefill workload only: the workload's linear gate on the hidden state, or the "
                          "Write-Gate MLP (width 4*head_dim, random weights) on the keys before/after the rotary embedding")
@@ -137,6 +140,8 @@ def main():
     ctx = wl.context_lengths(cfg)
     if args.ctx_scale != 1.0:
         ctx = np.maximum((ctx * args.ctx_scale).astype(np.int64), W + 1)
+    if args.ctx_fixed:
+        ctx = np.full_like(ctx, max(args.ctx_fixed, W + 1))
     rates = wl.unit_rates(cfg)
     total_steps = args.steps + args.warmup
     max_ctx = int(ctx.max())
@@ -285,7 +290,7 @@ def main():
         del src, dst
     # HBM bytes per launch measured with rocprofv3 counters (see the summary's header for the commands)
     traffic_file = os.path.join(ROOT, "profiles", f"attend_decode_kernel_{cfg.name}_hbm_traffic.txt")
-    if os.path.exists(traffic_file) and not sel_b:
+    if os.path.exists(traffic_file) and not sel_b and not args.ctx_fixed and args.ctx_scale == 1.0:
         for line in open(traffic_file):
             if line.startswith("hbm_bytes_per_launch:"):
                 roofline["traffic"] = float(line.split(":")[1])
