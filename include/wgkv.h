@@ -354,8 +354,11 @@ int wgkv_status(wgkv_pool *pool, wgkv_stream stream, int64_t *pages_free,
                 int32_t *device_error_flag);
 
 /* Measurement aid: when both are non-NULL hipEvent_t handles, every later
- * wgkv_attend records ev_begin right before and ev_end right after its main
- * attention kernel on the call's stream.  Pass NULLs to switch it off. */
+ * wgkv_attend times its main attention kernel on the call's stream.  The decode
+ * form attaches the two events to the kernel's own dispatch (hipExtLaunchKernelGGL:
+ * they carry the begin and end time stamps of that dispatch, what a kernel trace
+ * reports); the prefill form records ev_begin right before and ev_end right after
+ * its kernels.  Pass NULLs to switch it off. */
 int wgkv_set_profile_events(wgkv_pool *pool, void *ev_begin, void *ev_end);
 
 /* Frees the host handle only. */

@@ -20,6 +20,8 @@
 // independent online-softmax streams that are only combined when a unit ends.
 #include <type_traits>
 
+#include <hip/hip_ext.h>
+
 #include "wgkv_dev.h"
 
 namespace wgkv {
@@ -688,8 +690,10 @@ static hipError_t launch_g(const View &pv, const AttendArgs &a, int n_cu, int gr
     case GG:                                                                                       \
         grid = n_cu * resident_blocks_per_cu<DT, D, GG>();                                         \
         if (grid > grid_max) grid = grid_max;                                                      \
-        if (ev0) (void)hipEventRecord(ev0, st);                                                    \
-        hipLaunchKernelGGL((attend_decode_kernel<DT, D, GG>), dim3(grid), dim3(kAttnThreads), 0, st, pv, a); \
+        if (ev0 && ev1)  /* the events take the begin and end time stamps of this dispatch itself */ \
+            hipExtLaunchKernelGGL((attend_decode_kernel<DT, D, GG>), dim3(grid), dim3(kAttnThreads), 0, st, ev0, ev1, 0, pv, a); \
+        else                                                                                       \
+            hipLaunchKernelGGL((attend_decode_kernel<DT, D, GG>), dim3(grid), dim3(kAttnThreads), 0, st, pv, a); \
         break;
         WGKV_CASE(1)
         WGKV_CASE(2)
@@ -698,7 +702,6 @@ static hipError_t launch_g(const View &pv, const AttendArgs &a, int n_cu, int gr
 #undef WGKV_CASE
         default: return hipErrorInvalidValue;
     }
-    if (ev1) (void)hipEventRecord(ev1, st);
     return hipGetLastError();
 }
 
