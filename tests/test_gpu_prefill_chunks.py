@@ -21,7 +21,10 @@ GUARD = 1e-3          # |logit - logit(tau)| below which the fp32 and fp64 decis
 
 @pytest.mark.parametrize("dtype,T,dim,Hk", [(torch.bfloat16, 1000, 4096, 8), (torch.bfloat16, 7, 64, 2),
                                             (torch.float32, 129, 512, 8), (torch.bfloat16, 4096, 4096, 8),
-                                            (torch.bfloat16, 33, 2056, 12)])
+                                            (torch.bfloat16, 33, 2056, 12),
+                                            # more row quads than waves in the launch (a second pass with a ragged
+                                            # tail), the second one with four weight slices per pass as well
+                                            (torch.bfloat16, 9001, 1024, 8), (torch.float32, 8203, 8192, 3)])
 def test_gate_scores_match_fp64(dtype, T, dim, Hk):
     dev = torch.device("cuda:0")
     gen = torch.Generator(device="cpu").manual_seed(T * 131 + dim)
