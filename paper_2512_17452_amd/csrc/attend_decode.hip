@@ -507,14 +507,33 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                     if constexpr (S > 1) process(std::integral_constant<int, 1 % S>{}, std::true_type{}, j + 1);
                     if constexpr (S > 2) process(std::integral_constant<int, 2 % S>{}, std::true_type{}, j + 2);
                     if constexpr (S > 3) process(std::integral_constant<int, 3 % S>{}, std::true_type{}, j + 3);
+                    if constexpr (S > 4) process(std::integral_constant<int, 4 % S>{}, std::true_type{}, j + 4);
+                    if constexpr (S > 5) process(std::integral_constant<int, 5 % S>{}, std::true_type{}, j + 5);
+                    if constexpr (S > 6) process(std::integral_constant<int, 6 % S>{}, std::true_type{}, j + 6);
+                    if constexpr (S > 7) process(std::integral_constant<int, 7 % S>{}, std::true_type{}, j + 7);
                 }
                 // the last n_fast % S tiles are already in their register sets: no more loads
+                static_assert(S <= 8, "the loop above is written out for at most 8 register sets");
                 if constexpr (S > 1) {
                     if (j < n_fast) process(std::integral_constant<int, 0>{}, std::false_type{}, j);
+                }
+                if constexpr (S > 2) {
                     if (j + 1 < n_fast) process(std::integral_constant<int, 1 % S>{}, std::false_type{}, j + 1);
                 }
                 if constexpr (S > 3) {
                     if (j + 2 < n_fast) process(std::integral_constant<int, 2 % S>{}, std::false_type{}, j + 2);
+                }
+                if constexpr (S > 4) {
+                    if (j + 3 < n_fast) process(std::integral_constant<int, 3 % S>{}, std::false_type{}, j + 3);
+                }
+                if constexpr (S > 5) {
+                    if (j + 4 < n_fast) process(std::integral_constant<int, 4 % S>{}, std::false_type{}, j + 4);
+                }
+                if constexpr (S > 6) {
+                    if (j + 5 < n_fast) process(std::integral_constant<int, 5 % S>{}, std::false_type{}, j + 5);
+                }
+                if constexpr (S > 7) {
+                    if (j + 6 < n_fast) process(std::integral_constant<int, 6 % S>{}, std::false_type{}, j + 6);
                 }
             }
             // whatever is left of the piece, one tile at a time through register set 0
