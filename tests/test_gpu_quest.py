@@ -81,6 +81,8 @@ def _check_attend_selected(pair, layer, seqs, q, sel, cnt, scale):
     (wg.BF16, 32, 8, 128, 16, 256, 6000, 128),      # the paper's budget: 2048 KVs = 128 pages of 16
     (wg.BF16, 4, 4, 64, 32, 64, 700, 5),            # pages larger than a tile, group of one
     (wg.F32, 8, 1, 128, 2, 4, 150, 1000),           # budget larger than the cache: everything is read
+    (wg.F32, 8, 2, 64, 1, 4, 3000, 40),             # more than 2048 pages per head: three turns of the block over the scores
+    (wg.BF16, 8, 2, 128, 4, 16, 7000, 33),          # between 1024 and 2048 pages per head: two turns
 ])
 def test_quest_select_and_attend(dtype, Hq, Hk, d, P, W, T, budget):
     rng = np.random.default_rng(T + budget)
