@@ -37,7 +37,8 @@ def log(*a):
 
 
 class HipEvents:
-    """Raw HIP events (the library records them around its main attention kernel)."""
+    """Raw HIP events (the library hands them to the launch of its decode attention kernel, whose begin and
+    end time stamps they take, or records them before and after its prefill attention kernels)."""
 
     def __init__(self, n):
         self.hip = C.CDLL("libamdhip64.so")
@@ -86,9 +87,9 @@ def main():
     ap.add_argument("--workload", default="llama8b_32layer_b8_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-every", type=int, default=8, metavar="N",
-                    help="HIP events go around every N-th launch of the attention kernel, rotating over the layers "
-                         "(a pair of event records costs about 3 us of GPU time, which would add 6 %% to the step "
-                         "if every launch carried one)")
+                    help="a pair of HIP events goes with every N-th launch of the attention kernel, rotating over the "
+                         "layers (a timed launch costs a few us of GPU time more than an untimed one, which would add "
+                         "several per cent to the step if every launch carried a pair)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the per-kernel HIP events (roofline.achieved becomes null)")
     ap.add_argument("--ctx-scale", type=float, default=1.0, help="shrink contexts (debugging only)")
