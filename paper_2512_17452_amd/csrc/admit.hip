@@ -211,13 +211,6 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(View pv, Cal
 
 constexpr int kScatterBatch = 8;  // rows a thread has in flight in the copy loop
 
-// Rows that are copied are read once: non-temporal loads stream faster on this machine.
-typedef unsigned admit_u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 ld_once(const char *p) {
-    const admit_u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const admit_u32x4_t *>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
 // The copy is a chain of round trips if done row by row (page id, then the row, then the
 // store), so the destination page ids of the block go to LDS once (its rows land in one
 // contiguous range of the global cache) and a thread requests 8 rows before it stores any.
@@ -291,7 +284,7 @@ __global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs 
         const char *k0, *k1, *k2, *k3, *k4, *k5, *k6, *k7, *v0, *v1, *v2, *v3, *v4, *v5, *v6, *v7;
         src_of(r0, k0, v0); src_of(r0 + rp, k1, v1); src_of(r0 + 2 * rp, k2, v2); src_of(r0 + 3 * rp, k3, v3);
         src_of(r0 + 4 * rp, k4, v4); src_of(r0 + 5 * rp, k5, v5); src_of(r0 + 6 * rp, k6, v6); src_of(r0 + 7 * rp, k7, v7);
-#define WGKV_LD(p) ld_once((p) + sub16)
+#define WGKV_LD(p) load_once16((p) + sub16)
         const uint4 a0 = WGKV_LD(k0), b0 = WGKV_LD(v0), a1 = WGKV_LD(k1), b1 = WGKV_LD(v1), a2 = WGKV_LD(k2),
                     b2 = WGKV_LD(v2), a3 = WGKV_LD(k3), b3 = WGKV_LD(v3), a4 = WGKV_LD(k4), b4 = WGKV_LD(v4),
                     a5 = WGKV_LD(k5), b5 = WGKV_LD(v5), a6 = WGKV_LD(k6), b6 = WGKV_LD(v6), a7 = WGKV_LD(k7),

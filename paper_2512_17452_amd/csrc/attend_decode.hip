@@ -122,14 +122,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t part_rsrc(float *p, uint32_t b
     return __builtin_amdgcn_make_buffer_rsrc(p, 0, (int)bytes, 0x00020000);  // raw buffer, 32-bit data format
 }
 
-// K and V rows are read once per launch and never again before they have left every cache:
-// the loads carry the non-temporal hint, which on this machine streams 8-10 % faster than
-// plain loads (a read-only test kernel of the same launch shape: 6.9 instead of 6.2 TB/s).
-__device__ __forceinline__ uint4 ld_stream(const char *p) {
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
 template <int DT, int D, int G>
 __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, AttendArgs a) {
     constexpr int ES = Elem<DT>::es;
@@ -303,7 +295,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                             x[r * 4 + g] = d;
                         }
                         __builtin_amdgcn_sched_barrier(0);
-                        if constexpr (REFILL) kb[ST][r] = ld_stream(rowp[r]);
+                        if constexpr (REFILL) kb[ST][r] = load_once16(rowp[r]);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     // ---- reduce-scatter over the 16 lanes of the row group: lane `sub`
@@ -386,8 +378,8 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                             }
                             __builtin_amdgcn_sched_barrier(0);
                             if constexpr (REFILL) {
-                                vb[ST][2 * i] = ld_stream(rowp[2 * i] + pv.v_off);
-                                vb[ST][2 * i + 1] = ld_stream(rowp[2 * i + 1] + pv.v_off);
+                                vb[ST][2 * i] = load_once16(rowp[2 * i] + pv.v_off);
+                                vb[ST][2 * i + 1] = load_once16(rowp[2 * i + 1] + pv.v_off);
                             }
                             __builtin_amdgcn_sched_barrier(0);
                         }
@@ -405,7 +397,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
 #pragma unroll
                                 for (int g = 0; g < 4; g++) acc[g][e] = fmaf(pg[g], __uint_as_float(vw[e]), acc[g][e]);
                             __builtin_amdgcn_sched_barrier(0);
-                            if constexpr (REFILL) vb[ST][r] = ld_stream(rowp[r] + pv.v_off);
+                            if constexpr (REFILL) vb[ST][r] = load_once16(rowp[r] + pv.v_off);
                             __builtin_amdgcn_sched_barrier(0);
                         }
                         __builtin_amdgcn_wave_barrier();
@@ -434,7 +426,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                     __builtin_amdgcn_sched_barrier(0);  // the K registers are free from here on
                     if constexpr (REFILL) {
 #pragma unroll
-                        for (int r = 0; r < RPT; r++) kb[ST][r] = ld_stream(rowp[r]);
+                        for (int r = 0; r < RPT; r++) kb[ST][r] = load_once16(rowp[r]);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                     // ---- online softmax per query head, one rescale per tile ----
@@ -481,7 +473,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                     __builtin_amdgcn_sched_barrier(0);  // the V registers are free from here on
                     if constexpr (REFILL) {
 #pragma unroll
-                        for (int r = 0; r < RPT; r++) vb[ST][r] = ld_stream(rowp[r] + pv.v_off);
+                        for (int r = 0; r < RPT; r++) vb[ST][r] = load_once16(rowp[r] + pv.v_off);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -495,9 +487,9 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                     const char *rowp[RPT];
                     tile_rows(st, rowp);
 #pragma unroll
-                    for (int r = 0; r < RPT; r++) kb[st][r] = ld_stream(rowp[r]);
+                    for (int r = 0; r < RPT; r++) kb[st][r] = load_once16(rowp[r]);
 #pragma unroll
-                    for (int r = 0; r < RPT; r++) vb[st][r] = ld_stream(rowp[r] + pv.v_off);
+                    for (int r = 0; r < RPT; r++) vb[st][r] = load_once16(rowp[r] + pv.v_off);
                 }
                 // Main loop: S tiles per trip, straight-line, so that every wait is for exactly
                 // the load that is needed and the younger ones stay in flight.
@@ -541,9 +533,9 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                 const char *rowp[RPT];
                 tile_rows_any(j, rowp);
 #pragma unroll
-                for (int r = 0; r < RPT; r++) kb[0][r] = ld_stream(rowp[r]);
+                for (int r = 0; r < RPT; r++) kb[0][r] = load_once16(rowp[r]);
 #pragma unroll
-                for (int r = 0; r < RPT; r++) vb[0][r] = ld_stream(rowp[r] + pv.v_off);
+                for (int r = 0; r < RPT; r++) vb[0][r] = load_once16(rowp[r] + pv.v_off);
                 process(std::integral_constant<int, 0>{}, std::false_type{}, j);
             }
             cur += n;

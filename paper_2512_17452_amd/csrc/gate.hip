@@ -7,7 +7,6 @@
 namespace wgkv {
 
 typedef __attribute__((ext_vector_type(2))) __bf16 gate_bf16x2_t;
-typedef unsigned gate_u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kGateRows = 4;         // rows per wave
 constexpr int kGateWaves = 8;        // waves per block
@@ -67,9 +66,7 @@ __global__ __launch_bounds__(kGateWaves * 64) void gate_linear_kernel(const char
 #pragma unroll
         for (int r = 0; r < kGateRows; r++) {
             const bool ok = okc && row0 + r < T;
-            // read once: the non-temporal hint streams faster than a plain load on this machine
-            const gate_u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const gate_u32x4_t *>(
-                ok ? hidden + (size_t)(row0 + r) * row_bytes + (size_t)cw * 16 : hidden));
+            const uint4 v = load_once16(ok ? hidden + (size_t)(row0 + r) * row_bytes + (size_t)cw * 16 : hidden);
             dst[r] = make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
         }
     };
