@@ -73,7 +73,28 @@ __device__ __forceinline__ int ceil_tiles(int n) { return (n + kTile - 1) / kTil
 
 // tiles of every unit -> exclusive prefix in s_ts[0..n_units]
 __device__ __forceinline__ void build_tile_prefix(const View &pv, const AttendArgs &a, int n_units,
-                                                  int *s_ts, int *s_tmp) {
+                                                  int *s_ts, int *s_tmp, int *s_gl, int *s_nl) {
+    if (n_units <= 64) {  // one wave does it: a scan inside the wave, one barrier
+        if (threadIdx.x < 64) {
+            const int u = threadIdx.x;
+            int tiles = 0;
+            if (u < n_units) {
+                const int b = u / pv.Hkv, h = u % pv.Hkv, sid = a.sid[b];
+                const int t = pv.seq_len[sid * pv.L + a.layer];
+                const int gl_all = pv.global_len[unit_meta(pv, sid, a.layer, h)];
+                const int gl = global_tokens(pv, a, u, gl_all);
+                s_gl[u] = gl_all;
+                s_nl[u] = min(t, pv.W);
+                tiles = ceil_tiles(gl) + ceil_tiles(min(t, pv.W));
+                if (tiles > 0) tiles += kUnitStartTiles;
+            }
+            const int inc = wave_incl_scan(tiles, u);
+            if (u < n_units) s_ts[u] = inc - tiles;
+            if (u == 63) s_ts[n_units] = inc;
+        }
+        __syncthreads();
+        return;
+    }
     int carry = 0;
     for (int u0 = 0; u0 < n_units; u0 += kAttnThreads) {
         const int u = u0 + threadIdx.x;
@@ -81,7 +102,10 @@ __device__ __forceinline__ void build_tile_prefix(const View &pv, const AttendAr
         if (u < n_units) {
             const int b = u / pv.Hkv, h = u % pv.Hkv, sid = a.sid[b];
             const int t = pv.seq_len[sid * pv.L + a.layer];
-            const int gl = global_tokens(pv, a, u, pv.global_len[unit_meta(pv, sid, a.layer, h)]);
+            const int gl_all = pv.global_len[unit_meta(pv, sid, a.layer, h)];
+            const int gl = global_tokens(pv, a, u, gl_all);
+            s_gl[u] = gl_all;
+            s_nl[u] = min(t, pv.W);
             tiles = ceil_tiles(gl) + ceil_tiles(min(t, pv.W));
             if (tiles > 0) tiles += kUnitStartTiles;
         }
@@ -139,12 +163,14 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
     constexpr int S = FAST ? kStagesFast : 1;  // register sets = tiles in flight
 
     __shared__ int s_ts[kMaxCallUnits + 1];
+    __shared__ int s_gl[kMaxCallUnits];  // entries in the unit's global cache
+    __shared__ int s_nl[kMaxCallUnits];  // tokens in its ring
     __shared__ int s_tmp[20];
     __shared__ float s_p[kAttnWaves][64];          // fp32 weights of a tile (fp32 pool)
     __shared__ uint32_t s_pk[kAttnWaves][4][2][4]; // bf16 weight pairs of a tile: [row group][row pair][head]
 
     const int n_units = a.n_seqs * pv.Hkv;
-    build_tile_prefix(pv, a, n_units, s_ts, s_tmp);
+    build_tile_prefix(pv, a, n_units, s_ts, s_tmp, s_gl, s_nl);
     const int total = s_ts[n_units];
     if (blockIdx.x == 0) {  // units with nothing cached: the output is defined as zero
         for (int uu = 0; uu < n_units; uu++)
@@ -195,9 +221,9 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
         }
         const int b = u / pv.Hkv, h = u % pv.Hkv, sid = a.sid[b];
         const int um = unit_meta(pv, sid, a.layer, h);
-        const int gl_all = pv.global_len[um];
+        const int gl_all = s_gl[u];
         const int gl = global_tokens(pv, a, u, gl_all);
-        const int nloc = min(pv.seq_len[sid * pv.L + a.layer], pv.W);
+        const int nloc = s_nl[u];
         const int n_gt = ceil_tiles(gl);
 
         // this lane's slice of the G query rows

@@ -134,13 +134,24 @@ __device__ __forceinline__ float group_sum(float x) {
     return x;
 }
 
+// Inclusive prefix over the 64 lanes, in the vector unit (DPP) instead of six trips through the
+// LDS crossbar: sums of 4 from the original values (row_shr 1, 2, 3; lanes shifted in from
+// outside a row of 16 read zero), then of 8 and 16 inside the row, then lane 15 of the row before
+// into rows 1 and 3 (row_bcast15) and lane 31 into rows 2 and 3 (row_bcast31).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_masked_i(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xf, true);
+}
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int n = __shfl_up(v, o);
-        if (lane >= o) v += n;
-    }
-    return v;
+    (void)lane;
+    int t = v + dpp_masked_i<0x111, 0xf>(v);
+    t += dpp_masked_i<0x112, 0xf>(v);
+    t += dpp_masked_i<0x113, 0xf>(v);
+    t += dpp_masked_i<0x114, 0xf>(t);
+    t += dpp_masked_i<0x118, 0xf>(t);
+    t += dpp_masked_i<0x142, 0xa>(t);
+    t += dpp_masked_i<0x143, 0xc>(t);
+    return t;
 }
 
 // Exclusive prefix over the values of one 256- or 1024-thread block.  s_tmp: >= 17 ints.
