@@ -573,20 +573,23 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
             m[0] = dpp_f<0x00>(m1); m[1] = dpp_f<0x55>(m1); m[2] = dpp_f<0xAA>(m1); m[3] = dpp_f<0xFF>(m1);
             l[0] = dpp_f<0x00>(l1); l[1] = dpp_f<0x55>(l1); l[2] = dpp_f<0xAA>(l1); l[3] = dpp_f<0xFF>(l1);
         }
-#pragma unroll
-        for (int off = LPT; off < 64; off <<= 1) {
+        auto merge_groups = [&](auto off_tag) __attribute__((always_inline)) {
+            constexpr int OFF = decltype(off_tag)::value;
 #pragma unroll
             for (int g = 0; g < G; g++) {
-                const float mo = __shfl_xor(m[g], off), lo_ = __shfl_xor(l[g], off);
+                const float mo = lane_xor<OFF>(m[g], lane), lo_ = lane_xor<OFF>(l[g], lane);
                 const float mn = fmaxf(m[g], mo);
                 const float ms = mn == -INFINITY ? 0.f : mn;
                 const float ca = __builtin_amdgcn_exp2f(m[g] - ms), cb = __builtin_amdgcn_exp2f(mo - ms);
                 l[g] = l[g] * ca + lo_ * cb;
 #pragma unroll
-                for (int e = 0; e < EPL; e++) acc[g][e] = acc[g][e] * ca + __shfl_xor(acc[g][e], off) * cb;
+                for (int e = 0; e < EPL; e++) acc[g][e] = acc[g][e] * ca + lane_xor<OFF>(acc[g][e], lane) * cb;
                 m[g] = mn;
             }
-        }
+        };
+        if constexpr (LPT <= 8) merge_groups(std::integral_constant<int, 8>{});
+        if constexpr (LPT <= 16) merge_groups(std::integral_constant<int, 16>{});
+        merge_groups(std::integral_constant<int, 32>{});
         // waves whose share overlaps this unit
         const int w_first = wave_of(s_ts[u] + kUnitStartTiles), w_last = wave_of(s_ts[u + 1] - 1);
         float *o = a.out + ((size_t)b * pv.Hq + (size_t)h * G) * D;

@@ -117,6 +117,20 @@ __device__ __forceinline__ LanePair swap16(float a, float b) {
     asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
     return {a, b};
 }
+// The value of lane l ^ OFF (OFF = 8, 16 or 32), again without the LDS crossbar.
+template <int OFF>
+__device__ __forceinline__ float lane_xor(float x, int lane) {
+    static_assert(OFF == 8 || OFF == 16 || OFF == 32, "");
+    if constexpr (OFF == 8) {
+        return dpp_f<0x128>(x);  // rotate the row of 16 by 8
+    } else if constexpr (OFF == 16) {
+        const LanePair r = swap16(x, x);
+        return (lane & 16) ? r.a : r.b;
+    } else {
+        const LanePair r = swap32(x, x);
+        return (lane & 32) ? r.a : r.b;
+    }
+}
 __device__ __forceinline__ float sum_xor32(float x) { const LanePair r = swap32(x, x); return r.a + r.b; }
 __device__ __forceinline__ float sum_xor16(float x) { const LanePair r = swap16(x, x); return r.a + r.b; }
 __device__ __forceinline__ float max_xor32(float x) { const LanePair r = swap32(x, x); return fmaxf(r.a, r.b); }
@@ -154,23 +168,25 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
     return t;
 }
 
-// Exclusive prefix over the values of one 256- or 1024-thread block.  s_tmp: >= 17 ints.
-// Returns the exclusive prefix of v for this thread; *total gets the block sum.
+// Exclusive prefix over the values of one block of up to 1024 threads.  s_tmp: >= 16 ints.
+// Returns the exclusive prefix of v for this thread; *total gets the block sum.  Every thread adds
+// up the totals of the waves before its own by itself (at most 16 values, read as a broadcast),
+// so there is no serial pass of one thread and only the two barriers around the hand-over.
 __device__ __forceinline__ int block_excl_scan(int v, int *s_tmp, int *total) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
-    int inc = wave_incl_scan(v, lane);
-    __syncthreads();
+    const int inc = wave_incl_scan(v, lane);
+    __syncthreads();  // s_tmp may still be read from an earlier call
     if (lane == 63) s_tmp[w] = inc;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int i = 0; i < nw; i++) { int x = s_tmp[i]; s_tmp[i] = run; run += x; }
-        s_tmp[16] = run;
+    int before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const int x = i < nw ? s_tmp[i] : 0;
+        before += i < w ? x : 0;
+        all += x;
     }
-    __syncthreads();
-    int res = inc - v + s_tmp[w];
-    *total = s_tmp[16];
-    return res;
+    *total = all;
+    return inc - v + before;
 }
 
 }  // namespace wgkv
