@@ -201,7 +201,10 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
 
     // first unit of the share: the u with s_ts[u] <= T0 < s_ts[u+1]
     int u;
-    {
+    if (n_units <= 64) {  // one comparison per lane: the units whose first tile is at or before T0
+        const bool le = lane < n_units && s_ts[lane] <= T0;  // true for lane 0: s_ts[0] = 0
+        u = __builtin_popcountll(__builtin_amdgcn_ballot_w64(le)) - 1;
+    } else {
         int lo = 0, hi = n_units - 1;
         while (lo < hi) {
             int mid = (lo + hi + 1) >> 1;
