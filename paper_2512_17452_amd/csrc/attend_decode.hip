@@ -73,7 +73,7 @@ __device__ __forceinline__ int ceil_tiles(int n) { return (n + kTile - 1) / kTil
 
 // tiles of every unit -> exclusive prefix in s_ts[0..n_units]
 __device__ __forceinline__ void build_tile_prefix(const View &pv, const AttendArgs &a, int n_units,
-                                                  int *s_ts, int *s_tmp, int *s_gl, int *s_nl) {
+                                                  int *s_ts, int *s_tmp, int *s_gl, int *s_nl, int *s_um) {
     if (n_units <= 64) {  // one wave does it: a scan inside the wave, one barrier
         if (threadIdx.x < 64) {
             const int u = threadIdx.x;
@@ -81,8 +81,10 @@ __device__ __forceinline__ void build_tile_prefix(const View &pv, const AttendAr
             if (u < n_units) {
                 const int b = u / pv.Hkv, h = u % pv.Hkv, sid = a.sid[b];
                 const int t = pv.seq_len[sid * pv.L + a.layer];
-                const int gl_all = pv.global_len[unit_meta(pv, sid, a.layer, h)];
+                const int um = unit_meta(pv, sid, a.layer, h);
+                const int gl_all = pv.global_len[um];
                 const int gl = global_tokens(pv, a, u, gl_all);
+                s_um[u] = um;
                 s_gl[u] = gl_all;
                 s_nl[u] = min(t, pv.W);
                 tiles = ceil_tiles(gl) + ceil_tiles(min(t, pv.W));
@@ -102,8 +104,10 @@ __device__ __forceinline__ void build_tile_prefix(const View &pv, const AttendAr
         if (u < n_units) {
             const int b = u / pv.Hkv, h = u % pv.Hkv, sid = a.sid[b];
             const int t = pv.seq_len[sid * pv.L + a.layer];
-            const int gl_all = pv.global_len[unit_meta(pv, sid, a.layer, h)];
+            const int um = unit_meta(pv, sid, a.layer, h);
+            const int gl_all = pv.global_len[um];
             const int gl = global_tokens(pv, a, u, gl_all);
+            s_um[u] = um;
             s_gl[u] = gl_all;
             s_nl[u] = min(t, pv.W);
             tiles = ceil_tiles(gl) + ceil_tiles(min(t, pv.W));
@@ -165,17 +169,18 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
     __shared__ int s_ts[kMaxCallUnits + 1];
     __shared__ int s_gl[kMaxCallUnits];  // entries in the unit's global cache
     __shared__ int s_nl[kMaxCallUnits];  // tokens in its ring
+    __shared__ int s_um[kMaxCallUnits];  // its index into the per-unit metadata
     __shared__ int s_tmp[20];
     __shared__ float s_p[kAttnWaves][64];          // fp32 weights of a tile (fp32 pool)
     __shared__ uint32_t s_pk[kAttnWaves][4][2][4]; // bf16 weight pairs of a tile: [row group][row pair][head]
 
     const int n_units = a.n_seqs * pv.Hkv;
-    build_tile_prefix(pv, a, n_units, s_ts, s_tmp, s_gl, s_nl);
+    build_tile_prefix(pv, a, n_units, s_ts, s_tmp, s_gl, s_nl, s_um);
     const int total = s_ts[n_units];
     if (blockIdx.x == 0) {  // units with nothing cached: the output is defined as zero
         for (int uu = 0; uu < n_units; uu++)
             if (s_ts[uu + 1] == s_ts[uu]) {
-                float *o = a.out + ((size_t)(uu / pv.Hkv) * pv.Hq + (size_t)(uu % pv.Hkv) * G) * D;
+                float *o = a.out + (size_t)uu * G * D;
                 for (int i = threadIdx.x; i < G * D; i += kAttnThreads) o[i] = 0.f;
             }
     }
@@ -222,8 +227,8 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
             cur = u_begin;
             if (cur >= T1) break;  // the share ends inside the allowance: the next wave begins the unit
         }
-        const int b = u / pv.Hkv, h = u % pv.Hkv, sid = a.sid[b];
-        const int um = unit_meta(pv, sid, a.layer, h);
+        // unit u = (sequence b of the call, kv head h): its query rows are rows u*G .. u*G+G-1 of q and out
+        const int um = s_um[u];
         const int gl_all = s_gl[u];
         const int gl = global_tokens(pv, a, u, gl_all);
         const int nloc = s_nl[u];
@@ -232,7 +237,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
         // this lane's slice of the G query rows
         uint32_t qreg[G][4];
         {
-            const char *qp = a.q + ((size_t)(b * pv.Hq + h * G) * D) * ES + sub * 16;
+            const char *qp = a.q + ((size_t)u * G * D) * ES + sub * 16;
 #pragma unroll
             for (int g = 0; g < G; g++) {
                 const uint4 t4 = *reinterpret_cast<const uint4 *>(qp + (size_t)g * D * ES);
@@ -595,7 +600,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
         merge_groups(std::integral_constant<int, 32>{});
         // waves whose share overlaps this unit
         const int w_first = wave_of(s_ts[u] + kUnitStartTiles), w_last = wave_of(s_ts[u + 1] - 1);
-        float *o = a.out + ((size_t)b * pv.Hq + (size_t)h * G) * D;
+        float *o = a.out + (size_t)u * G * D;
         if (w_first == w_last) {  // the unit lies inside this wave's share
             if (lane < LPT) {
 #pragma unroll
