@@ -61,7 +61,8 @@ enum {
     WGKV_ERR_PT_OVERFLOW = -3,  /* a page-table row could exceed max_global_pages_per_head */
     WGKV_ERR_HIP = -4,          /* a HIP runtime call failed */
     WGKV_ERR_DEVICE_FLAG = -5,  /* the device-side sticky error flag is set */
-    WGKV_ERR_WORKSPACE = -6     /* workspace too small for this call */
+    WGKV_ERR_WORKSPACE = -6,    /* workspace too small for this call */
+    WGKV_ERR_HOST_MEMORY = -7   /* the host handle could not be allocated */
 };
 
 #define WGKV_MAX_CALL_SEQS 128  /* sequences per call */
@@ -116,7 +117,8 @@ int wgkv_init_pool(const wgkv_config *cfg, void *pool_dev, size_t pool_bytes, vo
  * chunked-prefill workload): g[t][h] = sigmoid(w[h] . hidden[t]).
  *   hidden_dev [n_tokens][hidden_dim], gate_w_dev [n_kv_heads][hidden_dim], both of
  *   `dtype`; g_out_dev float [n_tokens][n_kv_heads]; fp32 accumulation.
- * hidden_dim must be a multiple of 8. */
+ * hidden_dim must be a multiple of 8, n_kv_heads at most 16, both matrices 16-byte aligned
+ * (INVALID_ARG otherwise). */
 int wgkv_gate_scores(int32_t dtype, int64_t n_tokens, int32_t hidden_dim, int32_t n_kv_heads,
                      const void *hidden_dev, const void *gate_w_dev, float *g_out_dev,
                      wgkv_stream stream);
@@ -210,6 +212,8 @@ int wgkv_gate_mlp_scores(int32_t dtype, int64_t n_tokens, int32_t n_kv_heads, in
  *   g_dev        : float [sum T][n_kv_heads] scores, or NULL to compute them from
  *                  hidden_dev [sum T][hidden_dim] and gate_w_dev (see wgkv_gate_scores)
  *   admit_mask_out_dev : optional uint8 [sum T][n_kv_heads], 1(g >= tau)
+ * The gate form (g_dev == NULL) has the limits of wgkv_gate_scores: at most 16 kv heads,
+ * hidden_dim a multiple of 8, hidden_dev and gate_w_dev 16-byte aligned.
  * Errors: INVALID_ARG, OUT_OF_PAGES / PT_OVERFLOW (from host-side worst-case
  * bounds: every leaving token counted as admitted; wgkv_status tightens them),
  * WORKSPACE, HIP. */
@@ -349,9 +353,18 @@ int wgkv_free_seq(wgkv_pool *pool, int32_t seq_id, wgkv_stream stream);
 
 /* Synchronises the stream, reads free_top, the error flag, all token counts and all
  * global lengths back, and replaces the host-side bookkeeping (worst-case bounds, token
- * counts) by the exact values of the device. */
+ * counts) by the exact values of the device.  Returns WGKV_ERR_DEVICE_FLAG when the device
+ * flag is set (the bookkeeping has been refreshed all the same: a device-side refusal
+ * changes no state), else WGKV_OK. */
 int wgkv_status(wgkv_pool *pool, wgkv_stream stream, int64_t *pages_free,
                 int32_t *device_error_flag);
+
+/* Sec. 4.1 pool.  Clears the sticky device error flag, in stream order (one small kernel, so
+ * the call may also be captured).  The flag is set by a kernel that found no free page or a
+ * full page-table row (only replayed graphs get that far: direct calls are refused on the
+ * host) and left all state as it was; once pages are back (wgkv_free_seq, wgkv_evict_apply)
+ * the pool is usable again after this call and a wgkv_status.  Errors: INVALID_ARG, HIP. */
+int wgkv_clear_error(wgkv_pool *pool, wgkv_stream stream);
 
 /* Measurement aid: when both are non-NULL hipEvent_t handles, every later
  * wgkv_attend times its main attention kernel on the call's stream.  The decode

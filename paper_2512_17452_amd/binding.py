@@ -14,11 +14,11 @@ EXPORTED_SYMBOLS = [
     "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
     "wgkv_quest_select", "wgkv_attend_selected", "wgkv_soft_attn_forward", "wgkv_soft_attn_workspace_bytes",
     "wgkv_soft_attn_backward", "wgkv_sparsity_loss", "wgkv_free_seq",
-    "wgkv_status", "wgkv_set_profile_events", "wgkv_destroy",
+    "wgkv_status", "wgkv_clear_error", "wgkv_set_profile_events", "wgkv_destroy",
 ]
 
 _ERR = {-1: "invalid argument", -2: "out of pages", -3: "page-table overflow", -4: "HIP error",
-        -5: "device error flag set", -6: "workspace too small"}
+        -5: "device error flag set", -6: "workspace too small", -7: "host out of memory"}
 
 
 class WgkvError(RuntimeError):
@@ -102,6 +102,7 @@ def load_library():
     L.wgkv_evict_apply.argtypes = [vp, i32, i32, pi32, vp, i64, f32, vp, vp, sz, vp]
     L.wgkv_free_seq.argtypes = [vp, i32, vp]
     L.wgkv_status.argtypes = [vp, vp, C.POINTER(i64), C.POINTER(i32)]
+    L.wgkv_clear_error.argtypes = [vp, vp]
     L.wgkv_set_profile_events.argtypes = [vp, vp, vp]
     L.wgkv_destroy.argtypes = [vp]
     L.wgkv_destroy.restype = None
@@ -338,6 +339,9 @@ class Pool:
         if rc not in (0, -5):
             raise WgkvError(rc, "wgkv_status")
         return free.value, flag.value
+
+    def clear_error(self):
+        _check(self.L.wgkv_clear_error(self.h, _stream()), "wgkv_clear_error")
 
     def set_profile_events(self, ev_begin, ev_end):
         """ev_begin/ev_end: raw hipEvent_t handles (ints) or None."""

@@ -459,7 +459,15 @@ __global__ __launch_bounds__(256) void free_seq_kernel(View pv, int sid) {
     if (threadIdx.x == 0) *pv.free_top = top + carry;
 }
 
+// A kernel, not a memset: the call may sit in a captured graph.
+__global__ void clear_error_kernel(View pv) { *pv.err_flag = 0; }
+
 // ---- host-side launchers (called from the C ABI layer) ----
+
+hipError_t launch_clear_error(const View &pv, hipStream_t st) {
+    hipLaunchKernelGGL(clear_error_kernel, dim3(1), dim3(1), 0, st, pv);
+    return hipGetLastError();
+}
 
 hipError_t launch_init(const View &pv, hipStream_t st) {
     hipLaunchKernelGGL(init_kernel, dim3(4096), dim3(256), 0, st, pv);

@@ -39,7 +39,6 @@ constexpr int kUnitStartTiles = 12;
 // 4-5 % slower than the even one: the waves of an odd block get this many thousandths fewer
 // tiles, those of the even block before it as many more (flat optimum between 40 and 60).
 constexpr int kOddXcdSkewPermille = 40;
-
 struct AttendArgs {
     int layer;
     int n_seqs;
@@ -217,8 +216,6 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
         }
         u = lo;
     }
-    const uint32_t lane_off = (uint32_t)(grp * ROWB + sub * 16);
-
     int cur = T0;
     while (cur < T1) {
         while (s_ts[u + 1] <= cur) u++;  // also skips units without tiles
@@ -265,10 +262,11 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                                         : pv.local_pt + (size_t)um * pv.nlp;
             // A tile inside one page (P >= 16) needs one page id for the whole wave:
             // lane i keeps the page id of tile k0+i and the base address goes through
-            // scalar registers.  Rows of a partly filled last tile beyond the last token
-            // are read too (finite: the pool is zeroed at start-up and only ever holds K/V
-            // rows) and get weight zero.  With pages smaller than a tile every tile is
-            // handled one at a time with a page lookup per row.
+            // scalar registers.  In a partly filled last tile the rows beyond the last token
+            // read the last valid row again and get weight zero: nothing that is not a cached
+            // row of this head is ever read (a recycled page keeps whatever its last owner
+            // left in it, which need not be finite).  With pages smaller than a tile every
+            // tile is handled one at a time with a page lookup per row.
             // page id of the vp-th page of the region as this call reads it (with a selection: the
             // vp-th selected page; an index outside the table is clamped, never followed)
             const int32_t *sel = (is_glob && a.sel_pages) ? a.sel_pages + (size_t)u * a.sel_stride : nullptr;
@@ -285,8 +283,10 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                 const int k = k0 + j;
                 const int page = __builtin_amdgcn_readlane(ptreg, j);
                 const char *base = page_ptr(pv, page) + (size_t)((k * kTile) & (pv.P - 1)) * ROWB;
+                const int last_row = count - 1 - k * kTile;  // wave-uniform; >= kTile - 1 except in the last tile
 #pragma unroll
-                for (int r = 0; r < RPT; r++) rowp[r] = base + (lane_off + (uint32_t)(r * TPW * ROWB));
+                for (int r = 0; r < RPT; r++)
+                    rowp[r] = base + ((uint32_t)min(grp + r * TPW, last_row) * ROWB + (uint32_t)(sub * 16));
             };
             // Row addresses of any tile, one page lookup per row.
             auto tile_rows_any = [&](int j, const char *(&rowp)[RPT]) {
@@ -650,12 +650,23 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                     }
                 }
             }
-            // the partial must have reached device-coherent memory before the count moves
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            // The folding wave usually sits on another compute unit, often on another XCD, so the
+            // partial must be complete at device scope before the count moves.  The stores above
+            // carry the device-scope policy (written through, not left dirty in this XCD's L2), and
+            // on this architecture vmcnt counts stores until they are acknowledged at their scope:
+            // the wave waits for all of them here, then issues the increment.  (An agent-scope
+            // release fence says the same in the language's terms, but it also writes back the
+            // whole L2 in front of the wait, and its acquire twin invalidates it: measured 117.5
+            // instead of 86.6 us per launch on the 128K workload.)
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             int prev = 0;
             if (lane == 0) prev = __hip_atomic_fetch_add(&a.counters[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             prev = __builtin_amdgcn_readfirstlane(prev);
             if (prev == w_last - w_first) {  // every other wave of this unit is done: fold
+                // The loads below are issued after the count has come back (the branch depends on
+                // it) and bypass the caches that are not coherent at device scope; the compiler
+                // must not move them in front of the atomic either.
+                asm volatile("" ::: "memory");
                 float Mx[GT], Ls[GT], A[GT][EPL];
 #pragma unroll
                 for (int t = 0; t < GT; t++) {

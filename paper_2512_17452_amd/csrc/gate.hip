@@ -137,10 +137,17 @@ __global__ __launch_bounds__(kGateWaves * 64) void gate_linear_kernel(const char
 
 hipError_t launch_gate_linear(int dtype, int64_t n_tokens, int hidden_dim, int n_kv_heads,
                               const void *hidden, const void *w, float *g_out, hipStream_t st) {
-    int dev = 0, n_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
-        return hipErrorInvalidDevice;
+    // compute units of each device, asked for once
+    static int n_cu_of[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (n_cu_of[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            return hipErrorInvalidDevice;
+        n_cu_of[dev] = n;
+    }
+    const int n_cu = n_cu_of[dev];
     const int64_t rows_per_block = kGateWaves * kGateRows;
     const int64_t want = (n_tokens + rows_per_block - 1) / rows_per_block;
     const unsigned grid = (unsigned)(want < n_cu ? want : n_cu);

@@ -20,6 +20,7 @@ hipError_t launch_decode_step(const View &pv, const CallSeqs &cs, int layer, flo
                               const void *k, const void *v, const float *g, uint8_t *promoted_out,
                               hipStream_t st);
 hipError_t launch_free_seq(const View &pv, int sid, hipStream_t st);
+hipError_t launch_clear_error(const View &pv, hipStream_t st);
 size_t evict_ws_bytes(int n_units);
 size_t evict_scores_ws_bytes(const View &pv, int n_units, int n_obs);
 hipError_t launch_evict_scores(const View &pv, const CallSeqs &cs, int layer, const void *q_obs, int n_obs,
@@ -218,14 +219,19 @@ int wgkv_init_pool(const wgkv_config *cfg, void *pool_dev, size_t pool_bytes, vo
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
         return WGKV_ERR_HIP;
     wgkv_pool *p = new (std::nothrow) wgkv_pool();
-    if (!p) return WGKV_ERR_INVALID_ARG;
+    if (!p) return WGKV_ERR_HOST_MEMORY;
     p->cfg = *cfg;
     p->view = v;
     p->lay = lay;
     const size_t n_sl = (size_t)cfg->max_seqs * cfg->n_layers;
-    p->seq_len_h.assign(n_sl, 0);
-    p->touched_h.assign(n_sl, 0);
-    p->g_ub.assign(n_sl * cfg->n_kv_heads, 0);
+    try {
+        p->seq_len_h.assign(n_sl, 0);
+        p->touched_h.assign(n_sl, 0);
+        p->g_ub.assign(n_sl * cfg->n_kv_heads, 0);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return WGKV_ERR_HOST_MEMORY;
+    }
     p->pages_ub = 0;
     p->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
     p->ev0 = p->ev1 = nullptr;
@@ -265,7 +271,7 @@ int wgkv_gate_scores(int32_t dtype, int64_t n_tokens, int32_t hidden_dim, int32_
                      wgkv_stream stream) {
     if ((dtype != WGKV_F32 && dtype != WGKV_BF16) || n_tokens < 0 || hidden_dim < 8 ||
         (hidden_dim % 8) || n_kv_heads < 1 || n_kv_heads > 16 || !hidden_dev || !gate_w_dev ||
-        !g_out_dev)
+        !g_out_dev || (((uintptr_t)hidden_dev | (uintptr_t)gate_w_dev) & 15) != 0)
         return WGKV_ERR_INVALID_ARG;
     if (n_tokens == 0) return WGKV_OK;
     return launch_gate_linear(dtype, n_tokens, hidden_dim, n_kv_heads, hidden_dev, gate_w_dev,
@@ -399,7 +405,10 @@ int wgkv_prefill_admit(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_
     }
     if (total == 0) return WGKV_OK;
     if (!k_dev || !v_dev) return WGKV_ERR_INVALID_ARG;
-    if (!g_dev && (!hidden_dev || !gate_w_dev || hidden_dim < 8 || (hidden_dim % 8))) return WGKV_ERR_INVALID_ARG;
+    // scores from the linear gate: the same limits as wgkv_gate_scores (at most 16 kv heads, 16-byte rows)
+    if (!g_dev && (!hidden_dev || !gate_w_dev || hidden_dim < 8 || (hidden_dim % 8) || H > 16 ||
+                   (((uintptr_t)hidden_dev | (uintptr_t)gate_w_dev) & 15) != 0))
+        return WGKV_ERR_INVALID_ARG;
     const PrefillWs ws = prefill_ws(&c, n_seqs, total, max_T);
     if (workspace_bytes < ws.total) return WGKV_ERR_WORKSPACE;
     // worst case for the page bounds: every token that leaves the window is admitted
@@ -498,6 +507,7 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
     int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
     if (rc) return rc;
     if (!n_q_host || !q_dev || !out_dev || !workspace_dev || !std::isfinite(scale)) return WGKV_ERR_INVALID_ARG;
+    if ((((uintptr_t)q_dev | (uintptr_t)out_dev | (uintptr_t)workspace_dev) & 15) != 0) return WGKV_ERR_INVALID_ARG;
     const bool prefill = k_chunk_dev != nullptr;
     if (prefill != (v_chunk_dev != nullptr) || prefill != (g_chunk_dev != nullptr)) return WGKV_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
@@ -716,7 +726,6 @@ int wgkv_status(wgkv_pool *p, wgkv_stream stream, int64_t *pages_free, int32_t *
         return WGKV_ERR_HIP;
     if (pages_free) *pages_free = top;
     if (device_error_flag) *device_error_flag = flag;
-    if (flag != 0) return WGKV_ERR_DEVICE_FLAG;
     const wgkv_config &c = p->cfg;
     int64_t used = 0;
     for (size_t sl = 0; sl < p->touched_h.size(); sl++) {
@@ -732,7 +741,13 @@ int wgkv_status(wgkv_pool *p, wgkv_stream stream, int64_t *pages_free, int32_t *
         }
     }
     p->pages_ub = used;
-    return WGKV_OK;
+    // the mirrors are exact again whatever the flag says: a call that set it changed nothing
+    return flag != 0 ? WGKV_ERR_DEVICE_FLAG : WGKV_OK;
+}
+
+int wgkv_clear_error(wgkv_pool *p, wgkv_stream stream) {
+    if (!p) return WGKV_ERR_INVALID_ARG;
+    return launch_clear_error(p->view, (hipStream_t)stream) == hipSuccess ? WGKV_OK : WGKV_ERR_HIP;
 }
 
 }  // extern "C"
