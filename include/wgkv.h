@@ -261,6 +261,26 @@ int wgkv_attend(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *s
                 const void *v_chunk_dev, const float *g_chunk_dev, float tau, float scale,
                 float *out_dev, void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
 
+/* For callers that cannot allocate or pass a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the decode form of wgkv_attend, same
+ * arguments and same result, with the split-K partial results kept in an array of
+ * WGKV_STATIC_SCRATCH_BYTES bytes that is part of the library's device image instead of in a
+ * workspace.  Every GPU the library is loaded on holds its own copy until the process ends;
+ * its address is looked up once per device by wgkv_init_pool.  The call allocates and frees
+ * nothing and asks the runtime for nothing but the current device and the launch.
+ *   q_dev [n_seqs][n_q_heads][head_dim] of cfg.dtype, out_dev float [n_seqs][n_q_heads][head_dim]
+ * The launch uses at most 512 blocks, and the partials of that many blocks plus one per
+ * (sequence, kv head) must fit: (2048 + n_seqs * n_kv_heads) * group * (head_dim + 2) * 4 bytes
+ * (+ 256) <= WGKV_STATIC_SCRATCH_BYTES, else WGKV_ERR_WORKSPACE (every shape with group *
+ * head_dim <= 512 fits at the largest call; use wgkv_attend otherwise).  Nothing in the array
+ * has to start at zero (a partial is written before the count that announces it moves).  All
+ * calls on one GPU share the array: two such calls that overlap in time on the same GPU, on
+ * different streams or pools, race; calls in stream order do not.
+ * Errors: INVALID_ARG, WORKSPACE, HIP (also: no pool was initialised on the current device). */
+#define WGKV_STATIC_SCRATCH_BYTES (8u << 20)
+int wgkv_attend_decode_static(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                              const void *q_dev, float scale, float *out_dev, wgkv_stream stream);
+
 /* ---- read-time page selection over the admitted cache ----
  * Appendix "Synergy with KV Selection": Quest-style selection with key landmarks (the
  * per-page minimum and maximum key vectors) at a budget of so many KVs per query.  The

@@ -11,7 +11,7 @@ F32, BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
-    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
+    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_attend_decode_static", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
     "wgkv_quest_select", "wgkv_attend_selected", "wgkv_soft_attn_forward", "wgkv_soft_attn_workspace_bytes",
     "wgkv_soft_attn_backward", "wgkv_sparsity_loss", "wgkv_free_seq",
     "wgkv_status", "wgkv_clear_error", "wgkv_set_profile_events", "wgkv_destroy",
@@ -94,6 +94,7 @@ def load_library():
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
+    L.wgkv_attend_decode_static.argtypes = [vp, i32, i32, pi32, vp, f32, vp, vp]
     L.wgkv_quest_landmark_bytes.argtypes = [C.POINTER(_CConfig), C.POINTER(sz)]
     L.wgkv_quest_update.argtypes = [vp, i32, i32, pi32, vp, sz, i32, vp]
     L.wgkv_quest_select.argtypes = [vp, i32, i32, pi32, vp, vp, sz, i32, vp, i64, vp, vp, vp]
@@ -276,6 +277,12 @@ class Pool:
         _check(self.L.wgkv_attend(self.h, layer, len(seq_ids), _ids(seq_ids), _ids(n_q), _ptr(q),
                                   _ptr(k_chunk), _ptr(v_chunk), _ptr(g_chunk), tau, scale, _ptr(out),
                                   _ptr(self.workspace), self.workspace.numel(), _stream()), "wgkv_attend")
+        return out
+
+    def attend_decode_static(self, layer, seq_ids, q, out, scale):
+        """wgkv_attend_decode_static: decode attention without a workspace argument."""
+        _check(self.L.wgkv_attend_decode_static(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(q), scale,
+                                                _ptr(out), _stream()), "wgkv_attend_decode_static")
         return out
 
     def quest_landmarks(self):

@@ -781,6 +781,54 @@ size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid_max) {
     return b;
 }
 
+// ---- scratch for callers that bring no workspace ----
+// One array per GPU, part of the loaded code object: it exists from the moment the library is
+// loaded on a device until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; the address that kernels and copies use is the one that call returns,
+// looked up once per device while that device is current.
+static __device__ __align__(256) unsigned char scratch[WGKV_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, NULL = not looked up yet
+
+hipError_t static_scratch_init() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (g_scratch_ptr[dev]) return hipSuccess;
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+    return hipSuccess;
+}
+
+// The current device's scratch array, or NULL when static_scratch_init has not run on it.
+void *static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    return g_scratch_ptr[dev];
+}
+
+// Fills the occupancy cache of the pool's instantiation, so that no later launch asks the runtime.
+template <int DT, int D>
+static void warm_g(int G) {
+    switch (G) {
+        case 1: resident_blocks_per_cu<DT, D, 1>(); break;
+        case 2: resident_blocks_per_cu<DT, D, 2>(); break;
+        case 4: resident_blocks_per_cu<DT, D, 4>(); break;
+        case 8: resident_blocks_per_cu<DT, D, 8>(); break;
+        default: break;
+    }
+}
+void attend_decode_warm(const View &pv) {
+    if (pv.dtype == WGKV_BF16 && pv.d == 128) warm_g<WGKV_BF16, 128>(pv.G);
+    if (pv.dtype == WGKV_BF16 && pv.d == 64) warm_g<WGKV_BF16, 64>(pv.G);
+    if (pv.dtype == WGKV_F32 && pv.d == 128) warm_g<WGKV_F32, 128>(pv.G);
+    if (pv.dtype == WGKV_F32 && pv.d == 64) warm_g<WGKV_F32, 64>(pv.G);
+}
+
 hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int32_t *sids,
                                 const void *q, float scale, float *out, void *ws, int32_t *counters,
                                 int n_cu, int grid_max, int min_tpw, hipStream_t st, hipEvent_t ev0,

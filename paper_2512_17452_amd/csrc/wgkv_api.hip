@@ -35,6 +35,9 @@ hipError_t launch_quest_select(const View &pv, const CallSeqs &cs, int layer, co
                                int budget_pages, float *scores, int64_t score_stride, int32_t *sel_pages,
                                int32_t *sel_count, int64_t max_pages, hipStream_t st);
 size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid);
+hipError_t static_scratch_init();
+void *static_scratch();
+void attend_decode_warm(const View &pv);
 hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int32_t *sids,
                                 const void *q, float scale, float *out, void *ws, int32_t *counters,
                                 int n_cu, int grid_max, int min_tpw, hipStream_t st, hipEvent_t ev0,
@@ -69,6 +72,7 @@ namespace {
 constexpr int kPrefillBlkHost = 512;    // must match kPrefillBlk in admit.hip
 constexpr int kAttnGridMax = 2048;      // upper bound on the decode-attention grid (blocks of 4 waves)
 constexpr int kAttnMinTilesPerWave = 16;  // below that a share is shorter than the fold of its partial
+constexpr int kAttnStaticGridMax = 512;   // grid bound of the entry point that keeps its partials in the static array
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -235,6 +239,13 @@ int wgkv_init_pool(const wgkv_config *cfg, void *pool_dev, size_t pool_bytes, vo
     p->pages_ub = 0;
     p->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
     p->ev0 = p->ev1 = nullptr;
+    // set-up for wgkv_attend_decode_static: this device's address of the static scratch array and
+    // the launch shape of the pool's attention kernel, so that the call itself asks the runtime nothing
+    if (static_scratch_init() != hipSuccess) {
+        delete p;
+        return WGKV_ERR_HIP;
+    }
+    attend_decode_warm(v);
     if (launch_init(v, (hipStream_t)stream) != hipSuccess) {
         delete p;
         return WGKV_ERR_HIP;
@@ -545,6 +556,23 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
         return WGKV_ERR_HIP;
     if (p->ev1 && hipEventRecord(p->ev1, st) != hipSuccess) return WGKV_ERR_HIP;
     return WGKV_OK;
+}
+
+int wgkv_attend_decode_static(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                              const void *q_dev, float scale, float *out_dev, wgkv_stream stream) {
+    int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    if (!q_dev || !out_dev || !std::isfinite(scale)) return WGKV_ERR_INVALID_ARG;
+    if ((((uintptr_t)q_dev | (uintptr_t)out_dev) & 15) != 0) return WGKV_ERR_INVALID_ARG;
+    if (attend_decode_ws_bytes(p->view, n_seqs, kAttnStaticGridMax) > (size_t)WGKV_STATIC_SCRATCH_BYTES)
+        return WGKV_ERR_WORKSPACE;  // the call is larger than the static array: use wgkv_attend
+    void *ws = static_scratch();
+    if (!ws) return WGKV_ERR_HIP;  // no pool was ever initialised on the current device
+    return launch_attend_decode(p->view, layer, n_seqs, seq_ids_host, q_dev, scale, out_dev, ws,
+                                p->view.unit_counters, p->n_cu, kAttnStaticGridMax, kAttnMinTilesPerWave,
+                                (hipStream_t)stream, p->ev0, p->ev1, nullptr, nullptr, 0) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
 }
 
 int wgkv_quest_landmark_bytes(const wgkv_config *cfg, size_t *landmark_bytes) {
