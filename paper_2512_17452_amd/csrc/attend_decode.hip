@@ -176,13 +176,13 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
     const int n_units = a.n_seqs * pv.Hkv;
     build_tile_prefix(pv, a, n_units, s_ts, s_tmp, s_gl, s_nl, s_um);
     const int total = s_ts[n_units];
-    if (blockIdx.x == 0) {  // units with nothing cached: the output is defined as zero
-        for (int uu = 0; uu < n_units; uu++)
-            if (s_ts[uu + 1] == s_ts[uu]) {
-                float *o = a.out + (size_t)uu * G * D;
-                for (int i = threadIdx.x; i < G * D; i += kAttnThreads) o[i] = 0.f;
-            }
-    }
+    // units with nothing cached: the output is defined as zero (block b looks at units b, b + grid, ...:
+    // one comparison for most blocks, nothing for the rest)
+    for (int uu = blockIdx.x; uu < n_units; uu += gridDim.x)
+        if (s_ts[uu + 1] == s_ts[uu]) {
+            float *o = a.out + (size_t)uu * G * D;
+            for (int i = threadIdx.x; i < G * D; i += kAttnThreads) o[i] = 0.f;
+        }
     // From here on every wave works alone: no block-wide barrier below this line.
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPT, sub = lane % LPT;
@@ -526,40 +526,41 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
                     for (int r = 0; r < RPT; r++) vb[st][r] = load_once16(rowp[r] + pv.v_off);
                 }
                 // Main loop: S tiles per trip, straight-line, so that every wait is for exactly
-                // the load that is needed and the younger ones stay in flight.
+                // the load that is needed and the younger ones stay in flight.  It runs while every
+                // refill is a real tile of the piece.
+                using std::integral_constant;
+                constexpr std::true_type kRefill{};
+                constexpr std::false_type kNoRefill{};
+                static_assert(S == 1 || S == 4, "the loops below are written out for 1 or 4 register sets");
                 int j = 0;
-                for (; j + S <= n_fast; j += S) {
-                    process(std::integral_constant<int, 0>{}, std::true_type{}, j);
-                    if constexpr (S > 1) process(std::integral_constant<int, 1 % S>{}, std::true_type{}, j + 1);
-                    if constexpr (S > 2) process(std::integral_constant<int, 2 % S>{}, std::true_type{}, j + 2);
-                    if constexpr (S > 3) process(std::integral_constant<int, 3 % S>{}, std::true_type{}, j + 3);
-                    if constexpr (S > 4) process(std::integral_constant<int, 4 % S>{}, std::true_type{}, j + 4);
-                    if constexpr (S > 5) process(std::integral_constant<int, 5 % S>{}, std::true_type{}, j + 5);
-                    if constexpr (S > 6) process(std::integral_constant<int, 6 % S>{}, std::true_type{}, j + 6);
-                    if constexpr (S > 7) process(std::integral_constant<int, 7 % S>{}, std::true_type{}, j + 7);
-                }
-                // the last n_fast % S tiles are already in their register sets: no more loads
-                static_assert(S <= 8, "the loop above is written out for at most 8 register sets");
-                if constexpr (S > 1) {
-                    if (j < n_fast) process(std::integral_constant<int, 0>{}, std::false_type{}, j);
-                }
-                if constexpr (S > 2) {
-                    if (j + 1 < n_fast) process(std::integral_constant<int, 1 % S>{}, std::false_type{}, j + 1);
-                }
-                if constexpr (S > 3) {
-                    if (j + 2 < n_fast) process(std::integral_constant<int, 2 % S>{}, std::false_type{}, j + 2);
-                }
-                if constexpr (S > 4) {
-                    if (j + 3 < n_fast) process(std::integral_constant<int, 3 % S>{}, std::false_type{}, j + 3);
-                }
-                if constexpr (S > 5) {
-                    if (j + 4 < n_fast) process(std::integral_constant<int, 4 % S>{}, std::false_type{}, j + 4);
-                }
-                if constexpr (S > 6) {
-                    if (j + 5 < n_fast) process(std::integral_constant<int, 5 % S>{}, std::false_type{}, j + 5);
-                }
-                if constexpr (S > 7) {
-                    if (j + 6 < n_fast) process(std::integral_constant<int, 6 % S>{}, std::false_type{}, j + 6);
+                if constexpr (S == 4) {
+                    for (; j + 2 * S <= n_fast; j += S) {
+                        process(integral_constant<int, 0>{}, kRefill, j);
+                        process(integral_constant<int, 1>{}, kRefill, j + 1);
+                        process(integral_constant<int, 2>{}, kRefill, j + 2);
+                        process(integral_constant<int, 3>{}, kRefill, j + 3);
+                    }
+                    // the last full trip: only the first n_fast - j - S sets still have a tile to fetch
+                    // (a set without one is left alone: asking again for the last tile would be traffic
+                    // for nothing)
+                    if (j + S <= n_fast) {
+                        const int more = n_fast - j - S;
+                        if (more > 0) process(integral_constant<int, 0>{}, kRefill, j);
+                        else process(integral_constant<int, 0>{}, kNoRefill, j);
+                        if (more > 1) process(integral_constant<int, 1>{}, kRefill, j + 1);
+                        else process(integral_constant<int, 1>{}, kNoRefill, j + 1);
+                        if (more > 2) process(integral_constant<int, 2>{}, kRefill, j + 2);
+                        else process(integral_constant<int, 2>{}, kNoRefill, j + 2);
+                        process(integral_constant<int, 3>{}, kNoRefill, j + 3);
+                        j += S;
+                    }
+                    // the last n_fast % S tiles are already in their register sets
+                    if (j < n_fast) process(integral_constant<int, 0>{}, kNoRefill, j);
+                    if (j + 1 < n_fast) process(integral_constant<int, 1>{}, kNoRefill, j + 1);
+                    if (j + 2 < n_fast) process(integral_constant<int, 2>{}, kNoRefill, j + 2);
+                } else {
+                    for (; j + 1 < n_fast; j++) process(integral_constant<int, 0>{}, kRefill, j);
+                    if (j < n_fast) process(integral_constant<int, 0>{}, kNoRefill, j);
                 }
             }
             // whatever is left of the piece, one tile at a time through register set 0
