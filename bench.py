@@ -79,6 +79,10 @@ def attend_algorithmic_bytes(cfg, seq_len, global_len, layers):
     return per_layer
 
 
+def events_ok(args):
+    return not args.no_kernel_events
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -244,20 +248,21 @@ def main():
     n_sampled_max = args.steps * L // max(args.event_every, 1) + L
     sampled, armed = [0], [False]
     events = None if args.no_kernel_events else HipEvents(2 * n_sampled_max)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # one between every two steps
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    e0.record()
+    step_ev[0].record()
     for st in range(args.warmup, total_steps):
         if graph is not None:
             g_static.copy_(g_new[st])
             graph.replay()
         else:
             one_step(st, events)
-    e1.record()
+        step_ev[st - args.warmup + 1].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    gpu_ms = e0.elapsed_time(e1)
+    gpu_ms = step_ev[0].elapsed_time(step_ev[-1])
+    step_us = np.array([step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(args.steps)]) * 1e3
     ms_per_step = max(wall_ms, gpu_ms) / args.steps
     pool.set_profile_events(None, None)
     free, flag = pool.status()
@@ -289,12 +294,45 @@ def main():
             torch.add(src, 1, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    # HBM bytes per launch measured with rocprofv3 counters (see the summary's header for the commands)
-    traffic_file = os.path.join(ROOT, "profiles", f"attend_decode_kernel_{cfg.name}_hbm_traffic.txt")
-    if os.path.exists(traffic_file) and not sel_b and not args.ctx_fixed and args.ctx_scale == 1.0:
-        for line in open(traffic_file):
+    # What a pure read of the same number of bytes takes on this machine, measured now: the library's
+    # streaming probe over slices of the pool (fresh memory every launch), timed by its own dispatch.
+    if events_ok(args) and not sel_b:
+        n_probe = 12
+        pe = HipEvents(2 * n_probe)
+        nb = int(bytes_per_launch) // 4096 * 4096
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        span = pool.pool_buf.numel()
+        for i in range(n_probe):
+            off = (i * (nb + (1 << 24))) % max(span - nb, 1) // 4096 * 4096
+            wg.stream_read_probe(pool.pool_buf[off:], nb, sink, pe.ev[2 * i], pe.ev[2 * i + 1])
+        torch.cuda.synchronize()
+        pd = np.array([pe.elapsed_ms(pe.ev[2 * i], pe.ev[2 * i + 1]) for i in range(2, n_probe)]) * 1e3
+        pe.destroy()
+        ceil_gbs = nb / (float(pd.mean()) * 1e-6) / 1e9
+        roofline.update({"measured_read_ceiling": ceil_gbs, "measured_read_ceiling_us": float(pd.mean()),
+                         "frac_of_measured_ceiling": (roofline["achieved"] / ceil_gbs) if roofline["achieved"] else None})
+    # HBM bytes per launch measured with rocprofv3 counters in a run of their own; the summary names the
+    # commands and the kernel source it was taken from.  It is quoted only while that source is unchanged.
+    traffic_file = os.path.join("profiles", f"attend_decode_kernel_{cfg.name}_hbm_traffic.txt")
+    roofline["traffic_source"] = None
+    if os.path.exists(os.path.join(ROOT, traffic_file)) and not sel_b and not args.ctx_fixed and args.ctx_scale == 1.0:
+        import hashlib
+        src = os.path.join(ROOT, "paper_2512_17452_amd", "csrc", "attend_decode.hip")
+        sha_now = hashlib.sha256(open(src, "rb").read()).hexdigest()
+        traffic, sha_file, commit = None, None, None
+        for line in open(os.path.join(ROOT, traffic_file)):
             if line.startswith("hbm_bytes_per_launch:"):
-                roofline["traffic"] = float(line.split(":")[1])
+                traffic = float(line.split(":")[1])
+            elif line.startswith("kernel_source_sha256:"):
+                sha_file = line.split(":")[1].strip()
+            elif line.startswith("taken_at_commit:"):
+                commit = line.split(":")[1].strip()
+        if sha_file == sha_now:
+            roofline["traffic"] = traffic
+            roofline["traffic_source"] = f"{traffic_file} (rocprofv3 FETCH_SIZE + WRITE_SIZE runs at commit {commit}; " \
+                                         f"attend_decode.hip unchanged since)"
+        else:
+            roofline["traffic_source"] = f"{traffic_file} is from another version of attend_decode.hip: not quoted"
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -311,6 +349,10 @@ def main():
                    "w_local": W, "page_size": P, "tau": cfg.tau, "ctx_min": int(ctx.min()), "ctx_max": int(ctx.max()),
                    "select_pages": sel_b, "hip_graph": bool(args.graph),
                    "mean_cached_tokens_per_head": float((np.minimum(sl1, W)[:, :, None] + gl1).mean()),
+                   # the paper's x axis: cached entries of a head over the tokens it has seen, (W + G_h) / t
+                   "normalized_kv_size": float(((np.minimum(sl1, W)[:, :, None] + gl1) / np.maximum(sl1, 1)[:, :, None]).mean()),
+                   "step_p10_us": float(np.percentile(step_us, 10)), "step_p50_us": float(np.percentile(step_us, 50)),
+                   "step_p90_us": float(np.percentile(step_us, 90)),
                    "attend_us_per_layer": roofline.get("kernel_avg_us"),
                    "gpu_ms_per_step": gpu_ms / args.steps, "host_wall_ms_per_step": wall_ms / args.steps},
         "roofline": roofline, "cpu_baseline": cpu_baseline,

@@ -394,6 +394,15 @@ int wgkv_clear_error(wgkv_pool *pool, wgkv_stream stream);
  * its kernels.  Pass NULLs to switch it off. */
 int wgkv_set_profile_events(wgkv_pool *pool, void *ev_begin, void *ev_end);
 
+/* Measurement aid: enqueues a kernel that reads bytes (rounded down to a multiple of 16) of
+ * buf_dev (16-byte aligned) once, with the same kind of loads the decode attention kernel
+ * streams K/V rows with, and does nothing else: its duration is what the memory system of
+ * this machine gives a pure read of that size.  sink_dev: one uint32 the kernel may write.
+ * When both are non-NULL hipEvent_t handles, ev_begin and ev_end take the begin and end time
+ * stamps of the kernel's dispatch.  Errors: INVALID_ARG, HIP. */
+int wgkv_stream_read_probe(const void *buf_dev, size_t bytes, uint32_t *sink_dev, void *ev_begin, void *ev_end,
+                           wgkv_stream stream);
+
 /* Frees the host handle only. */
 void wgkv_destroy(wgkv_pool *pool);
 

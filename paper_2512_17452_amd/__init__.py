@@ -6,5 +6,5 @@ There is no CPU fallback: importing works anywhere, calling needs the built
 library and a GPU.
 """
 from .binding import (Config, Pool, WgkvError, gate_mlp_scores, gate_scores, load_library, library_path,  # noqa: F401
-                      soft_attn_backward, soft_attn_forward, sparsity_loss,
+                      soft_attn_backward, soft_attn_forward, sparsity_loss, stream_read_probe,
                       EXPORTED_SYMBOLS, F32, BF16)

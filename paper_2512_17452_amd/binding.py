@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = [
     "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_attend_decode_static", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
     "wgkv_quest_select", "wgkv_attend_selected", "wgkv_soft_attn_forward", "wgkv_soft_attn_workspace_bytes",
     "wgkv_soft_attn_backward", "wgkv_sparsity_loss", "wgkv_free_seq",
-    "wgkv_status", "wgkv_clear_error", "wgkv_set_profile_events", "wgkv_destroy",
+    "wgkv_status", "wgkv_clear_error", "wgkv_stream_read_probe", "wgkv_set_profile_events", "wgkv_destroy",
 ]
 
 _ERR = {-1: "invalid argument", -2: "out of pages", -3: "page-table overflow", -4: "HIP error",
@@ -104,6 +104,7 @@ def load_library():
     L.wgkv_free_seq.argtypes = [vp, i32, vp]
     L.wgkv_status.argtypes = [vp, vp, C.POINTER(i64), C.POINTER(i32)]
     L.wgkv_clear_error.argtypes = [vp, vp]
+    L.wgkv_stream_read_probe.argtypes = [vp, sz, vp, vp, vp, vp]
     L.wgkv_set_profile_events.argtypes = [vp, vp, vp]
     L.wgkv_destroy.argtypes = [vp]
     L.wgkv_destroy.restype = None
@@ -128,6 +129,14 @@ def _stream():
 def _check(rc, what):
     if rc != 0:
         raise WgkvError(rc, what)
+
+
+def stream_read_probe(buf, n_bytes, sink, ev_begin=None, ev_end=None):
+    """wgkv_stream_read_probe: a read-only kernel over the first n_bytes of the uint8 tensor `buf`;
+    ev_begin / ev_end are raw hipEvent_t handles (ints) or None."""
+    L = load_library()
+    _check(L.wgkv_stream_read_probe(_ptr(buf), int(n_bytes), _ptr(sink), C.c_void_p(ev_begin) if ev_begin else None,
+                                    C.c_void_p(ev_end) if ev_end else None, _stream()), "wgkv_stream_read_probe")
 
 
 def gate_scores(hidden, gate_w, out=None):

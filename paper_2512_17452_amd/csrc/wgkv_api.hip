@@ -59,6 +59,8 @@ hipError_t launch_soft_attn_bwd(int n_seqs, const int32_t *n_tokens, int Hq, int
 size_t sparsity_ws_bytes();
 hipError_t launch_sparsity_loss(const float *g, int64_t n, int64_t n_total, float *loss, float *dg, void *ws,
                                 hipStream_t st);
+hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, int n_cu, hipStream_t st,
+                              hipEvent_t ev0, hipEvent_t ev1);
 size_t attend_prefill_ws_bytes(const View &pv, int n_seqs, int64_t total_q);
 hipError_t launch_attend_prefill(const View &pv, const CallSeqs &cs, int layer, const void *q,
                                  const void *k, const void *v, const float *g, float tau,
@@ -771,6 +773,20 @@ int wgkv_status(wgkv_pool *p, wgkv_stream stream, int64_t *pages_free, int32_t *
     p->pages_ub = used;
     // the mirrors are exact again whatever the flag says: a call that set it changed nothing
     return flag != 0 ? WGKV_ERR_DEVICE_FLAG : WGKV_OK;
+}
+
+int wgkv_stream_read_probe(const void *buf_dev, size_t bytes, uint32_t *sink_dev, void *ev_begin, void *ev_end,
+                           wgkv_stream stream) {
+    if (!buf_dev || !sink_dev || bytes < 16 || ((uintptr_t)buf_dev & 15) || ((ev_begin == nullptr) != (ev_end == nullptr)))
+        return WGKV_ERR_INVALID_ARG;
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+        return WGKV_ERR_HIP;
+    return launch_stream_read(buf_dev, bytes, sink_dev, n_cu, (hipStream_t)stream, (hipEvent_t)ev_begin,
+                              (hipEvent_t)ev_end) == hipSuccess
+               ? WGKV_OK
+               : WGKV_ERR_HIP;
 }
 
 int wgkv_clear_error(wgkv_pool *p, wgkv_stream stream) {
