@@ -560,6 +560,8 @@ def main_prefill(args, cfg, torch, wg, wl, dev):
     tflops = float(np.sum(flops)) / float(durs.sum()) / 1e9
     log(f"[bench] chunks {first_timed}..{n_chunks - 1}: attention {durs.sum():.1f} ms, gate {gate_ms:.2f} ms, "
         f"admit {admit_ms:.2f} ms, wall incl. input generation {wall_ms:.1f} ms")
+    log("[bench] TFLOP/s of the attention kernel per timed chunk: "
+        + " ".join(f"{f / t / 1e9:.0f}" for f, t in zip(flops, durs)))
     res = {
         "metric": "prefill_chunk_latency_us (one layer: write gate + chunk attention under the vertical-slash mask + admission)",
         "value": path_ms / steps * 1e3, "unit": "us/chunk", "n_gpus": 1, "steps": steps, "warmup": first_timed,
