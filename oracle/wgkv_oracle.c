@@ -331,7 +331,7 @@ void orc_get_head_tables(const orc_state *S, int seq, int layer, int h, int32_t 
 }
 void orc_get_global_pos(const orc_state *S, int seq, int layer, int h, int64_t *out) {
     const orc_head *H = &S->sl[(size_t)seq * S->c.n_layers + layer].h[h];
-    memcpy(out, H->gpos, sizeof(int64_t) * (size_t)H->glen);
+    if (H->glen > 0) memcpy(out, H->gpos, sizeof(int64_t) * (size_t)H->glen);  /* empty cache: no array yet */
 }
 /* cached rows: global entries in order, then ring slots 0..W-1 */
 int orc_get_payload(const orc_state *S, int seq, int layer, int h, float *gk, float *gv,
@@ -339,8 +339,8 @@ int orc_get_payload(const orc_state *S, int seq, int layer, int h, float *gk, fl
     if (!S->c.keep_payload) return ORC_ERR_ARG;
     const orc_head *H = &S->sl[(size_t)seq * S->c.n_layers + layer].h[h];
     const size_t d = S->c.head_dim;
-    if (gk) memcpy(gk, H->gk, sizeof(float) * H->glen * d);
-    if (gv) memcpy(gv, H->gv, sizeof(float) * H->glen * d);
+    if (gk && H->glen > 0) memcpy(gk, H->gk, sizeof(float) * H->glen * d);
+    if (gv && H->glen > 0) memcpy(gv, H->gv, sizeof(float) * H->glen * d);
     if (ring_k) memcpy(ring_k, H->ring_k, sizeof(float) * S->c.w_local * d);
     if (ring_v) memcpy(ring_v, H->ring_v, sizeof(float) * S->c.w_local * d);
     return ORC_OK;
@@ -838,10 +838,16 @@ int orc_gate_mlp(int64_t T, int H, int d, int width, const float *k, const float
                  const float *W1, const float *b1, const float *W2, const float *b2, double eps,
                  int feature_bf16, double *logit_out, double *g_out) {
     if (T < 0 || H < 1 || d < 1 || width < 1) return ORC_ERR_ARG;
+    int rc_all = ORC_OK;
     /* tokens are independent: spread them over the host threads */
 #pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < T; t++) {
         double *x = (double *)malloc(sizeof(double) * 2 * (size_t)d);
+        if (!x) {
+#pragma omp atomic write
+            rc_all = ORC_ERR_NOMEM;
+            continue;
+        }
         for (int h = 0; h < H; h++) {
             for (int part = 0; part < 2; part++) {
                 const float *v = (part == 0 ? k : k_rope) + ((size_t)t * H + h) * d;
@@ -866,7 +872,7 @@ int orc_gate_mlp(int64_t T, int H, int d, int width, const float *k, const float
         }
         free(x);
     }
-    return ORC_OK;
+    return rc_all;
 }
 
 

@@ -47,9 +47,15 @@ def _f32(a):
 def lib():
     global _lib
     if _lib is None:
-        path = _build.LIB
-        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
-            _build.build(force=True)
+        path = os.environ.get("WGKV_ORACLE_LIB")  # e.g. the build with the sanitizers (see build.py)
+        if path:
+            path = os.path.abspath(path)
+            if not os.path.exists(path):
+                raise FileNotFoundError(f"WGKV_ORACLE_LIB names {path}, which does not exist")
+        else:
+            path = _build.LIB
+            if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+                _build.build(force=True)
         L = C.CDLL(path)
         L.orc_create.restype = C.c_void_p
         L.orc_create.argtypes = [C.POINTER(_CConfig)]

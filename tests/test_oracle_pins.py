@@ -227,6 +227,38 @@ def test_mechanism_attention_equals_definition(W, P):
     np.testing.assert_array_equal(out_b[0], o.attend_cached(0, 0, Q[n - 1], scale))
 
 
+def test_batched_decode_attention_on_permuted_sequences_and_layers():
+    """orc_attend_cached_batch against library attention under the Sec. 4.2 mask, built from each
+    (sequence, layer)'s own history: four sequences of different lengths, two layers with different
+    contents, the calls naming the sequences out of order and only some of them.  Reading the wrong
+    sequence, the wrong layer, or the batch slot instead of the sequence id fails it."""
+    Hq, Hk, d, W, P, tau = 6, 3, 8, 4, 2, 0.55
+    S, L = 4, 2
+    o = _mk(Hq, Hk, d, P, W, n_pages=600, max_gp=64, L=L, S=S)
+    scale = 1 / math.sqrt(d)
+    lens = {(s, l): 9 + 7 * s + 5 * l for s in range(S) for l in range(L)}
+    hist = {}
+    for (s, l), n in lens.items():
+        K, V, Q, g = _rand(100 + 10 * s + l, n, Hq, Hk, d)
+        hist[(s, l)] = (K, V, Q, g)
+        o.push_tokens(l, [s], [n], K, V, g, tau)
+
+    def expected(s, l):
+        K, V, Q, g = hist[(s, l)]
+        n = K.shape[0]
+        j = np.arange(n)
+        vis = ((n - 1 - j < W)[None, :] | (g.T >= np.float32(tau)))  # [Hk, n]: what the last position sees
+        return _sdpa(K, V, Q[n - 1:n], mask=vis[:, None, :])[0]
+
+    for layer, ids in [(1, [3, 0, 2]), (0, [1, 3, 2, 0]), (1, [1]), (0, [2, 2])]:
+        q = np.stack([hist[(s, layer)][2][-1] for s in ids])
+        out, threads = o.attend_cached_batch(layer, ids, q, scale)
+        assert threads >= 1
+        for b, s in enumerate(ids):
+            np.testing.assert_allclose(out[b], expected(s, layer), rtol=0, atol=1e-12)
+            np.testing.assert_array_equal(out[b], o.attend_cached(s, layer, q[b], scale))
+
+
 @pytest.mark.parametrize("W,P", [(1, 1), (2, 1), (2, 2), (4, 2), (4, 1)])
 def test_brute_force_all_admission_patterns(W, P):
     # every one of the 2^N admit patterns of one head, N <= 10
