@@ -62,7 +62,8 @@ enum {
     WGKV_ERR_HIP = -4,          /* a HIP runtime call failed */
     WGKV_ERR_DEVICE_FLAG = -5,  /* the device-side sticky error flag is set */
     WGKV_ERR_WORKSPACE = -6,    /* workspace too small for this call */
-    WGKV_ERR_HOST_MEMORY = -7   /* the host handle could not be allocated */
+    WGKV_ERR_HOST_MEMORY = -7,  /* the host handle could not be allocated */
+    WGKV_ERR_ADMIT_BOUND = -8   /* device flag only: a unit admitted more tokens than the caller's bound */
 };
 
 #define WGKV_MAX_CALL_SEQS 128  /* sequences per call */
@@ -223,6 +224,25 @@ int wgkv_prefill_admit(wgkv_pool *pool, int32_t layer, int32_t n_seqs,
                        const void *hidden_dev, const void *gate_w_dev, int32_t hidden_dim,
                        float tau, uint8_t *admit_mask_out_dev, void *workspace_dev,
                        size_t workspace_bytes, wgkv_stream stream);
+
+/* The same call for a pool sized for the admitted cache rather than for the worst case
+ * (Sec. 4.2 "Initial cache population"; Sec. 3.3: the gate admits a small share of the tokens).
+ * max_admitted_per_head >= 0 is the caller's promise that no (sequence, kv head) of this call
+ * admits more than that many tokens to its global cache in this call.  The host-side page
+ * bounds then count min(leaving tokens, max_admitted_per_head) per head instead of all leaving
+ * tokens, so a loop of chunks needs no wgkv_status (a device synchronisation) between calls
+ * to stay inside a pool of that size.  The device checks the promise before it changes
+ * anything: when a head admits more, the call leaves the pool exactly as it was and sets the
+ * sticky device flag to WGKV_ERR_ADMIT_BOUND (seen by the next wgkv_status, which also
+ * re-reads the token counts; the host's counts of that call are then ahead of the device's
+ * until it does).  Everything else as wgkv_prefill_admit.
+ * Errors: those of wgkv_prefill_admit; INVALID_ARG for a negative bound. */
+int wgkv_prefill_admit_bounded(wgkv_pool *pool, int32_t layer, int32_t n_seqs,
+                               const int32_t *seq_ids_host, const int32_t *n_tokens_host,
+                               const void *k_dev, const void *v_dev, const float *g_dev,
+                               const void *hidden_dev, const void *gate_w_dev, int32_t hidden_dim,
+                               float tau, int32_t max_admitted_per_head, uint8_t *admit_mask_out_dev,
+                               void *workspace_dev, size_t workspace_bytes, wgkv_stream stream);
 
 /* Sec. 4.3 lazy promotion, one new token per sequence: the victim in slot
  * t mod W (if t >= W) is appended to the global cache iff its stored score

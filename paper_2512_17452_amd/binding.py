@@ -11,14 +11,15 @@ F32, BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
-    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_decode_step", "wgkv_attend", "wgkv_attend_decode_static", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
+    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_prefill_admit_bounded", "wgkv_decode_step", "wgkv_attend", "wgkv_attend_decode_static", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
     "wgkv_quest_select", "wgkv_attend_selected", "wgkv_soft_attn_forward", "wgkv_soft_attn_workspace_bytes",
     "wgkv_soft_attn_backward", "wgkv_sparsity_loss", "wgkv_free_seq",
     "wgkv_status", "wgkv_clear_error", "wgkv_stream_read_probe", "wgkv_set_profile_events", "wgkv_destroy",
 ]
 
 _ERR = {-1: "invalid argument", -2: "out of pages", -3: "page-table overflow", -4: "HIP error",
-        -5: "device error flag set", -6: "workspace too small", -7: "host out of memory"}
+        -5: "device error flag set", -6: "workspace too small", -7: "host out of memory",
+        -8: "a head admitted more tokens than the bound given to wgkv_prefill_admit_bounded"}
 
 
 class WgkvError(RuntimeError):
@@ -92,6 +93,7 @@ def load_library():
                                           vp, vp, vp, vp, vp, sz, vp]
     L.wgkv_sparsity_loss.argtypes = [vp, i64, i64, vp, vp, vp, sz, vp]
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+    L.wgkv_prefill_admit_bounded.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
     L.wgkv_attend_decode_static.argtypes = [vp, i32, i32, pi32, vp, f32, vp, vp]
@@ -267,12 +269,20 @@ class Pool:
 
     # ---- the path ----
     def prefill_admit(self, layer, seq_ids, n_tokens, k, v, g=None, hidden=None, gate_w=None,
-                      tau=0.5, admit_mask_out=None):
+                      tau=0.5, admit_mask_out=None, max_admitted_per_head=None):
+        """wgkv_prefill_admit, or wgkv_prefill_admit_bounded when max_admitted_per_head is given."""
         hd = 0 if hidden is None else hidden.shape[-1]
-        _check(self.L.wgkv_prefill_admit(self.h, layer, len(seq_ids), _ids(seq_ids), _ids(n_tokens),
-                                         _ptr(k), _ptr(v), _ptr(g), _ptr(hidden), _ptr(gate_w), hd,
-                                         tau, _ptr(admit_mask_out), _ptr(self.workspace),
-                                         self.workspace.numel(), _stream()), "wgkv_prefill_admit")
+        if max_admitted_per_head is None:
+            _check(self.L.wgkv_prefill_admit(self.h, layer, len(seq_ids), _ids(seq_ids), _ids(n_tokens),
+                                             _ptr(k), _ptr(v), _ptr(g), _ptr(hidden), _ptr(gate_w), hd,
+                                             tau, _ptr(admit_mask_out), _ptr(self.workspace),
+                                             self.workspace.numel(), _stream()), "wgkv_prefill_admit")
+        else:
+            _check(self.L.wgkv_prefill_admit_bounded(self.h, layer, len(seq_ids), _ids(seq_ids), _ids(n_tokens),
+                                                     _ptr(k), _ptr(v), _ptr(g), _ptr(hidden), _ptr(gate_w), hd,
+                                                     tau, int(max_admitted_per_head), _ptr(admit_mask_out),
+                                                     _ptr(self.workspace), self.workspace.numel(), _stream()),
+                   "wgkv_prefill_admit_bounded")
 
     def decode_step(self, layer, seq_ids, k_new, v_new, g_new, tau=0.5, promoted_out=None):
         _check(self.L.wgkv_decode_step(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(k_new),

@@ -3,8 +3,8 @@
 //  init_kernel            free stack + cleared tables                       (Sec. 4.1)
 //  prefill_count_kernel   gate score -> admit mask, per-block admitted counts (Sec. 3.3 last sentence)
 //  prefill_plan_kernel    prefix sums over blocks and units, page hand-out    (Sec. 4.1, 4.2)
-//  prefill_scatter_kernel stable compaction of admitted K/V rows into global pages (Sec. 4.2)
-//  prefill_ring_kernel    last min(W,T) tokens into the ring                  (Sec. 4.2)
+//  prefill_scatter_kernel stable compaction of admitted K/V rows into global pages, then the
+//                         last min(W,T) tokens into the ring                  (Sec. 4.2)
 //  decode_step_kernel     lazy promotion of the victim, then overwrite        (Sec. 4.3 (1)-(3))
 //  free_seq_kernel        pages of a sequence slot back to the free stack
 //
@@ -20,7 +20,8 @@ constexpr int kPlanThreads = 1024; // the one block of prefill_plan_kernel
 
 struct PrefillArgs {
     int layer;
-    int nblk_max;         // grid.x
+    int nblk_max;         // blocks of leaving tokens per unit (the row stride of cnt)
+    int max_adm;          // the caller's bound on tokens admitted per unit in this call, < 0: none
     float tau;
     const char *k, *v;    // [sumT][Hkv][d]
     const float *g;       // [sumT][Hkv]
@@ -102,11 +103,11 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(View pv, Cal
     __shared__ int s_dl[kMaxCallUnits];
     __shared__ int s_um[kMaxCallUnits];
     __shared__ int s_tmp[20];
-    __shared__ int s_err;
+    __shared__ int s_err, s_over;
     const int n_units = cs.n * pv.Hkv;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     constexpr int NW = kPlanThreads / 64;
-    if (threadIdx.x == 0) s_err = 0;
+    if (threadIdx.x == 0) { s_err = 0; s_over = 0; }
     // what phase B needs of the first kPlanThreads units is asked for now: the kernel is a
     // chain of round trips on cold metadata, and these do not depend on phase A
     int um0 = 0, gold0 = 0, lp00 = 0;
@@ -132,7 +133,10 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(View pv, Cal
             if (i < nblk) c[i] = run + inc - v;
             run += __shfl(inc, 63);
         }
-        if (lane == 0) s_adm[u] = run;
+        if (lane == 0) {
+            s_adm[u] = run;
+            if (a.max_adm >= 0 && run > a.max_adm) s_over = 1;  // more admitted than the caller sized its pool for
+        }
     }
     __syncthreads();
     // B: page demand of every unit, prefix over units in call order
@@ -160,7 +164,10 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(View pv, Cal
         carry += total;
     }
     __syncthreads();
-    if (threadIdx.x == 0 && s_err == 0 && carry > top) s_err = WGKV_ERR_OUT_OF_PAGES;
+    if (threadIdx.x == 0) {
+        if (s_over) s_err = WGKV_ERR_ADMIT_BOUND;  // reported first: the host's page accounting relied on the bound
+        else if (s_err == 0 && carry > top) s_err = WGKV_ERR_OUT_OF_PAGES;
+    }
     __syncthreads();
     if (s_err != 0) {  // block-uniform: leave all state as it was
         if (threadIdx.x == 0) {
@@ -211,9 +218,30 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(View pv, Cal
 
 constexpr int kScatterBatch = 8;  // rows a thread has in flight in the copy loop
 
+// Row r of the new ring contents of a unit: token T - nr + r of the sequence's part of the call
+// goes to slot (t0 + T - nr + r) mod W, its score with it.  lpr lanes of 16 bytes per row.
+__device__ __forceinline__ void ring_put(const View &pv, const PrefillArgs &a, int um, int h, int base, int t0,
+                                         int i, int sub) {
+    const int slot = (t0 + i) % pv.W;
+    const size_t row = (size_t)(base + i) * pv.Hkv + h;
+    char *dp = page_ptr(pv, pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)]) +
+               (size_t)(slot & (pv.P - 1)) * pv.row_bytes;
+    *reinterpret_cast<uint4 *>(dp + sub * 16) = *reinterpret_cast<const uint4 *>(a.k + row * pv.row_bytes + sub * 16);
+    *reinterpret_cast<uint4 *>(dp + pv.v_off + sub * 16) =
+        *reinterpret_cast<const uint4 *>(a.v + row * pv.row_bytes + sub * 16);
+    if (sub == 0) pv.ring_g[(size_t)um * pv.W + slot] = a.g[row];
+}
+
 // The copy is a chain of round trips if done row by row (page id, then the row, then the
 // store), so the destination page ids of the block go to LDS once (its rows land in one
 // contiguous range of the global cache) and a thread requests 8 rows before it stores any.
+//
+// The ring is rewritten in the same launch.  A ring slot whose old token leaves the window is read
+// by exactly one block here (the one that owns the leaving token), so that block also writes the
+// slot's new token, after a barrier behind its copy loop: every new ring token whose slot was
+// occupied has such an owner (the occupant of a slot always leaves when a token of the call takes
+// the slot).  Slots that were still empty (sequences shorter than the window) are written by the
+// blocks past the first nblk_max of the grid, which read nothing from the ring.
 __global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs cs, PrefillArgs a) {
     __shared__ int s_src[kPrefillBlk];  // admitted leaving tokens of the block, in order
     __shared__ int s_rpg[kPrefillBlk];  // ring page of the token if its row sits in the ring, else -1
@@ -224,6 +252,16 @@ __global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs 
     const int t0 = cs.t0[b], T = cs.ntok[b], base = cs.base[b];
     const int um = unit_meta(pv, cs.sid[b], a.layer, h);
     const int lo = max(0, t0 - pv.W), hi = max(0, t0 + T - pv.W), n_leave = hi - lo;
+    if ((int)blockIdx.x >= a.nblk_max) {
+        // new ring tokens whose slot held nothing: slot >= t0 while the ring is not full yet
+        if (t0 >= pv.W) return;
+        const int nr = min(T, pv.W), lpr = pv.row_bytes >> 4;
+        const int r = (((int)blockIdx.x - a.nblk_max) * 256 + (int)threadIdx.x) / lpr;
+        if (r >= nr) return;
+        const int i = T - nr + r;
+        if ((t0 + i) % pv.W >= t0) ring_put(pv, a, um, h, base, t0, i, threadIdx.x % lpr);
+        return;
+    }
     if (blockIdx.x * kPrefillBlk >= n_leave) return;
     const int dst0 = a.plan[1 + u] + a.cnt[(size_t)u * a.nblk_max + blockIdx.x];
     const int i0 = blockIdx.x * kPrefillBlk + threadIdx.x * kTok;
@@ -293,26 +331,17 @@ __global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs 
         put(r0, a0, b0); put(r0 + rp, a1, b1); put(r0 + 2 * rp, a2, b2); put(r0 + 3 * rp, a3, b3);
         put(r0 + 4 * rp, a4, b4); put(r0 + 5 * rp, a5, b5); put(r0 + 6 * rp, a6, b6); put(r0 + 7 * rp, a7, b7);
     }
-}
-
-__global__ __launch_bounds__(256) void prefill_ring_kernel(View pv, CallSeqs cs, PrefillArgs a) {
-    if (a.plan[0] != 0) return;
-    const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
-    const int t0 = cs.t0[b], T = cs.ntok[b], base = cs.base[b];
-    const int um = unit_meta(pv, cs.sid[b], a.layer, h);
-    const int nr = min(T, pv.W);
-    const int lpr = pv.row_bytes >> 4;
-    const int r = (blockIdx.x * 256 + threadIdx.x) / lpr, sub = threadIdx.x % lpr;
-    if (r >= nr) return;
-    const int i = T - nr + r;  // index in the chunk
-    const int slot = (t0 + i) % pv.W;
-    const size_t row = (size_t)(base + i) * pv.Hkv + h;
-    char *dp = page_ptr(pv, pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)]) +
-               (size_t)(slot & (pv.P - 1)) * pv.row_bytes;
-    *reinterpret_cast<uint4 *>(dp + sub * 16) = *reinterpret_cast<const uint4 *>(a.k + row * pv.row_bytes + sub * 16);
-    *reinterpret_cast<uint4 *>(dp + pv.v_off + sub * 16) =
-        *reinterpret_cast<const uint4 *>(a.v + row * pv.row_bytes + sub * 16);
-    if (sub == 0) pv.ring_g[(size_t)um * pv.W + slot] = a.g[row];
+    // The ring slots of this block's leaving tokens that sat in the ring (leaving index < t0 - lo): every row and
+    // score the block takes from them has arrived (the stores above used them), for all its threads behind the
+    // barrier.  The slot of position p gets the last position of the call that is congruent to p modulo W.
+    const int i_hi = min((int)(blockIdx.x + 1) * kPrefillBlk, min(n_leave, t0 - lo));
+    if ((int)blockIdx.x * kPrefillBlk >= i_hi) return;  // block-uniform
+    __syncthreads();
+    for (int i = blockIdx.x * kPrefillBlk + threadIdx.x / lpr; i < i_hi; i += rows_per_pass) {
+        const int pos = lo + i;
+        const int q = pos + pv.W * ((t0 + T - 1 - pos) / pv.W);
+        ring_put(pv, a, um, h, base, t0, q - t0, sub);
+    }
 }
 
 // One block does the whole step: decisions and page hand-out first (they need a
@@ -476,8 +505,8 @@ hipError_t launch_init(const View &pv, hipStream_t st) {
 
 hipError_t launch_prefill(const View &pv, const CallSeqs &cs, int layer, float tau, const void *k,
                           const void *v, const float *g, uint8_t *admit_out, int32_t *cnt,
-                          int32_t *plan, int nblk_leave_max, int max_T, int max_ring_rows,
-                          hipStream_t st) {
+                          int32_t *plan, int nblk_leave_max, int max_T, int max_empty_ring_rows,
+                          int max_admitted, hipStream_t st) {
     PrefillArgs a;
     a.layer = layer;
     a.tau = tau;
@@ -488,18 +517,18 @@ hipError_t launch_prefill(const View &pv, const CallSeqs &cs, int layer, float t
     a.cnt = cnt;
     a.plan = plan;
     a.nblk_max = nblk_leave_max > 0 ? nblk_leave_max : 1;
+    a.max_adm = max_admitted;
     const int n_units = cs.n * pv.Hkv;
     int gx = a.nblk_max;
     if (admit_out) gx = max(gx, (max_T + kPrefillBlk - 1) / kPrefillBlk);
     hipLaunchKernelGGL(prefill_count_kernel, dim3(gx, n_units), dim3(256), 0, st, pv, cs, a);
     hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, pv, cs, a);
-    if (nblk_leave_max > 0)
-        hipLaunchKernelGGL(prefill_scatter_kernel, dim3(a.nblk_max, n_units), dim3(256), 0, st, pv, cs, a);
-    if (max_ring_rows > 0) {
-        const int lpr = pv.row_bytes >> 4;
-        const int gxr = (max_ring_rows * lpr + 255) / 256;
-        hipLaunchKernelGGL(prefill_ring_kernel, dim3(gxr, n_units), dim3(256), 0, st, pv, cs, a);
-    }
+    // blocks 0 .. nblk_max-1 of a unit: leaving tokens (and the ring slots they vacate); the rest: ring rows
+    // that go to slots still empty (max_empty_ring_rows: the most ring rows of a sequence that has any such)
+    const int lpr = pv.row_bytes >> 4;
+    const int gxr = (max_empty_ring_rows * lpr + 255) / 256;
+    if (nblk_leave_max > 0 || gxr > 0)
+        hipLaunchKernelGGL(prefill_scatter_kernel, dim3(a.nblk_max + gxr, n_units), dim3(256), 0, st, pv, cs, a);
     return hipGetLastError();
 }
 

@@ -14,8 +14,8 @@ namespace wgkv {
 hipError_t launch_init(const View &pv, hipStream_t st);
 hipError_t launch_prefill(const View &pv, const CallSeqs &cs, int layer, float tau, const void *k,
                           const void *v, const float *g, uint8_t *admit_out, int32_t *cnt,
-                          int32_t *plan, int nblk_leave_max, int max_T, int max_ring_rows,
-                          hipStream_t st);
+                          int32_t *plan, int nblk_leave_max, int max_T, int max_empty_ring_rows,
+                          int max_admitted, hipStream_t st);
 hipError_t launch_decode_step(const View &pv, const CallSeqs &cs, int layer, float tau,
                               const void *k, const void *v, const float *g, uint8_t *promoted_out,
                               hipStream_t st);
@@ -386,11 +386,12 @@ int wgkv_sparsity_loss(const float *g_dev, int64_t n, int64_t n_total, float *lo
                : WGKV_ERR_HIP;
 }
 
-int wgkv_prefill_admit(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
-                       const int32_t *n_tokens_host, const void *k_dev, const void *v_dev,
-                       const float *g_dev, const void *hidden_dev, const void *gate_w_dev,
-                       int32_t hidden_dim, float tau, uint8_t *admit_mask_out_dev,
-                       void *workspace_dev, size_t workspace_bytes, wgkv_stream stream) {
+// max_admitted < 0: no bound from the caller (every leaving token may be admitted)
+static int prefill_admit_impl(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                              const int32_t *n_tokens_host, const void *k_dev, const void *v_dev,
+                              const float *g_dev, const void *hidden_dev, const void *gate_w_dev,
+                              int32_t hidden_dim, float tau, int32_t max_admitted, uint8_t *admit_mask_out_dev,
+                              void *workspace_dev, size_t workspace_bytes, wgkv_stream stream) {
     int rc = check_seqs(p, layer, n_seqs, seq_ids_host);
     if (rc) return rc;
     if (!n_tokens_host || !workspace_dev) return WGKV_ERR_INVALID_ARG;
@@ -414,7 +415,7 @@ int wgkv_prefill_admit(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_
         const int64_t leave = std::max<int64_t>(0, t0 + T - W) - std::max<int64_t>(0, t0 - W);
         max_T = std::max<int64_t>(max_T, T);
         max_leave = std::max(max_leave, leave);
-        max_ring = std::max<int64_t>(max_ring, std::min(T, W));
+        if (t0 < W) max_ring = std::max<int64_t>(max_ring, std::min(T, W));  // ring rows that may go to empty slots
     }
     if (total == 0) return WGKV_OK;
     if (!k_dev || !v_dev) return WGKV_ERR_INVALID_ARG;
@@ -424,14 +425,19 @@ int wgkv_prefill_admit(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_
         return WGKV_ERR_INVALID_ARG;
     const PrefillWs ws = prefill_ws(&c, n_seqs, total, max_T);
     if (workspace_bytes < ws.total) return WGKV_ERR_WORKSPACE;
-    // worst case for the page bounds: every token that leaves the window is admitted
+    // worst case for the page bounds: every token that leaves the window is admitted, up to the
+    // caller's bound per unit if it gave one (the device refuses the call when a unit exceeds it)
+    auto admitted_ub = [&](int64_t t0, int T) {
+        const int64_t leave = std::max<int64_t>(0, t0 + T - W) - std::max<int64_t>(0, t0 - W);
+        return max_admitted >= 0 ? std::min<int64_t>(leave, max_admitted) : leave;
+    };
     int64_t new_pages = 0;
     for (int b = 0; b < n_seqs; b++) {
         const int T = cs.ntok[b];
         if (T == 0) continue;
         const size_t sl = (size_t)cs.sid[b] * c.n_layers + layer;
         const int64_t t0 = cs.t0[b];
-        const int64_t leave = std::max<int64_t>(0, t0 + T - W) - std::max<int64_t>(0, t0 - W);
+        const int64_t leave = admitted_ub(t0, T);
         if (!p->touched_h[sl]) new_pages += (int64_t)p->view.nlp * H;
         for (int h = 0; h < H; h++) {
             const int64_t g0 = p->g_ub[sl * H + h], g1 = g0 + leave;
@@ -453,20 +459,42 @@ int wgkv_prefill_admit(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_
     const int nblk_leave = (int)((max_leave + kPrefillBlkHost - 1) / kPrefillBlkHost);
     if (launch_prefill(p->view, cs, layer, tau, k_dev, v_dev, g, admit_mask_out_dev,
                        (int32_t *)(wsp + ws.cnt_off), (int32_t *)(wsp + ws.plan_off), nblk_leave,
-                       (int)max_T, (int)max_ring, st) != hipSuccess)
+                       (int)max_T, (int)max_ring, max_admitted, st) != hipSuccess)
         return WGKV_ERR_HIP;
     for (int b = 0; b < n_seqs; b++) {
         const int T = cs.ntok[b];
         if (T == 0) continue;
         const size_t sl = (size_t)cs.sid[b] * c.n_layers + layer;
         const int64_t t0 = cs.t0[b];
-        const int64_t leave = std::max<int64_t>(0, t0 + T - W) - std::max<int64_t>(0, t0 - W);
+        const int64_t leave = admitted_ub(t0, T);
         p->touched_h[sl] = 1;
         p->seq_len_h[sl] = (int32_t)(t0 + T);
         for (int h = 0; h < H; h++) p->g_ub[sl * H + h] += (int32_t)leave;
     }
     p->pages_ub += new_pages;
     return WGKV_OK;
+}
+
+int wgkv_prefill_admit(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                       const int32_t *n_tokens_host, const void *k_dev, const void *v_dev,
+                       const float *g_dev, const void *hidden_dev, const void *gate_w_dev,
+                       int32_t hidden_dim, float tau, uint8_t *admit_mask_out_dev,
+                       void *workspace_dev, size_t workspace_bytes, wgkv_stream stream) {
+    return prefill_admit_impl(p, layer, n_seqs, seq_ids_host, n_tokens_host, k_dev, v_dev, g_dev, hidden_dev,
+                              gate_w_dev, hidden_dim, tau, -1, admit_mask_out_dev, workspace_dev,
+                              workspace_bytes, stream);
+}
+
+int wgkv_prefill_admit_bounded(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
+                               const int32_t *n_tokens_host, const void *k_dev, const void *v_dev,
+                               const float *g_dev, const void *hidden_dev, const void *gate_w_dev,
+                               int32_t hidden_dim, float tau, int32_t max_admitted_per_head,
+                               uint8_t *admit_mask_out_dev, void *workspace_dev, size_t workspace_bytes,
+                               wgkv_stream stream) {
+    if (max_admitted_per_head < 0) return WGKV_ERR_INVALID_ARG;
+    return prefill_admit_impl(p, layer, n_seqs, seq_ids_host, n_tokens_host, k_dev, v_dev, g_dev, hidden_dev,
+                              gate_w_dev, hidden_dim, tau, max_admitted_per_head, admit_mask_out_dev,
+                              workspace_dev, workspace_bytes, stream);
 }
 
 int wgkv_decode_step(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,

@@ -30,12 +30,13 @@ class Pair:
         self.touched = set()
 
     # inputs are torch CPU tensors in the pool dtype (k, v, q) and float32 (g)
-    def prefill(self, layer, seq_ids, n_tokens, k, v, g, tau, check_mask=True):
+    def prefill(self, layer, seq_ids, n_tokens, k, v, g, tau, check_mask=True, max_admitted_per_head=None):
         tot = int(sum(n_tokens))
         Hk = self.cfg.n_kv_heads
         mask = torch.zeros((max(tot, 1), Hk), dtype=torch.uint8, device=self.dev)
         self.pool.prefill_admit(layer, seq_ids, n_tokens, k.to(self.dev), v.to(self.dev),
-                                g.to(self.dev), tau=tau, admit_mask_out=mask)
+                                g.to(self.dev), tau=tau, admit_mask_out=mask,
+                                max_admitted_per_head=max_admitted_per_head)
         admit, _ = self.orc.push_tokens(layer, seq_ids, n_tokens, k.float().numpy(), v.float().numpy(),
                                         g.numpy(), tau)
         for s, n in zip(seq_ids, n_tokens):

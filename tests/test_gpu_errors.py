@@ -1,7 +1,8 @@
 """Refusals of the boundary, forced from the host (every kernel that runs exits normally): a pool
 a few pages short, a page-table row too narrow, a workspace one byte short, a replayed graph that
 runs out of pages (the device-side sticky flag), a recycled page that holds non-finite rows, and
-argument limits of the gate form of wgkv_prefill_admit.  A refused call must leave the cache state
+argument limits of the gate form of wgkv_prefill_admit, and the caller's bound on admitted tokens
+(wgkv_prefill_admit_bounded) held and broken.  A refused call must leave the cache state
 untouched: the metadata block is compared byte for byte."""
 import ctypes as C
 import math
@@ -16,7 +17,7 @@ from harness import MAX_ABS_TOL, MEAN_ABS_TOL, Pair, rand_q, rand_tokens
 
 pytestmark = pytest.mark.gpu
 
-OUT_OF_PAGES, PT_OVERFLOW, DEVICE_FLAG, WORKSPACE, INVALID = -2, -3, -5, -6, -1
+OUT_OF_PAGES, PT_OVERFLOW, DEVICE_FLAG, WORKSPACE, INVALID, ADMIT_BOUND = -2, -3, -5, -6, -1, -8
 
 
 def _meta_bytes(pool):
@@ -290,3 +291,76 @@ def test_gate_form_of_prefill_admit_checks_its_limits():
     assert rc == INVALID
     assert L.wgkv_gate_scores(wg.BF16, 20, dim, 8, C.c_void_p(hid.data_ptr() + 2), _ptr(w8),
                               _ptr(torch.zeros((20, 8), device=dev)), _stream()) == INVALID
+
+
+def _sparse_scores(rng, n, Hk, per_chunk, chunk, W):
+    """Scores with exactly `per_chunk` values >= 0.5 per head in every chunk of `chunk` tokens, none of them among
+    the last W of a chunk: a call that feeds one chunk then admits exactly `per_chunk` tokens per head (the ones
+    among the chunk's first chunk - W tokens; the W tokens that leave the ring hold none)."""
+    g = (0.4 * rng.random((n, Hk))).astype(np.float32)
+    for c0 in range(0, n, chunk):
+        for h in range(Hk):
+            g[c0 + rng.choice(chunk - W, per_chunk, replace=False), h] = 0.9
+    return torch.from_numpy(g)
+
+
+def test_bound_on_admitted_tokens_lets_a_pool_sized_for_the_admitted_cache_run_without_status():
+    Hq, Hk, d, P, W, chunk, n_chunks, per_chunk = 4, 2, 64, 4, 16, 64, 6, 6
+    n = chunk * n_chunks
+    # ring pages + the admitted cache if every head admits `per_chunk` tokens in every chunk, and nothing more
+    n_pages = Hk * (W // P + (n_chunks * per_chunk + P - 1) // P)
+    rng = np.random.default_rng(35)
+    k, v, _ = rand_tokens(rng, n, Hk, d, torch.bfloat16)
+    g = _sparse_scores(rng, n, Hk, per_chunk, chunk, W)
+    # without the bound the host has to assume that every leaving token is admitted: refused at once or after a
+    # few chunks (no wgkv_status in the loop to tighten its count)
+    pr0 = Pair(1, Hq, Hk, d, wg.BF16, P, W, 1, 32, n_pages, max_call_seqs=1, max_call_tokens=chunk)
+    with pytest.raises(wg.WgkvError) as e:
+        for c in range(n_chunks):
+            sl = slice(c * chunk, (c + 1) * chunk)
+            pr0.pool.prefill_admit(0, [0], [chunk], k[sl].to(pr0.dev), v[sl].to(pr0.dev), g[sl].to(pr0.dev), tau=0.5)
+    assert e.value.code == OUT_OF_PAGES
+    # with it the same pool takes the whole prompt; the state and the attention are the oracle's
+    pr = Pair(1, Hq, Hk, d, wg.BF16, P, W, 1, 32, n_pages, max_call_seqs=1, max_call_tokens=chunk)
+    for c in range(n_chunks):
+        sl = slice(c * chunk, (c + 1) * chunk)
+        pr.prefill(0, [0], [chunk], k[sl], v[sl], g[sl], 0.5, max_admitted_per_head=per_chunk)
+    pr.check_state()
+    # what left the window was admitted at 6 per chunk; the last W tokens are still in the ring
+    adm = int((g[:n - W, 0] >= 0.5).sum())
+    assert pr.orc.global_len(0, 0, 0) == adm and pr.orc.free_top >= 0
+    pr.check_attend(0, [0], rand_q(rng, 1, Hq, d, torch.bfloat16))
+    with pytest.raises(wg.WgkvError) as e:
+        pr.pool.prefill_admit(0, [0], [1], k[:1].to(pr.dev), v[:1].to(pr.dev), g[:1].to(pr.dev), tau=0.5,
+                              max_admitted_per_head=-1)
+    assert e.value.code == INVALID
+
+
+def test_broken_bound_on_admitted_tokens_is_refused_on_the_device():
+    Hq, Hk, d, P, W, chunk = 4, 2, 64, 4, 16, 64
+    pr = Pair(1, Hq, Hk, d, wg.BF16, P, W, 2, 32, 200, max_call_seqs=2, max_call_tokens=2 * chunk)
+    rng = np.random.default_rng(36)
+    k, v, _ = rand_tokens(rng, 3 * chunk, Hk, d, torch.bfloat16)
+    g = _sparse_scores(rng, 3 * chunk, Hk, 6, chunk, W)
+    pr.prefill(0, [0, 1], [chunk, chunk], k[:2 * chunk], v[:2 * chunk], g[:2 * chunk], 0.5, max_admitted_per_head=6)
+    pr.check_state()
+    # third chunk for sequence 1: head 1 admits one token more than promised (7 of the tokens that leave)
+    g3 = g[2 * chunk:].clone()
+    g3[:] = 0.1
+    g3[:7, 1] = 0.9     # the W tokens that leave the ring hold no admitted one
+    before = _meta_bytes(pr.pool)
+    dev = pr.dev
+    pr.pool.prefill_admit(0, [1], [chunk], k[2 * chunk:].to(dev), v[2 * chunk:].to(dev), g3.to(dev), tau=0.5,
+                          max_admitted_per_head=6)    # accepted by the host, which cannot know
+    free, flag = pr.pool.status()
+    assert flag == ADMIT_BOUND
+    after = _meta_bytes(pr.pool)
+    # nothing but the flag has changed
+    diff = np.nonzero(before != after)[0]
+    assert 0 < diff.size <= 4, diff
+    pr.pool.clear_error()
+    pr.check_state()                # still the state after two chunks: the oracle never saw the third
+    # within the bound (7 admitted, bound 7) the same chunk goes through
+    pr.prefill(0, [1], [chunk], k[2 * chunk:], v[2 * chunk:], g3, 0.5, max_admitted_per_head=7)
+    pr.check_state()
+    pr.check_attend(0, [0, 1], rand_q(rng, 2, Hq, d, torch.bfloat16))
