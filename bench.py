@@ -2,8 +2,10 @@
 """Benchmark of the Write-Gated KV hot path on one MI355X.
 
 A step is one new token for the whole batch through every layer of the workload:
-per layer `wgkv_decode_step` (lazy promotion + ring write) then `wgkv_attend`
-(ragged paged GQA decode attention).  Inputs are synthetic, seeded and already
+`wgkv_decode_promote` once (victim test, page hand-out and row move of the lazy
+promotion of all layers), then per layer `wgkv_decode_step` (the ring write) and
+`wgkv_attend` (ragged paged GQA decode attention).  `--no-promote-ahead` leaves the
+first call out: every layer's `wgkv_decode_step` then does its promotion itself.  Inputs are synthetic, seeded and already
 resident in HBM when the timed region starts.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
@@ -107,6 +109,9 @@ def main():
                     help="decode workloads: read only this many pages of each head's global cache per step, picked "
                          "with key landmarks (128 pages of 16 = the 2048 KVs per query of the paper's selection run); "
                          "the step then is promotion + landmark upkeep + page scoring/selection + attention")
+    ap.add_argument("--no-promote-ahead", action="store_true",
+                    help="decode workloads: no wgkv_decode_promote at the start of a step (each layer's "
+                         "wgkv_decode_step then decides and moves its promotions itself)")
     ap.add_argument("--graph", action="store_true",
                     help="decode workloads: capture one whole step (all layers) in a HIP graph and time replays "
                          "instead of direct calls (per-kernel events are then not available)")
@@ -192,6 +197,7 @@ def main():
     log(f"[bench] setup {time.time() - t_setup:.1f}s")
 
     sel_b = args.select_pages
+    promote_ahead = not args.no_promote_ahead
     if sel_b:
         lm = pool.quest_landmarks()
         pool.status()
@@ -205,6 +211,8 @@ def main():
         _p, _i, _chk = wg.binding._ptr, wg.binding._ids, wg.binding._check
 
     def one_step(st, events=None):
+        if promote_ahead:
+            pool.decode_promote(seqs, tau=cfg.tau)
         for l in range(L):
             pool.decode_step(l, seqs, k_new[l], v_new[l], g_new[st, l], tau=cfg.tau)
             if sel_b:
@@ -238,6 +246,8 @@ def main():
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             with torch.cuda.graph(graph, stream=side):
+                if promote_ahead:
+                    pool.decode_promote(seqs, tau=cfg.tau)
                 for l in range(L):
                     pool.decode_step(l, seqs, k_new[l], v_new[l], g_static[l], tau=cfg.tau)
                     pool.attend(l, seqs, q_new[l], out[l], scale)
@@ -347,7 +357,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "layers": L, "q_heads": Hq, "kv_heads": Hk, "head_dim": d,
                    "w_local": W, "page_size": P, "tau": cfg.tau, "ctx_min": int(ctx.min()), "ctx_max": int(ctx.max()),
-                   "select_pages": sel_b, "hip_graph": bool(args.graph),
+                   "select_pages": sel_b, "hip_graph": bool(args.graph), "promote_ahead": promote_ahead,
                    "mean_cached_tokens_per_head": float((np.minimum(sl1, W)[:, :, None] + gl1).mean()),
                    # the paper's x axis: cached entries of a head over the tokens it has seen, (W + G_h) / t
                    "normalized_kv_size": float(((np.minimum(sl1, W)[:, :, None] + gl1) / np.maximum(sl1, 1)[:, :, None]).mean()),

@@ -63,7 +63,9 @@ enum {
     WGKV_ERR_DEVICE_FLAG = -5,  /* the device-side sticky error flag is set */
     WGKV_ERR_WORKSPACE = -6,    /* workspace too small for this call */
     WGKV_ERR_HOST_MEMORY = -7,  /* the host handle could not be allocated */
-    WGKV_ERR_ADMIT_BOUND = -8   /* device flag only: a unit admitted more tokens than the caller's bound */
+    WGKV_ERR_ADMIT_BOUND = -8,  /* device flag only: a unit admitted more tokens than the caller's bound */
+    WGKV_ERR_NOT_PROMOTED = -9  /* device flag only: a decode step that relied on wgkv_decode_promote found a
+                                   head whose promotion had not been done ahead */
 };
 
 #define WGKV_MAX_CALL_SEQS 128  /* sequences per call */
@@ -90,11 +92,14 @@ typedef struct {
  *   free_stack int32 [n_pages]       LIFO of free pages
  *   free_top   int32                 number of free pages
  *   err_flag   int32                 sticky: 0 ok, else first WGKV_ERR_* seen on device
+ *   ahead      int32 [S][L][H]       (t << 1) | promoted once wgkv_decode_promote has handled the
+ *                                    step that feeds token t of this head, else -1
  *   unit_counters int32 [WGKV_MAX_CALL_UNITS]  scratch of wgkv_attend, zero between calls
  * Pool: element [page][0=K,1=V][slot 0..P-1][head_dim]. */
 typedef struct {
     size_t seq_len, global_len, local_pt, global_pt, ring_g, free_stack, free_top, err_flag;
     size_t unit_counters;
+    size_t ahead;
     size_t total_bytes;
     int32_t n_local_pages;
 } wgkv_meta_layout;
@@ -261,6 +266,31 @@ int wgkv_prefill_admit_bounded(wgkv_pool *pool, int32_t layer, int32_t n_seqs,
 int wgkv_decode_step(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,
                      const void *k_new_dev, const void *v_new_dev, const float *g_new_dev,
                      float tau, uint8_t *promoted_out_dev, wgkv_stream stream);
+
+/* Sec. 4.3 steps (1)-(2) of ALL layers ahead of time.  Whether the victim of the coming token
+ * is promoted depends on the score stored with it and on the token count only, not on the
+ * layer's new key and value: this call does the victim test, the page hand-out and the row move
+ * of every layer of the named sequences in two launches, and the wgkv_decode_step calls of the
+ * same token (one per layer, as before, same tau) then only write the ring, which takes a layer's
+ * step off the path between its projections and its attention.  Optional: without it
+ * wgkv_decode_step does all three steps itself.  The promotion masks and the cached rows are
+ * the same either way, and so are the page tables bit for bit (pages are taken in the order
+ * layer, sequence of the call, head, as the layers' own steps take them) when the steps name
+ * the same sequences in the same order as this call and none of them receives its very first
+ * token in this step (its ring pages are handed out by its decode steps, after the global
+ * pages of all layers instead of in between); otherwise the same pages end up under other
+ * numbers.
+ * Every layer of a sequence must hold the same number of tokens (INVALID_ARG otherwise).
+ * After this call the next call on those sequences must be wgkv_decode_step for each layer:
+ * wgkv_prefill_admit on a layer promoted ahead is refused (INVALID_ARG).  Calling it twice
+ * for the same token changes nothing the second time.
+ * HIP graphs: capture it together with the layers' steps.  A replayed wgkv_decode_step whose
+ * promotion is not in the graph finds no promotion done, changes nothing and sets the device
+ * flag to WGKV_ERR_NOT_PROMOTED.  Running out of pages sets the flag like a replayed step does
+ * (all layers or none).
+ * Errors: INVALID_ARG, OUT_OF_PAGES / PT_OVERFLOW (host-side bounds), HIP. */
+int wgkv_decode_promote(wgkv_pool *pool, int32_t n_seqs, const int32_t *seq_ids_host, float tau,
+                        wgkv_stream stream);
 
 /* Attention of the queries of layer `layer` over what the cache holds.
  * Decode (every n_q_host[b] == 1, k_chunk_dev == NULL): call after

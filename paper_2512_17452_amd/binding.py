@@ -11,7 +11,7 @@ F32, BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
-    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_prefill_admit_bounded", "wgkv_decode_step", "wgkv_attend", "wgkv_attend_decode_static", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
+    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_prefill_admit_bounded", "wgkv_decode_step", "wgkv_decode_promote", "wgkv_attend", "wgkv_attend_decode_static", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
     "wgkv_quest_select", "wgkv_attend_selected", "wgkv_soft_attn_forward", "wgkv_soft_attn_workspace_bytes",
     "wgkv_soft_attn_backward", "wgkv_sparsity_loss", "wgkv_free_seq",
     "wgkv_status", "wgkv_clear_error", "wgkv_stream_read_probe", "wgkv_set_profile_events", "wgkv_destroy",
@@ -19,7 +19,8 @@ EXPORTED_SYMBOLS = [
 
 _ERR = {-1: "invalid argument", -2: "out of pages", -3: "page-table overflow", -4: "HIP error",
         -5: "device error flag set", -6: "workspace too small", -7: "host out of memory",
-        -8: "a head admitted more tokens than the bound given to wgkv_prefill_admit_bounded"}
+        -8: "a head admitted more tokens than the bound given to wgkv_prefill_admit_bounded",
+        -9: "a decode step relied on wgkv_decode_promote, which had not handled this token"}
 
 
 class WgkvError(RuntimeError):
@@ -37,7 +38,7 @@ class _CConfig(C.Structure):
 
 class _CLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in ("seq_len", "global_len", "local_pt", "global_pt", "ring_g",
-                                          "free_stack", "free_top", "err_flag", "unit_counters",
+                                          "free_stack", "free_top", "err_flag", "unit_counters", "ahead",
                                           "total_bytes")] + \
                [("n_local_pages", C.c_int32)]
 
@@ -93,6 +94,7 @@ def load_library():
                                           vp, vp, vp, vp, vp, sz, vp]
     L.wgkv_sparsity_loss.argtypes = [vp, i64, i64, vp, vp, vp, sz, vp]
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+    L.wgkv_decode_promote.argtypes = [vp, i32, pi32, f32, vp]
     L.wgkv_prefill_admit_bounded.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
@@ -288,6 +290,10 @@ class Pool:
         _check(self.L.wgkv_decode_step(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(k_new),
                                        _ptr(v_new), _ptr(g_new), tau, _ptr(promoted_out), _stream()),
                "wgkv_decode_step")
+
+    def decode_promote(self, seq_ids, tau=0.5):
+        """wgkv_decode_promote: victim test, page hand-out and row move of every layer, ahead of the layers' steps."""
+        _check(self.L.wgkv_decode_promote(self.h, len(seq_ids), _ids(seq_ids), tau, _stream()), "wgkv_decode_promote")
 
     def attend(self, layer, seq_ids, q, out, scale, n_q=None, k_chunk=None, v_chunk=None,
                g_chunk=None, tau=0.5):

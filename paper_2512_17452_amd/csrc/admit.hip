@@ -6,6 +6,9 @@
 //  prefill_scatter_kernel stable compaction of admitted K/V rows into global pages, then the
 //                         last min(W,T) tokens into the ring                  (Sec. 4.2)
 //  decode_step_kernel     lazy promotion of the victim, then overwrite        (Sec. 4.3 (1)-(3))
+//  decode_promote_kernel, decode_promote_move_kernel
+//                         steps (1)-(2) of every layer ahead of the layers' ring writes
+//  decode_ring_kernel     step (3) alone, for units promoted ahead
 //  free_seq_kernel        pages of a sequence slot back to the free stack
 //
 // Page hand-out never races: demands are prefix-summed in (sequence position in
@@ -49,6 +52,7 @@ __global__ void init_kernel(View pv) {
     for (size_t i = i0; i < n_u * pv.maxgp; i += stride) pv.global_pt[i] = -1;
     for (size_t i = i0; i < n_u * pv.W; i += stride) pv.ring_g[i] = 0.0f;
     for (size_t i = i0; i < (size_t)kMaxCallUnits; i += stride) pv.unit_counters[i] = 0;
+    for (size_t i = i0; i < n_u; i += stride) pv.ahead[i] = -1;
     // the pool starts as zeros: attention may read rows of a page beyond the last token
     // written (they get weight zero) and those must be finite
     uint4 *pool16 = reinterpret_cast<uint4 *>(pv.pool);
@@ -370,7 +374,7 @@ __global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs,
     __syncthreads();
     const int top = *pv.free_top;
     const int u = threadIdx.x;  // n_units <= 1024 = blockDim.x
-    int demand = 0, dl = 0, promote = 0, gold = 0, um = 0, slot = 0, lpage = -1, gpage = -1;
+    int demand = 0, dl = 0, promote = 0, gold = 0, um = 0, slot = 0, lpage = -1, gpage = -1, ahead_mask = -1;
     if (u < n_units) {
         // the token count comes from device memory, not from the launch arguments, so that a
         // captured launch can be replayed: every replay is one more token
@@ -387,7 +391,11 @@ __global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs,
             rg = pv.ring_g[(size_t)um * pv.W + slot];
             lpage = pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)];
         }
-        promote = (t >= pv.W) && (rg >= a.tau);
+        // promoted ahead for this very token (wgkv_decode_promote): steps (1)-(2) are done, only the mask is left
+        const int ah = pv.ahead[um];
+        const bool done = ah >= 0 && (ah >> 1) == t;
+        ahead_mask = done ? (ah & 1) : -1;
+        promote = !done && (t >= pv.W) && (rg >= a.tau);
         dl = (lp0 < 0) ? pv.nlp : 0;
         const int need = promote && ((gold & (pv.P - 1)) == 0);
         if (need && (gold >> pv.logP) >= pv.maxgp) s_err = WGKV_ERR_PT_OVERFLOW;
@@ -413,7 +421,7 @@ __global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs,
             pv.global_pt[(size_t)um * pv.maxgp + (gold >> pv.logP)] = gpage;
         }
         if (promote) pv.global_len[um] = gold + 1;
-        if (a.promoted_out) a.promoted_out[u] = (uint8_t)promote;
+        if (a.promoted_out) a.promoted_out[u] = (uint8_t)(ahead_mask >= 0 ? ahead_mask : promote);
         s_gold[u] = (int)((unsigned)gold | ((unsigned)promote << 31));
         s_lpage[u] = lpage;
         s_gpage[u] = gpage;
@@ -440,6 +448,162 @@ __global__ __launch_bounds__(1024) void decode_step_kernel(View pv, CallSeqs cs,
             *reinterpret_cast<uint4 *>(dp + pv.v_off) = vv;
         }
         if (c != (int)threadIdx.x) {  // beyond the first 1024 chunks: not in registers yet
+            const size_t row = (size_t)uu * pv.row_bytes + sub * 16;
+            kn = *reinterpret_cast<const uint4 *>(a.k + row);
+            vn = *reinterpret_cast<const uint4 *>(a.v + row);
+        }
+        *reinterpret_cast<uint4 *>(rp) = kn;
+        *reinterpret_cast<uint4 *>(rp + pv.v_off) = vn;
+        if (sub == 0) pv.ring_g[(size_t)m * pv.W + sl] = a.g[uu];
+    }
+}
+
+// Steps (1)-(2) of Sec. 4.3 for every layer of the call's sequences at once, ahead of the layers' own
+// decode steps: whether the victim of the coming token is promoted depends only on the score stored
+// with it and on the token count, not on the layer's new K/V.  One block: the page hand-out needs a
+// prefix over all units.  All-or-nothing like the step itself: a first sweep over the units only adds up
+// the demand; the second takes the same decisions again (nothing they read has changed) and writes.
+// A unit that was handled gets ahead[um] = (t << 1) | promoted; the rows are moved by
+// decode_promote_move_kernel, and the layer's decode step then only writes the ring.
+__device__ __forceinline__ void promote_decide(const View &pv, const CallSeqs &cs, float tau, int u, int &um, int &t,
+                                               int &gold, int &promote, int &need) {
+    // units in the order in which the layers' own steps would take their pages: layer, sequence of the call, head
+    const int per_layer = cs.n * pv.Hkv;
+    const int l = u / per_layer, r = u - l * per_layer;
+    const int b = r / pv.Hkv;
+    const int sl = cs.sid[b] * pv.L + l;
+    um = sl * pv.Hkv + r % pv.Hkv;
+    const int slot_h = cs.t0[b] % pv.W;  // where the host's count of the first layer puts the victim
+    t = pv.seq_len[sl];
+    const int ah = pv.ahead[um];
+    gold = pv.global_len[um];
+    float rg = pv.ring_g[(size_t)um * pv.W + slot_h];
+    const int slot = t % pv.W;
+    if (slot != slot_h) rg = pv.ring_g[(size_t)um * pv.W + slot];
+    const bool done = ah >= 0 && (ah >> 1) == t;
+    promote = done ? -1 : (int)((t >= pv.W) && (rg >= tau));
+    need = promote > 0 && ((gold & (pv.P - 1)) == 0);
+}
+
+__global__ __launch_bounds__(1024) void decode_promote_kernel(View pv, CallSeqs cs, float tau) {
+    __shared__ int s_tmp[20];
+    __shared__ int s_err;
+    const int n_all = cs.n * pv.L * pv.Hkv;
+    const int top = *pv.free_top;
+    if (threadIdx.x == 0) s_err = 0;
+    __syncthreads();
+    int carry = 0;
+    for (int u0 = 0; u0 < n_all; u0 += 1024) {
+        const int u = u0 + threadIdx.x;
+        int um, t, gold, promote, need = 0;
+        if (u < n_all) {
+            promote_decide(pv, cs, tau, u, um, t, gold, promote, need);
+            if (need && (gold >> pv.logP) >= pv.maxgp) s_err = WGKV_ERR_PT_OVERFLOW;
+        }
+        int total;
+        block_excl_scan(need, s_tmp, &total);
+        carry += total;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && s_err == 0 && carry > top) s_err = WGKV_ERR_OUT_OF_PAGES;
+    __syncthreads();
+    if (s_err != 0) {  // block-uniform: leave all state as it was
+        if (threadIdx.x == 0) atomicCAS(pv.err_flag, 0, s_err);
+        return;
+    }
+    carry = 0;
+    for (int u0 = 0; u0 < n_all; u0 += 1024) {
+        const int u = u0 + threadIdx.x;
+        int um = 0, t = 0, gold = 0, promote = -1, need = 0;
+        if (u < n_all) promote_decide(pv, cs, tau, u, um, t, gold, promote, need);
+        int total;
+        const int ex = block_excl_scan(need, s_tmp, &total);
+        if (u < n_all && promote >= 0) {
+            if (need) pv.global_pt[(size_t)um * pv.maxgp + (gold >> pv.logP)] = pv.free_stack[top - 1 - (carry + ex)];
+            if (promote) pv.global_len[um] = gold + 1;
+            pv.ahead[um] = (t << 1) | promote;
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0) *pv.free_top = top - carry;
+}
+
+// The rows of the units that decode_promote_kernel promoted: ring slot t mod W -> global entry G - 1 (G already
+// counts the new entry).  Reads everything from the pool's state, so running it again before the layer's decode
+// step copies the same row to the same place.
+__global__ __launch_bounds__(256) void decode_promote_move_kernel(View pv, CallSeqs cs) {
+    const int lpr = pv.row_bytes >> 4;
+    const int n_all = cs.n * pv.L * pv.Hkv;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int u = c / lpr, sub = c % lpr;
+    if (u >= n_all) return;
+    const int per_layer = cs.n * pv.Hkv;
+    const int l = u / per_layer, r = u - l * per_layer;
+    const int b = r / pv.Hkv;
+    const int sl = cs.sid[b] * pv.L + l;
+    const int um = sl * pv.Hkv + r % pv.Hkv;
+    const int slot_h = cs.t0[b] % pv.W;
+    const int t = pv.seq_len[sl];
+    const int ah = pv.ahead[um];
+    const int gl = pv.global_len[um];
+    int lpage = pv.local_pt[(size_t)um * pv.nlp + (slot_h >> pv.logP)];
+    if (ah < 0 || (ah >> 1) != t || !(ah & 1)) return;
+    const int slot = t % pv.W;
+    if (slot != slot_h) lpage = pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)];
+    const int g0 = gl - 1;
+    const int gpage = pv.global_pt[(size_t)um * pv.maxgp + (g0 >> pv.logP)];
+    const char *rp = page_ptr(pv, lpage) + (size_t)(slot & (pv.P - 1)) * pv.row_bytes + sub * 16;
+    const uint4 kk = *reinterpret_cast<const uint4 *>(rp);
+    const uint4 vv = *reinterpret_cast<const uint4 *>(rp + pv.v_off);
+    char *dp = page_ptr(pv, gpage) + (size_t)(g0 & (pv.P - 1)) * pv.row_bytes + sub * 16;
+    *reinterpret_cast<uint4 *>(dp) = kk;
+    *reinterpret_cast<uint4 *>(dp + pv.v_off) = vv;
+}
+
+// Step (3) of Sec. 4.3 alone, for a call whose units have all been promoted ahead and own their ring pages: one
+// round trip (token count, stamp, page of the slot, the new rows) and the stores.  A unit whose stamp does not
+// carry the device's token count (a replayed launch whose graph lacks the promotion, a promotion that was
+// refused) makes the whole call do nothing and sets the sticky flag.
+__global__ __launch_bounds__(1024) void decode_ring_kernel(View pv, CallSeqs cs, DecodeArgs a) {
+    __shared__ int s_lpage[kMaxCallUnits];
+    __shared__ int s_t[kMaxCallSeqs];
+    const int n_units = cs.n * pv.Hkv;
+    const int lpr = pv.row_bytes >> 4, n_items = n_units * lpr;
+    uint4 kn = make_uint4(0, 0, 0, 0), vn = kn;
+    if ((int)threadIdx.x < n_items) {
+        const size_t row = (size_t)(threadIdx.x / lpr) * pv.row_bytes + (threadIdx.x % lpr) * 16;
+        kn = *reinterpret_cast<const uint4 *>(a.k + row);
+        vn = *reinterpret_cast<const uint4 *>(a.v + row);
+    }
+    const int u = threadIdx.x;
+    int bad = 0, mask = 0;
+    if (u < n_units) {
+        const int b = u / pv.Hkv, h = u % pv.Hkv;
+        const int um = unit_meta(pv, cs.sid[b], a.layer, h);
+        const int slot_h = cs.t0[b] % pv.W;
+        const int t = pv.seq_len[cs.sid[b] * pv.L + a.layer];
+        const int ah = pv.ahead[um];
+        int lpage = pv.local_pt[(size_t)um * pv.nlp + (slot_h >> pv.logP)];
+        const int slot = t % pv.W;
+        if (slot != slot_h) lpage = pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)];  // a replayed launch
+        bad = ah < 0 || (ah >> 1) != t || lpage < 0;
+        s_lpage[u] = lpage;
+        if (h == 0) s_t[b] = t;
+        mask = ah & 1;
+    }
+    if (__syncthreads_or(bad)) {  // block-uniform
+        if (threadIdx.x == 0) atomicCAS(pv.err_flag, 0, WGKV_ERR_NOT_PROMOTED);
+        return;
+    }
+    if (u < n_units && a.promoted_out) a.promoted_out[u] = (uint8_t)mask;
+    if ((int)threadIdx.x < cs.n) pv.seq_len[cs.sid[threadIdx.x] * pv.L + a.layer] = s_t[threadIdx.x] + 1;
+    for (int c = threadIdx.x; c < n_items; c += blockDim.x) {
+        const int uu = c / lpr, sub = c % lpr;
+        const int b = uu / pv.Hkv, h = uu % pv.Hkv;
+        const int m = unit_meta(pv, cs.sid[b], a.layer, h);
+        const int sl = s_t[b] % pv.W;
+        char *rp = page_ptr(pv, s_lpage[uu]) + (size_t)(sl & (pv.P - 1)) * pv.row_bytes + sub * 16;
+        if (c != (int)threadIdx.x) {
             const size_t row = (size_t)uu * pv.row_bytes + sub * 16;
             kn = *reinterpret_cast<const uint4 *>(a.k + row);
             vn = *reinterpret_cast<const uint4 *>(a.v + row);
@@ -479,6 +643,7 @@ __global__ __launch_bounds__(256) void free_seq_kernel(View pv, int sid) {
                 }
             }
             pv.global_len[um] = 0;
+            pv.ahead[um] = -1;
             for (int s = 0; s < pv.W; s++) pv.ring_g[(size_t)um * pv.W + s] = 0.0f;
         }
         carry += total;
@@ -543,6 +708,29 @@ hipError_t launch_decode_step(const View &pv, const CallSeqs &cs, int layer, flo
     a.g = g;
     a.promoted_out = promoted_out;
     hipLaunchKernelGGL(decode_step_kernel, dim3(1), dim3(1024), 0, st, pv, cs, a);
+    return hipGetLastError();
+}
+
+// ring_only: every unit of the call was promoted ahead and owns its ring pages (as far as the host knows; the
+// kernel checks)
+hipError_t launch_decode_ring(const View &pv, const CallSeqs &cs, int layer, const void *k, const void *v,
+                              const float *g, uint8_t *promoted_out, hipStream_t st) {
+    DecodeArgs a;
+    a.layer = layer;
+    a.tau = 0.f;
+    a.k = (const char *)k;
+    a.v = (const char *)v;
+    a.g = g;
+    a.promoted_out = promoted_out;
+    hipLaunchKernelGGL(decode_ring_kernel, dim3(1), dim3(1024), 0, st, pv, cs, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_promote(const View &pv, const CallSeqs &cs, float tau, hipStream_t st) {
+    hipLaunchKernelGGL(decode_promote_kernel, dim3(1), dim3(1024), 0, st, pv, cs, tau);
+    const int lpr = pv.row_bytes >> 4;
+    const int64_t items = (int64_t)cs.n * pv.L * pv.Hkv * lpr;
+    hipLaunchKernelGGL(decode_promote_move_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, pv, cs);
     return hipGetLastError();
 }
 

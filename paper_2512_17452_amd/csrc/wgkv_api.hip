@@ -20,6 +20,9 @@ hipError_t launch_decode_step(const View &pv, const CallSeqs &cs, int layer, flo
                               const void *k, const void *v, const float *g, uint8_t *promoted_out,
                               hipStream_t st);
 hipError_t launch_free_seq(const View &pv, int sid, hipStream_t st);
+hipError_t launch_decode_ring(const View &pv, const CallSeqs &cs, int layer, const void *k, const void *v,
+                              const float *g, uint8_t *promoted_out, hipStream_t st);
+hipError_t launch_decode_promote(const View &pv, const CallSeqs &cs, float tau, hipStream_t st);
 hipError_t launch_clear_error(const View &pv, hipStream_t st);
 size_t evict_ws_bytes(int n_units);
 size_t evict_scores_ws_bytes(const View &pv, int n_units, int n_obs);
@@ -108,6 +111,7 @@ void make_layout(const wgkv_config *c, wgkv_meta_layout *o) {
     o->free_top = off;   off = align256(off + 4);
     o->err_flag = off;   off = align256(off + 4);
     o->unit_counters = off; off = align256(off + (size_t)WGKV_MAX_CALL_UNITS * 4);
+    o->ahead = off;      off = align256(off + S * L * H * 4);
     o->total_bytes = off;
     o->n_local_pages = (int32_t)nlp;
 }
@@ -138,6 +142,7 @@ View make_view(const wgkv_config *c, void *pool, void *meta) {
     v.free_top = (int32_t *)(m + lay.free_top);
     v.err_flag = (int32_t *)(m + lay.err_flag);
     v.unit_counters = (int32_t *)(m + lay.unit_counters);
+    v.ahead = (int32_t *)(m + lay.ahead);
     return v;
 }
 
@@ -165,6 +170,7 @@ struct wgkv_pool {
     std::vector<int32_t> seq_len_h;  // [S][L] exact mirror (deterministic)
     std::vector<uint8_t> touched_h;  // [S][L] local pages handed out
     std::vector<int32_t> g_ub;       // [S][L][H] upper bound of the global length
+    std::vector<int32_t> ahead_h;    // [S][L] token count whose promotion wgkv_decode_promote has enqueued, else -1
     int64_t pages_ub;                // upper bound of pages in use
     int n_cu;                        // compute units of the device
     hipEvent_t ev0, ev1;
@@ -234,6 +240,7 @@ int wgkv_init_pool(const wgkv_config *cfg, void *pool_dev, size_t pool_bytes, vo
         p->seq_len_h.assign(n_sl, 0);
         p->touched_h.assign(n_sl, 0);
         p->g_ub.assign(n_sl * cfg->n_kv_heads, 0);
+        p->ahead_h.assign(n_sl, -1);
     } catch (const std::bad_alloc &) {
         delete p;
         return WGKV_ERR_HOST_MEMORY;
@@ -406,6 +413,8 @@ static int prefill_admit_impl(wgkv_pool *p, int32_t layer, int32_t n_seqs, const
         if (T < 0) return WGKV_ERR_INVALID_ARG;
         const int64_t t0 = p->seq_len_h[(size_t)seq_ids_host[b] * c.n_layers + layer];
         if (t0 + T >= ((int64_t)1 << 30)) return WGKV_ERR_INVALID_ARG;
+        // promoted ahead: the victim is in the global cache already and only a decode step may follow
+        if (T > 0 && p->ahead_h[(size_t)seq_ids_host[b] * c.n_layers + layer] == t0) return WGKV_ERR_INVALID_ARG;
         cs.sid[b] = seq_ids_host[b];
         cs.t0[b] = (int32_t)t0;
         cs.ntok[b] = T;
@@ -509,6 +518,7 @@ int wgkv_decode_step(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t 
     memset(&cs, 0, sizeof(cs));
     cs.n = n_seqs;
     int64_t new_pages = 0;
+    bool ring_only = true;  // every sequence of the call promoted ahead for this token, ring pages in place
     for (int b = 0; b < n_seqs; b++) {
         const size_t sl = (size_t)seq_ids_host[b] * c.n_layers + layer;
         const int64_t t0 = p->seq_len_h[sl];
@@ -517,8 +527,10 @@ int wgkv_decode_step(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t 
         cs.t0[b] = (int32_t)t0;
         cs.ntok[b] = 1;
         cs.base[b] = b;
+        const bool ahead = p->ahead_h[sl] == t0;  // its pages were counted by wgkv_decode_promote
+        ring_only = ring_only && ahead && p->touched_h[sl];
         if (!p->touched_h[sl]) new_pages += (int64_t)p->view.nlp * H;
-        if (t0 >= W)
+        if (t0 >= W && !ahead)
             for (int h = 0; h < H; h++) {
                 const int64_t g0 = p->g_ub[sl * H + h];
                 const int64_t pg1 = (g0 + 1 + P - 1) / P;
@@ -527,16 +539,61 @@ int wgkv_decode_step(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t 
             }
     }
     if (p->pages_ub + new_pages > c.n_pages) return WGKV_ERR_OUT_OF_PAGES;
-    if (launch_decode_step(p->view, cs, layer, tau, k_new_dev, v_new_dev, g_new_dev,
-                           promoted_out_dev, (hipStream_t)stream) != hipSuccess)
-        return WGKV_ERR_HIP;
+    const hipError_t e = ring_only ? launch_decode_ring(p->view, cs, layer, k_new_dev, v_new_dev, g_new_dev,
+                                                        promoted_out_dev, (hipStream_t)stream)
+                                   : launch_decode_step(p->view, cs, layer, tau, k_new_dev, v_new_dev, g_new_dev,
+                                                        promoted_out_dev, (hipStream_t)stream);
+    if (e != hipSuccess) return WGKV_ERR_HIP;
     for (int b = 0; b < n_seqs; b++) {
         const size_t sl = (size_t)cs.sid[b] * c.n_layers + layer;
         p->touched_h[sl] = 1;
-        if (cs.t0[b] >= W)
+        if (cs.t0[b] >= W && p->ahead_h[sl] != cs.t0[b])
             for (int h = 0; h < H; h++) p->g_ub[sl * H + h] += 1;
         p->seq_len_h[sl] = cs.t0[b] + 1;
     }
+    p->pages_ub += new_pages;
+    return WGKV_OK;
+}
+
+int wgkv_decode_promote(wgkv_pool *p, int32_t n_seqs, const int32_t *seq_ids_host, float tau, wgkv_stream stream) {
+    int rc = check_seqs(p, 0, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    const wgkv_config &c = p->cfg;
+    const int W = c.w_local, P = c.page_size, H = c.n_kv_heads, L = c.n_layers;
+    CallSeqs cs;
+    memset(&cs, 0, sizeof(cs));
+    cs.n = n_seqs;
+    int64_t new_pages = 0;
+    for (int b = 0; b < n_seqs; b++) {
+        const size_t sl0 = (size_t)seq_ids_host[b] * L;
+        const int64_t t0 = p->seq_len_h[sl0];
+        if (t0 + 1 >= ((int64_t)1 << 30)) return WGKV_ERR_INVALID_ARG;
+        cs.sid[b] = seq_ids_host[b];
+        cs.t0[b] = (int32_t)t0;
+        cs.ntok[b] = 1;
+        cs.base[b] = b;
+        for (int l = 0; l < L; l++) {
+            const size_t sl = sl0 + l;
+            if (p->seq_len_h[sl] != t0) return WGKV_ERR_INVALID_ARG;  // the layers of a sequence advance together
+            if (t0 >= W && p->ahead_h[sl] != t0)
+                for (int h = 0; h < H; h++) {
+                    const int64_t g0 = p->g_ub[sl * H + h];
+                    const int64_t pg1 = (g0 + 1 + P - 1) / P;
+                    if (pg1 > c.max_global_pages_per_head) return WGKV_ERR_PT_OVERFLOW;
+                    new_pages += pg1 - (g0 + P - 1) / P;
+                }
+        }
+    }
+    if (p->pages_ub + new_pages > c.n_pages) return WGKV_ERR_OUT_OF_PAGES;
+    if (launch_decode_promote(p->view, cs, tau, (hipStream_t)stream) != hipSuccess) return WGKV_ERR_HIP;
+    for (int b = 0; b < n_seqs; b++)
+        for (int l = 0; l < L; l++) {
+            const size_t sl = (size_t)cs.sid[b] * L + l;
+            if (p->ahead_h[sl] == cs.t0[b]) continue;
+            if (cs.t0[b] >= W)
+                for (int h = 0; h < H; h++) p->g_ub[sl * H + h] += 1;
+            p->ahead_h[sl] = cs.t0[b];
+        }
     p->pages_ub += new_pages;
     return WGKV_OK;
 }
@@ -767,6 +824,7 @@ int wgkv_free_seq(wgkv_pool *p, int32_t seq_id, wgkv_stream stream) {
         }
         p->touched_h[sl] = 0;
         p->seq_len_h[sl] = 0;
+        p->ahead_h[sl] = -1;
     }
     return WGKV_OK;
 }
@@ -790,6 +848,7 @@ int wgkv_status(wgkv_pool *p, wgkv_stream stream, int64_t *pages_free, int32_t *
         // token counts as the device has them: replays of a captured decode step advance them
         // without the host seeing it
         p->seq_len_h[sl] = sl_dev[sl];
+        p->ahead_h[sl] = -1;  // unknown from here: the full decode step looks at the device's stamps itself
         p->touched_h[sl] = sl_dev[sl] > 0;
         if (p->touched_h[sl]) used += (int64_t)p->view.nlp * c.n_kv_heads;
         for (int h = 0; h < c.n_kv_heads; h++) {

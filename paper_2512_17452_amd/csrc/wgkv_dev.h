@@ -24,6 +24,8 @@ struct View {
     float *ring_g;
     int32_t *free_stack, *free_top, *err_flag;
     int32_t *unit_counters;              // [kMaxCallUnits], zero between calls
+    int32_t *ahead;                      // [S][L][Hkv]: (t << 1) | promoted once the promotion of the step that
+                                         // feeds token t has been done ahead of its ring write, else -1
 };
 
 // The sequences of one call, passed by value in the kernel arguments.
