@@ -301,8 +301,10 @@ int wgkv_decode_promote(wgkv_pool *pool, int32_t n_seqs, const int32_t *seq_ids_
  * chunk (position t+i) sees the global cache, ring positions j with
  * (pos_i - j < W or stored g_j >= tau) and chunk keys j <= i with
  * (i - j < W or g_j >= tau)  (Sec. 4.2 mask equation).
- * The prefill-chunk form needs dtype bf16, head_dim 128 and 4 query heads per kv head
- * (INVALID_ARG otherwise).
+ * With dtype bf16, head_dim 128 and 4 query heads per kv head (the paper's models) the
+ * prefill-chunk form runs on the matrix cores; every other shape the pool accepts takes a plain
+ * kernel (fp32 accumulation, one wave per query and head: correct, not fast).  k_chunk_dev and
+ * v_chunk_dev must be 16-byte aligned.
  *   q_dev   : [sum n_q][n_q_heads][head_dim] of cfg.dtype
  *   out_dev : float [sum n_q][n_q_heads][head_dim]
  *   scale   : multiplies q.k before the softmax (1/sqrt(head_dim) in the paper) */

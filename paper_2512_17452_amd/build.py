@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libwgkv.so")
-SOURCES = ["wgkv_api.hip", "admit.hip", "attend_decode.hip", "attend_prefill.hip", "gate.hip", "gate_mlp.hip", "evict.hip", "evict_scores.hip", "quest.hip", "soft_attn.hip", "probe.hip"]
+SOURCES = ["wgkv_api.hip", "admit.hip", "attend_decode.hip", "attend_prefill.hip", "attend_prefill_plain.hip", "gate.hip", "gate_mlp.hip", "evict.hip", "evict_scores.hip", "quest.hip", "soft_attn.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -68,6 +68,9 @@ size_t attend_prefill_ws_bytes(const View &pv, int n_seqs, int64_t total_q);
 hipError_t launch_attend_prefill(const View &pv, const CallSeqs &cs, int layer, const void *q,
                                  const void *k, const void *v, const float *g, float tau,
                                  float scale, float *out, void *ws, hipStream_t st);
+hipError_t launch_attend_prefill_plain(const View &pv, const CallSeqs &cs, int layer, const void *q, const void *k,
+                                       const void *v, const float *g, float tau, float scale, float *out,
+                                       hipStream_t st);
 }  // namespace wgkv
 
 using namespace wgkv;
@@ -620,8 +623,9 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
                    ? WGKV_OK
                    : WGKV_ERR_HIP;
     }
-    // the matrix-core path is built for the shape of the paper's models
-    if (p->cfg.dtype != WGKV_BF16 || p->cfg.head_dim != 128 || p->view.G != 4) return WGKV_ERR_INVALID_ARG;
+    // the matrix-core kernel is built for the shape of the paper's models; every other shape takes the plain one
+    const bool mfma_shape = p->cfg.dtype == WGKV_BF16 && p->cfg.head_dim == 128 && p->view.G == 4;
+    if ((((uintptr_t)k_chunk_dev | (uintptr_t)v_chunk_dev) & 15) != 0) return WGKV_ERR_INVALID_ARG;
     CallSeqs cs;
     memset(&cs, 0, sizeof(cs));
     cs.n = n_seqs;
@@ -638,9 +642,11 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
     if (total == 0) return WGKV_OK;
     if (workspace_bytes < attend_prefill_ws_bytes(p->view, n_seqs, total)) return WGKV_ERR_WORKSPACE;
     if (p->ev0 && hipEventRecord(p->ev0, st) != hipSuccess) return WGKV_ERR_HIP;
-    if (launch_attend_prefill(p->view, cs, layer, q_dev, k_chunk_dev, v_chunk_dev, g_chunk_dev, tau,
-                              scale, out_dev, workspace_dev, st) != hipSuccess)
-        return WGKV_ERR_HIP;
+    const hipError_t e = mfma_shape ? launch_attend_prefill(p->view, cs, layer, q_dev, k_chunk_dev, v_chunk_dev,
+                                                            g_chunk_dev, tau, scale, out_dev, workspace_dev, st)
+                                    : launch_attend_prefill_plain(p->view, cs, layer, q_dev, k_chunk_dev, v_chunk_dev,
+                                                                  g_chunk_dev, tau, scale, out_dev, st);
+    if (e != hipSuccess) return WGKV_ERR_HIP;
     if (p->ev1 && hipEventRecord(p->ev1, st) != hipSuccess) return WGKV_ERR_HIP;
     return WGKV_OK;
 }

@@ -15,6 +15,7 @@ from oracle import Oracle, OracleConfig, attend_definition, linear_gate
 pytestmark = pytest.mark.gpu
 SCALE = float(os.environ.get("WGKV_TEST_SCALE", "1.0"))
 MAX_ABS_TOL, MEAN_ABS_TOL = 1e-2, 1e-3
+F32_MAX_ABS_TOL = 2e-5  # fp32 inputs: rounding of fp32 dot products and of exp2 only
 GATE_TOL = 1e-4       # fp32 accumulation of bf16 products vs fp64
 GUARD = 1e-3          # |logit - logit(tau)| below which the fp32 and fp64 decisions may differ
 
@@ -38,14 +39,17 @@ def test_gate_scores_match_fp64(dtype, T, dim, Hk):
     assert np.array_equal((g >= 0.5)[far], (ref >= 0.5)[far])
 
 
-def _flow(B, lens, chunk, W, P, hidden_dim, seed, tau=0.5, use_gate=True, check_rows=None):
+def _flow(B, lens, chunk, W, P, hidden_dim, seed, tau=0.5, use_gate=True, check_rows=None,
+          shape=(32, 8, 128, wg.BF16)):
     """Feeds B sequences chunk by chunk: gate -> attend(prefill form) -> prefill_admit."""
-    Hq, Hk, d = 32, 8, 128
+    Hq, Hk, d, dtype = shape
+    tdt = torch.bfloat16 if dtype == wg.BF16 else torch.float32
+    max_abs_tol, mean_abs_tol = (MAX_ABS_TOL, MEAN_ABS_TOL) if dtype == wg.BF16 else (F32_MAX_ABS_TOL, F32_MAX_ABS_TOL)
     dev = torch.device("cuda:0")
     max_len = max(lens)
     max_gp = max_len // P + 4
     n_pages = B * Hk * (max_gp + W // P + 1) + 64
-    pool = wg.Pool(wg.Config(1, Hq, Hk, d, wg.BF16, P, W, B, max_gp, n_pages), B, B * chunk)
+    pool = wg.Pool(wg.Config(1, Hq, Hk, d, dtype, P, W, B, max_gp, n_pages), B, B * chunk)
     orc = Oracle(OracleConfig(1, Hq, Hk, d, P, W, B, max_gp, n_pages, True))
     gen = torch.Generator(device="cpu").manual_seed(seed)
     w = (0.02 * torch.randn((Hk, hidden_dim), generator=gen)).to(torch.bfloat16)
@@ -59,9 +63,9 @@ def _flow(B, lens, chunk, W, P, hidden_dim, seed, tau=0.5, use_gate=True, check_
         seqs = [s for s in range(B) if done[s] < lens[s]]
         nt = [min(chunk, lens[s] - done[s]) for s in seqs]
         tot = sum(nt)
-        q = torch.randn((tot, Hq, d), generator=gen).to(torch.bfloat16)
-        k = torch.randn((tot, Hk, d), generator=gen).to(torch.bfloat16)
-        v = torch.randn((tot, Hk, d), generator=gen).to(torch.bfloat16)
+        q = torch.randn((tot, Hq, d), generator=gen).to(tdt)
+        k = torch.randn((tot, Hk, d), generator=gen).to(tdt)
+        v = torch.randn((tot, Hk, d), generator=gen).to(tdt)
         if use_gate:
             # The scores of the flow are the oracle's (fp64 gate, stored as fp32) on both sides; the
             # gate kernel is checked against them, and its decisions wherever the logit is outside
@@ -97,7 +101,7 @@ def _flow(B, lens, chunk, W, P, hidden_dim, seed, tau=0.5, use_gate=True, check_
             ref = attend_definition(h[0], h[1], h[2], q[base:base + n].float().numpy()[rows], done[s] + rows, W, tau, scale)
             err = np.abs(o[base:base + n][rows].astype(np.float64) - ref)
             assert np.isfinite(o[base:base + n]).all()
-            assert err.max() <= MAX_ABS_TOL and err.mean() <= MEAN_ABS_TOL, (s, done[s], err.max(), err.mean())
+            assert err.max() <= max_abs_tol and err.mean() <= mean_abs_tol, (s, done[s], err.max(), err.mean())
             worst = [max(worst[0], err.max()), max(worst[1], err.mean())]
             done[s] += n
             base += n
@@ -123,6 +127,19 @@ def test_chunked_prefill_every_row(chunk, W, P):
     lens = [min(1536, 12 * chunk + 5), min(900, 7 * chunk)] if chunk > 1 else [70, 33]
     _, _, worst, near = _flow(2, lens, chunk, W, P, hidden_dim=256, seed=1000 + chunk)
     print(f"chunk {chunk} W {W} P {P}: max abs err {worst[0]:.2e}, mean {worst[1]:.2e}, {near} scores in the guard band", flush=True)
+
+
+@pytest.mark.parametrize("shape", [(8, 2, 64, wg.F32),     # the tiny fp32 workload's heads
+                                   (8, 2, 64, wg.BF16), (16, 2, 128, wg.BF16), (3, 3, 128, wg.F32),
+                                   (4, 2, 128, wg.BF16)],
+                         ids=["f32-d64-G4", "bf16-d64-G4", "bf16-d128-G8", "f32-d128-G1", "bf16-d128-G2"])
+@pytest.mark.parametrize("chunk,W,P", [(100, 64, 16), (37, 16, 4), (64, 8, 1)])
+def test_chunked_prefill_on_shapes_outside_the_matrix_core_kernel(shape, chunk, W, P):
+    """The prefill form of wgkv_attend for fp32 pools, head_dim 64 and other group sizes (a plain kernel): every
+    row against the definition, several chunks so that global cache, ring and chunk keys all occur."""
+    lens = [5 * chunk + 7, 3 * chunk]
+    _, _, worst, _ = _flow(2, lens, chunk, W, P, hidden_dim=64, seed=2000 + chunk + shape[0], use_gate=False, shape=shape)
+    print(f"shape {shape} chunk {chunk} W {W} P {P}: max abs err {worst[0]:.2e}, mean {worst[1]:.2e}", flush=True)
 
 
 def test_prefill_admit_computes_the_gate_itself():
@@ -195,11 +212,11 @@ def test_chunk_of_one_equals_decode_order():
         assert torch.equal(ma[name], mb[name]), name
 
 
-def test_prefill_form_rejects_unsupported_shapes():
+def test_prefill_form_rejects_misaligned_chunk_tensors():
     pool = wg.Pool(wg.Config(1, 8, 2, 64, wg.F32, 16, 32, 1, 8, 64), 1, 64)
     dev = torch.device("cuda:0")
     q = torch.zeros((4, 8, 64), device=dev)
-    kv = torch.zeros((4, 2, 64), device=dev)
+    kv = torch.zeros((4 * 2 * 64 + 1,), device=dev)[1:].view(4, 2, 64)   # 4 bytes past a 16-byte boundary
     g = torch.zeros((4, 2), device=dev)
     out = torch.zeros((4, 8, 64), device=dev)
     with pytest.raises(wg.WgkvError) as e:
