@@ -101,65 +101,76 @@ __global__ __launch_bounds__(256) void quest_update_kernel(View pv, CallSeqs cs,
     if (threadIdx.x == 0) a.lm_len[um] = N;
 }
 
-// Sixteen lanes per page, four pages per wave at a time; a lane reads 16 bytes of the minimum row and
-// of the maximum row per turn.  The group's queries sit in LDS as floats.
-template <int DT>
+// Sixteen lanes per page, four pages per wave at a time and four such turns in flight; a lane reads 16 bytes
+// of the minimum row and of the maximum row of a page, once for the whole group of query heads, whose queries sit
+// in LDS as floats.  The launch is small (1/P of the keys), so its time is its chain of dependent loads: the page
+// ids are asked for together with the head's length (entries past the last page hold -1 and the table row is
+// maxgp wide, so the ids need no length to be read safely), which leaves two round trips, ids then landmarks;
+// the grid is sized so that nearly every lane group has a single turn of four pages.
+template <int DT, int G>
 __global__ __launch_bounds__(256) void quest_score_kernel(View pv, CallSeqs cs, QuestArgs a) {
     extern __shared__ float s_q[];  // [G][d]
     constexpr int EPC = DT == WGKV_F32 ? 4 : 8;  // elements per 16-byte chunk
+    constexpr int PF = 4;
     const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
     const int um = unit_meta(pv, cs.sid[b], a.layer, h);
-    const int N = pv.global_len[um];
-    const int n_pages = (N + pv.P - 1) >> pv.logP;
-    for (int i = threadIdx.x; i < pv.G * pv.d; i += 256)
-        s_q[i] = q_ld<DT>(a.q, ((size_t)b * pv.Hq + (size_t)h * pv.G) * pv.d + i);
-    __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane & 15, slot = lane >> 4, cpr = (int)(pv.row_bytes / 16);
+    const int32_t *pt = pv.global_pt + (size_t)um * pv.maxgp;
+    int pidx[PF], page[PF];
+#pragma unroll
+    for (int k = 0; k < PF; k++) {
+        pidx[k] = (k * gridDim.x + blockIdx.x) * 16 + wave * 4 + slot;
+        page[k] = pidx[k] < pv.maxgp ? pt[pidx[k]] : -1;
+    }
+    const int N = pv.global_len[um];
+    const int n_pages = (N + pv.P - 1) >> pv.logP;
+    for (int i = threadIdx.x; i < G * pv.d; i += 256)
+        s_q[i] = q_ld<DT>(a.q, ((size_t)b * pv.Hq + (size_t)h * G) * pv.d + i);
+    __syncthreads();
     const int n_iter = (n_pages + gridDim.x * 16 - 1) / (gridDim.x * 16);  // the same for every lane: no divergence
-    // four pages per lane group in flight: their page ids first, then both landmark rows of all four,
-    // each read once for the whole group of query heads (at most 8 of them)
-    constexpr int PF = 4, GMAX = 8;
     for (int it0 = 0; it0 < n_iter; it0 += PF) {
-        int pidx[PF], page[PF];
+        float acc[G][PF];
 #pragma unroll
-        for (int k = 0; k < PF; k++) {
-            pidx[k] = ((it0 + k) * gridDim.x + blockIdx.x) * 16 + wave * 4 + slot;
-            page[k] = pv.global_pt[(size_t)um * pv.maxgp + (pidx[k] < n_pages ? pidx[k] : 0)];
-        }
-        float acc[GMAX][PF];
-#pragma unroll
-        for (int g = 0; g < GMAX; g++)
+        for (int g = 0; g < G; g++)
 #pragma unroll
             for (int k = 0; k < PF; k++) acc[g][k] = 0.f;
+        int cur_idx[PF], cur_page[PF];
+#pragma unroll
+        for (int k = 0; k < PF; k++) { cur_idx[k] = pidx[k]; cur_page[k] = (pidx[k] < n_pages && page[k] >= 0) ? page[k] : 0; }
+        if (it0 + PF < n_iter) {  // the ids of the next turn, on their way while this one is read and summed
+#pragma unroll
+            for (int k = 0; k < PF; k++) {
+                pidx[k] = ((it0 + PF + k) * gridDim.x + blockIdx.x) * 16 + wave * 4 + slot;
+                page[k] = pidx[k] < pv.maxgp ? pt[pidx[k]] : -1;
+            }
+        }
         for (int c = sub; c < cpr; c += 16) {  // one turn for 256-byte rows
             uint4 lo4[PF], hi4[PF];
 #pragma unroll
             for (int k = 0; k < PF; k++) {
-                const char *lo_row = a.lm + (size_t)page[k] * 2 * pv.row_bytes;
+                const char *lo_row = a.lm + (size_t)cur_page[k] * 2 * pv.row_bytes;
                 lo4[k] = *reinterpret_cast<const uint4 *>(lo_row + c * 16);
                 hi4[k] = *reinterpret_cast<const uint4 *>(lo_row + pv.row_bytes + c * 16);
             }
 #pragma unroll
-            for (int g = 0; g < GMAX; g++) {
-                if (g < pv.G) {
-                    const float *qg = s_q + g * pv.d + c * EPC;
-                    float qv[EPC];
+            for (int g = 0; g < G; g++) {
+                const float *qg = s_q + g * pv.d + c * EPC;
+                float qv[EPC];
 #pragma unroll
-                    for (int i = 0; i < EPC; i++) qv[i] = qg[i];
+                for (int i = 0; i < EPC; i++) qv[i] = qg[i];
 #pragma unroll
-                    for (int k = 0; k < PF; k++) {
-                        const uint32_t lw[4] = {lo4[k].x, lo4[k].y, lo4[k].z, lo4[k].w};
-                        const uint32_t hw[4] = {hi4[k].x, hi4[k].y, hi4[k].z, hi4[k].w};
+                for (int k = 0; k < PF; k++) {
+                    const uint32_t lw[4] = {lo4[k].x, lo4[k].y, lo4[k].z, lo4[k].w};
+                    const uint32_t hw[4] = {hi4[k].x, hi4[k].y, hi4[k].z, hi4[k].w};
 #pragma unroll
-                        for (int i = 0; i < 4; i++) {
-                            if (DT == WGKV_F32) {
-                                acc[g][k] += fmaxf(qv[i] * __uint_as_float(lw[i]), qv[i] * __uint_as_float(hw[i]));
-                            } else {
-                                acc[g][k] += fmaxf(qv[2 * i] * __uint_as_float(lw[i] << 16), qv[2 * i] * __uint_as_float(hw[i] << 16));
-                                acc[g][k] += fmaxf(qv[2 * i + 1] * __uint_as_float(lw[i] & 0xffff0000u),
-                                                   qv[2 * i + 1] * __uint_as_float(hw[i] & 0xffff0000u));
-                            }
+                    for (int i = 0; i < 4; i++) {
+                        if (DT == WGKV_F32) {
+                            acc[g][k] += fmaxf(qv[i] * __uint_as_float(lw[i]), qv[i] * __uint_as_float(hw[i]));
+                        } else {
+                            acc[g][k] += fmaxf(qv[2 * i] * __uint_as_float(lw[i] << 16), qv[2 * i] * __uint_as_float(hw[i] << 16));
+                            acc[g][k] += fmaxf(qv[2 * i + 1] * __uint_as_float(lw[i] & 0xffff0000u),
+                                               qv[2 * i + 1] * __uint_as_float(hw[i] & 0xffff0000u));
                         }
                     }
                 }
@@ -169,9 +180,8 @@ __global__ __launch_bounds__(256) void quest_score_kernel(View pv, CallSeqs cs, 
         for (int k = 0; k < PF; k++) {
             float best = -INFINITY;
 #pragma unroll
-            for (int g = 0; g < GMAX; g++)
-                if (g < pv.G) best = fmaxf(best, group_sum<16>(acc[g][k]));
-            if (it0 + k < n_iter && pidx[k] < n_pages && sub == 0) a.scores[(size_t)u * a.score_stride + pidx[k]] = best;
+            for (int g = 0; g < G; g++) best = fmaxf(best, group_sum<16>(acc[g][k]));
+            if (it0 + k < n_iter && cur_idx[k] < n_pages && sub == 0) a.scores[(size_t)u * a.score_stride + cur_idx[k]] = best;
         }
     }
 }
@@ -286,16 +296,24 @@ hipError_t launch_quest_select(const View &pv, const CallSeqs &cs, int layer, co
     a.budget_pages = budget_pages;
     a.sel_pages = sel_pages;
     a.sel_count = sel_count;
-    // 16 pages per block and turn, four turns in flight; no more blocks than are resident at once
-    // (three per compute unit at this register count), so that there is a single round of them
+    // 16 pages per block and turn, four turns in flight: enough blocks for one pass of four turns where the
+    // launch stays within a few rounds of resident blocks, more turns per block beyond that
     int bx = (int)((max_pages + 63) / 64);
-    const int cap = n_units > 0 ? (768 / n_units > 1 ? 768 / n_units : 1) : 1;
+    const int cap = n_units > 0 ? (4096 / n_units > 1 ? 4096 / n_units : 1) : 1;
     bx = bx < 1 ? 1 : (bx > cap ? cap : bx);
-    bx = bx > 64 ? 64 : bx;
     const dim3 grid(bx, n_units);
     const size_t smem = (size_t)pv.G * pv.d * sizeof(float);
-    if (pv.dtype == WGKV_F32) hipLaunchKernelGGL(quest_score_kernel<WGKV_F32>, grid, dim3(256), smem, st, pv, cs, a);
-    else hipLaunchKernelGGL(quest_score_kernel<WGKV_BF16>, grid, dim3(256), smem, st, pv, cs, a);
+#define WGKV_QS(DT_, G_) hipLaunchKernelGGL((quest_score_kernel<DT_, G_>), grid, dim3(256), smem, st, pv, cs, a)
+    if (pv.dtype == WGKV_F32) {
+        if (pv.G == 1) WGKV_QS(WGKV_F32, 1); else if (pv.G == 2) WGKV_QS(WGKV_F32, 2);
+        else if (pv.G == 4) WGKV_QS(WGKV_F32, 4); else if (pv.G == 8) WGKV_QS(WGKV_F32, 8);
+        else return hipErrorNotSupported;
+    } else {
+        if (pv.G == 1) WGKV_QS(WGKV_BF16, 1); else if (pv.G == 2) WGKV_QS(WGKV_BF16, 2);
+        else if (pv.G == 4) WGKV_QS(WGKV_BF16, 4); else if (pv.G == 8) WGKV_QS(WGKV_BF16, 8);
+        else return hipErrorNotSupported;
+    }
+#undef WGKV_QS
     hipLaunchKernelGGL(quest_select_kernel, dim3(n_units), dim3(1024), 0, st, pv, cs, a);
     return hipGetLastError();
 }
