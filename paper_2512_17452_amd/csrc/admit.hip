@@ -53,8 +53,7 @@ __global__ void init_kernel(View pv) {
     for (size_t i = i0; i < n_u * pv.W; i += stride) pv.ring_g[i] = 0.0f;
     for (size_t i = i0; i < (size_t)kMaxCallUnits; i += stride) pv.unit_counters[i] = 0;
     for (size_t i = i0; i < n_u; i += stride) pv.ahead[i] = -1;
-    // the pool starts as zeros: attention may read rows of a page beyond the last token
-    // written (they get weight zero) and those must be finite
+    // the pool starts as zeros (no kernel relies on it: rows past a head's last token are never read)
     uint4 *pool16 = reinterpret_cast<uint4 *>(pv.pool);
     const size_t n16 = (size_t)pv.n_pages * pv.page_bytes / 16;
     for (size_t i = i0; i < n16; i += stride) pool16[i] = make_uint4(0u, 0u, 0u, 0u);
