@@ -39,8 +39,9 @@ def test_query_sizes_and_layout(lib):
     assert lib.wgkv_get_meta_layout(C.byref(cc), C.byref(lay)) == 0
     assert lay.n_local_pages == 16 and lay.total_bytes == mb.value
     offs = [lay.seq_len, lay.global_len, lay.local_pt, lay.global_pt, lay.ring_g, lay.free_stack,
-            lay.free_top, lay.err_flag]
+            lay.free_top, lay.err_flag, lay.unit_counters, lay.ahead]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    assert lay.total_bytes - lay.ahead >= 8 * 32 * 8 * 4      # one stamp per (sequence, layer, kv head)
     assert lay.global_len - lay.seq_len >= 8 * 32 * 4
     assert lay.ring_g - lay.global_pt >= 8 * 32 * 8 * 8208 * 4
     assert wb.value > 0
@@ -62,4 +63,11 @@ def test_null_handles_are_rejected(lib):
     assert lib.wgkv_status(None, None, None, None) == -1
     assert lib.wgkv_set_profile_events(None, None, None) == -1
     assert lib.wgkv_gate_scores(1, 4, 12, 8, None, None, None, None) == -1
+    assert lib.wgkv_clear_error(None, None) == -1
+    assert lib.wgkv_decode_promote(None, 1, (C.c_int32 * 1)(0), 0.5, None) == -1
+    assert lib.wgkv_decode_step(None, 0, 1, (C.c_int32 * 1)(0), None, None, None, 0.5, None, None) == -1
+    assert lib.wgkv_prefill_admit_bounded(None, 0, 1, (C.c_int32 * 1)(0), (C.c_int32 * 1)(1), None, None, None, None,
+                                          None, 0, 0.5, 4, None, None, 0, None) == -1
+    assert lib.wgkv_attend_decode_static(None, 0, 1, (C.c_int32 * 1)(0), None, 1.0, None, None) == -1
+    assert lib.wgkv_stream_read_probe(None, 1024, None, None, None, None) == -1
     lib.wgkv_destroy(None)
