@@ -183,6 +183,8 @@ def _run_multilayer(cfg, n_samples, decode_steps, check_steps):
     worst = [0.0, 0.0]
     for step in range(decode_steps):
         q_host = {}
+        if step % 2 == 1:   # every other token with the promotions of all layers done ahead of the layers' steps
+            pool.decode_promote(seqs, tau=cfg.tau)
         for l in range(L):
             k1 = wl.draw_normal(cfg, "dec_k", (B, Hk, d), device=dev, key=(l, step))
             v1 = wl.draw_normal(cfg, "dec_v", (B, Hk, d), device=dev, key=(l, step))
