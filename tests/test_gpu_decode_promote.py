@@ -47,6 +47,35 @@ def test_promote_ahead_gives_the_state_of_plain_steps(P, W):
         pr.check_attend(l, seqs, rand_q(rng, B, Hq, d, pr.tdt))
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_promote_ahead_on_seeded_random_shapes(seed):
+    """Shapes, window, page size, sequence lengths and the tokens with a promotion ahead all drawn from the seed."""
+    rng = np.random.default_rng(700 + seed)
+    L = int(rng.integers(1, 4))
+    Hk = int(rng.integers(1, 4))
+    G = int(rng.choice([1, 2, 4, 8]))
+    d = int(rng.choice([64, 128]))
+    dtype = wg.BF16 if rng.random() < 0.7 else wg.F32
+    P = int(rng.choice([1, 2, 4, 8, 16, 32]))
+    W = int(rng.integers(1, 41))
+    B = int(rng.integers(1, 5))
+    pr = Pair(L, Hk * G, Hk, d, dtype, P, W, B, 96, 6000, max_call_seqs=B, max_call_tokens=256)
+    seqs = [int(x) for x in rng.permutation(B)]
+    lens = [int(rng.integers(1, 2 * W + 20)) for _ in seqs]
+    _prefill_all_layers(pr, rng, L, seqs, lens, Hk, d, rate=float(rng.uniform(0.2, 0.9)))
+    n_steps = 2 * W + 9
+    for step in range(n_steps):
+        if rng.random() < 0.6:
+            pr.pool.decode_promote(seqs, tau=0.5)
+        for l in range(L):
+            k, v, g = rand_tokens(rng, B, Hk, d, pr.tdt, rates=[0.6] * Hk)
+            pr.decode(l, seqs, k, v, g, 0.5)
+        if step % 7 == 3 or step == n_steps - 1:
+            pr.check_state()
+            l = int(rng.integers(L))
+            pr.check_attend(l, seqs, rand_q(rng, B, Hk * G, d, pr.tdt))
+
+
 def test_promote_ahead_for_part_of_the_call():
     """A step whose call holds promoted and unpromoted sequences takes the general kernel, which honours the
     stamps.  One layer and the promoted sequence first in the call: the pages are then taken in the order of
