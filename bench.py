@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--no-promote-ahead", action="store_true",
                     help="decode workloads: no wgkv_decode_promote at the start of a step (each layer's "
                          "wgkv_decode_step then decides and moves its promotions itself)")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="decode workloads: no wgkv_tune_decode_attention before the timed steps (the split of the "
+                         "tiles between the XCDs of a pair then keeps its default of 40 per mille)")
     ap.add_argument("--graph", action="store_true",
                     help="decode workloads: capture one whole step (all layers) in a HIP graph and time replays "
                          "instead of direct calls (per-kernel events are then not available)")
@@ -237,6 +240,12 @@ def main():
     for st in range(args.warmup):
         one_step(st)
     torch.cuda.synchronize()
+    # the split of a launch's tiles over the XCDs, tuned to this machine on the workload's own cache (untimed
+    # set-up, a few milliseconds; the cache is not changed)
+    xcd_skew = None
+    if not args.no_tune and not sel_b:
+        xcd_skew = pool.tune_decode_attention(seqs, q_new[0], out[0], scale)
+        log(f"[bench] split correction between the XCDs of a pair kept by the tuning: {xcd_skew} per mille")
     graph = None
     if args.graph:
         assert not sel_b, "--graph times the plain decode step"
@@ -357,7 +366,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "layers": L, "q_heads": Hq, "kv_heads": Hk, "head_dim": d,
                    "w_local": W, "page_size": P, "tau": cfg.tau, "ctx_min": int(ctx.min()), "ctx_max": int(ctx.max()),
-                   "select_pages": sel_b, "hip_graph": bool(args.graph), "promote_ahead": promote_ahead,
+                   "select_pages": sel_b, "hip_graph": bool(args.graph), "promote_ahead": promote_ahead, "xcd_skew_permille": xcd_skew,
                    "mean_cached_tokens_per_head": float((np.minimum(sl1, W)[:, :, None] + gl1).mean()),
                    # the paper's x axis: cached entries of a head over the tokens it has seen, (W + G_h) / t
                    "normalized_kv_size": float(((np.minimum(sl1, W)[:, :, None] + gl1) / np.maximum(sl1, 1)[:, :, None]).mean()),

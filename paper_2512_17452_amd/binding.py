@@ -11,7 +11,7 @@ F32, BF16 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "wgkv_version", "wgkv_get_meta_layout", "wgkv_query_sizes", "wgkv_init_pool",
-    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_prefill_admit_bounded", "wgkv_decode_step", "wgkv_decode_promote", "wgkv_attend", "wgkv_attend_decode_static", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
+    "wgkv_gate_scores", "wgkv_gate_mlp_scores", "wgkv_prefill_admit", "wgkv_prefill_admit_bounded", "wgkv_decode_step", "wgkv_decode_promote", "wgkv_attend", "wgkv_attend_decode_static", "wgkv_tune_decode_attention", "wgkv_evict_scores", "wgkv_evict_apply", "wgkv_quest_landmark_bytes", "wgkv_quest_update",
     "wgkv_quest_select", "wgkv_attend_selected", "wgkv_soft_attn_forward", "wgkv_soft_attn_workspace_bytes",
     "wgkv_soft_attn_backward", "wgkv_sparsity_loss", "wgkv_free_seq",
     "wgkv_status", "wgkv_clear_error", "wgkv_stream_read_probe", "wgkv_set_profile_events", "wgkv_destroy",
@@ -95,6 +95,7 @@ def load_library():
     L.wgkv_sparsity_loss.argtypes = [vp, i64, i64, vp, vp, vp, sz, vp]
     L.wgkv_prefill_admit.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
     L.wgkv_decode_promote.argtypes = [vp, i32, pi32, f32, vp]
+    L.wgkv_tune_decode_attention.argtypes = [vp, i32, pi32, vp, f32, vp, vp, sz, vp, C.POINTER(C.c_int32)]
     L.wgkv_prefill_admit_bounded.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, vp, i32, f32, i32, vp, vp, sz, vp]
     L.wgkv_decode_step.argtypes = [vp, i32, i32, pi32, vp, vp, vp, f32, vp, vp]
     L.wgkv_attend.argtypes = [vp, i32, i32, pi32, pi32, vp, vp, vp, vp, f32, f32, vp, vp, sz, vp]
@@ -303,6 +304,14 @@ class Pool:
                                   _ptr(k_chunk), _ptr(v_chunk), _ptr(g_chunk), tau, scale, _ptr(out),
                                   _ptr(self.workspace), self.workspace.numel(), _stream()), "wgkv_attend")
         return out
+
+    def tune_decode_attention(self, seq_ids, q, out, scale):
+        """wgkv_tune_decode_attention: picks the odd/even XCD correction of the tile split on this machine; returns it."""
+        kept = C.c_int32(-1)
+        _check(self.L.wgkv_tune_decode_attention(self.h, len(seq_ids), _ids(seq_ids), _ptr(q), scale, _ptr(out),
+                                                 _ptr(self.workspace), self.workspace.numel(), _stream(),
+                                                 C.byref(kept)), "wgkv_tune_decode_attention")
+        return kept.value
 
     def attend_decode_static(self, layer, seq_ids, q, out, scale):
         """wgkv_attend_decode_static: decode attention without a workspace argument."""

@@ -36,13 +36,15 @@ constexpr int kStagesFast = 4;   // tiles in flight per wave on the fast path
 // The split charges it to the unit, as tiles in front of the first real one that nobody reads.
 constexpr int kUnitStartTiles = 12;
 // Blocks go to the XCDs round-robin, and in every launch measured the odd XCD of a pair streams
-// 4-5 % slower than the even one: the waves of an odd block get this many thousandths fewer
-// tiles, those of the even block before it as many more (flat optimum between 40 and 60).
-constexpr int kOddXcdSkewPermille = 40;
+// slower than the even one, by 4-5 % on some machines and by about twice that on others: the
+// waves of an odd block get a number of thousandths fewer tiles, those of the even block before
+// it as many more (AttendArgs::skew_permille; 40 unless the pool was tuned on its machine, see
+// wgkv_tune_decode_attention).
 struct AttendArgs {
     int layer;
     int n_seqs;
     int min_tpw;              // at least this many tiles per wave
+    int skew_permille;        // share of the odd blocks' tiles that goes to the even blocks instead
     float scale_log2e;        // scale * log2(e)
     const char *q;            // [n_seqs][Hq][d]
     float *out;               // [n_seqs][Hq][d]
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(kAttnThreads) void attend_decode_kernel(View pv, At
     const int wid = (int)blockIdx.x * kAttnWaves + wave;
     // shares: a pair of blocks (even, odd) covers 2 * kAttnWaves * tpw tiles, te per wave of the
     // even block and to per wave of the odd one
-    const int skew = (gridDim.x % 2 == 0) ? tpw * kOddXcdSkewPermille / 1000 : 0;
+    const int skew = (gridDim.x % 2 == 0) ? tpw * a.skew_permille / 1000 : 0;
     const int te = tpw + skew, to = tpw - skew;
     constexpr int PW = 2 * kAttnWaves;
     auto wave_of = [&](int x) {  // the wave whose share holds tile x
@@ -834,8 +836,9 @@ hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int
                                 const void *q, float scale, float *out, void *ws, int32_t *counters,
                                 int n_cu, int grid_max, int min_tpw, hipStream_t st, hipEvent_t ev0,
                                 hipEvent_t ev1, const int32_t *sel_pages, const int32_t *sel_count,
-                                int sel_stride) {
+                                int sel_stride, int skew_permille) {
     AttendArgs a;
+    a.skew_permille = skew_permille;
     a.sel_pages = sel_pages;
     a.sel_count = sel_count;
     a.sel_stride = sel_stride;

@@ -2,6 +2,7 @@
 // Every entry point is documented in include/wgkv.h.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -45,7 +46,7 @@ hipError_t launch_attend_decode(const View &pv, int layer, int n_seqs, const int
                                 const void *q, float scale, float *out, void *ws, int32_t *counters,
                                 int n_cu, int grid_max, int min_tpw, hipStream_t st, hipEvent_t ev0,
                                 hipEvent_t ev1, const int32_t *sel_pages, const int32_t *sel_count,
-                                int sel_stride);
+                                int sel_stride, int skew_permille);
 hipError_t launch_gate_mlp(int dtype, int64_t n_tokens, int n_kv_heads, int head_dim, int width,
                            const void *k, const void *k_rope, const void *w1, const float *b1,
                            const void *w2, const float *b2, float eps, float *g_out, hipStream_t st);
@@ -80,6 +81,7 @@ namespace {
 constexpr int kPrefillBlkHost = 512;    // must match kPrefillBlk in admit.hip
 constexpr int kAttnGridMax = 2048;      // upper bound on the decode-attention grid (blocks of 4 waves)
 constexpr int kAttnMinTilesPerWave = 16;  // below that a share is shorter than the fold of its partial
+constexpr int kAttnDefaultSkewPermille = 40;  // see wgkv_tune_decode_attention
 constexpr int kAttnStaticGridMax = 512;   // grid bound of the entry point that keeps its partials in the static array
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -176,6 +178,7 @@ struct wgkv_pool {
     std::vector<int32_t> ahead_h;    // [S][L] token count whose promotion wgkv_decode_promote has enqueued, else -1
     int64_t pages_ub;                // upper bound of pages in use
     int n_cu;                        // compute units of the device
+    int skew_permille;               // decode attention: thousandths of an odd block's tiles given to the even one
     hipEvent_t ev0, ev1;
 };
 
@@ -251,6 +254,7 @@ int wgkv_init_pool(const wgkv_config *cfg, void *pool_dev, size_t pool_bytes, vo
     p->pages_ub = 0;
     p->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
     p->ev0 = p->ev1 = nullptr;
+    p->skew_permille = kAttnDefaultSkewPermille;
     // set-up for wgkv_attend_decode_static: this device's address of the static scratch array and
     // the launch shape of the pool's attention kernel, so that the call itself asks the runtime nothing
     if (static_scratch_init() != hipSuccess) {
@@ -619,7 +623,7 @@ int wgkv_attend(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t *seq_
         return launch_attend_decode(p->view, layer, n_seqs, seq_ids_host, q_dev, scale, out_dev,
                                     workspace_dev, p->view.unit_counters, p->n_cu, kAttnGridMax,
                                     kAttnMinTilesPerWave, st, p->ev0, p->ev1, nullptr, nullptr,
-                                    0) == hipSuccess
+                                    0, p->skew_permille) == hipSuccess
                    ? WGKV_OK
                    : WGKV_ERR_HIP;
     }
@@ -663,7 +667,8 @@ int wgkv_attend_decode_static(wgkv_pool *p, int32_t layer, int32_t n_seqs, const
     if (!ws) return WGKV_ERR_HIP;  // no pool was ever initialised on the current device
     return launch_attend_decode(p->view, layer, n_seqs, seq_ids_host, q_dev, scale, out_dev, ws,
                                 p->view.unit_counters, p->n_cu, kAttnStaticGridMax, kAttnMinTilesPerWave,
-                                (hipStream_t)stream, p->ev0, p->ev1, nullptr, nullptr, 0) == hipSuccess
+                                (hipStream_t)stream, p->ev0, p->ev1, nullptr, nullptr, 0,
+                                p->skew_permille) == hipSuccess
                ? WGKV_OK
                : WGKV_ERR_HIP;
 }
@@ -739,7 +744,7 @@ int wgkv_attend_selected(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int3
     return launch_attend_decode(p->view, layer, n_seqs, seq_ids_host, q_dev, scale, out_dev, workspace_dev,
                                 p->view.unit_counters, p->n_cu, kAttnGridMax, kAttnMinTilesPerWave,
                                 (hipStream_t)stream, p->ev0, p->ev1, sel_pages_dev, sel_count_dev,
-                                sel_stride) == hipSuccess
+                                sel_stride, p->skew_permille) == hipSuccess
                ? WGKV_OK
                : WGKV_ERR_HIP;
 }
@@ -813,6 +818,60 @@ int wgkv_evict_apply(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t 
             p->g_ub[sl * H + h] = g1;
         }
     }
+    return WGKV_OK;
+}
+
+int wgkv_tune_decode_attention(wgkv_pool *p, int32_t n_seqs, const int32_t *seq_ids_host, const void *q_dev,
+                               float scale, float *out_dev, void *workspace_dev, size_t workspace_bytes,
+                               wgkv_stream stream, int32_t *skew_permille_out) {
+    int rc = check_seqs(p, 0, n_seqs, seq_ids_host);
+    if (rc) return rc;
+    if (!q_dev || !out_dev || !workspace_dev || !std::isfinite(scale)) return WGKV_ERR_INVALID_ARG;
+    if ((((uintptr_t)q_dev | (uintptr_t)out_dev | (uintptr_t)workspace_dev) & 15) != 0) return WGKV_ERR_INVALID_ARG;
+    if (workspace_bytes < attend_decode_ws_bytes(p->view, n_seqs, kAttnGridMax)) return WGKV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    static const int kCand[] = {0, 20, 40, 60, 80, 100, 120};
+    constexpr int kNc = (int)(sizeof(kCand) / sizeof(kCand[0])), kReps = 5;
+    const int L = p->cfg.n_layers;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return WGKV_ERR_HIP;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return WGKV_ERR_HIP; }
+    float ms_of[kNc][kReps];
+    bool ok = true;
+    // One measurement of a candidate is a pass over all layers, as a decode step makes it (a layer that is
+    // read again right away would come out of the memory-side cache in part); the candidates in turn, several
+    // rounds, round 0 to warm up.  Launches of one kernel on one state: only the split differs.
+    for (int r = 0; r < kReps + 1 && ok; r++)
+        for (int c = 0; c < kNc && ok; c++) {
+            float sum = 0.f;
+            for (int l = 0; l < L && ok; l++) {
+                ok = launch_attend_decode(p->view, l, n_seqs, seq_ids_host, q_dev, scale, out_dev, workspace_dev,
+                                          p->view.unit_counters, p->n_cu, kAttnGridMax, kAttnMinTilesPerWave, st, e0,
+                                          e1, nullptr, nullptr, 0, kCand[c]) == hipSuccess &&
+                     hipEventSynchronize(e1) == hipSuccess;
+                float ms = 0.f;
+                ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+                sum += ms;
+            }
+            if (ok && r > 0) ms_of[c][r - 1] = sum;
+        }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (!ok) return WGKV_ERR_HIP;
+    float med[kNc];
+    for (int c = 0; c < kNc; c++) {
+        std::sort(ms_of[c], ms_of[c] + kReps);
+        med[c] = ms_of[c][kReps / 2];
+    }
+    int best = 0;
+    for (int c = 1; c < kNc; c++)
+        if (med[c] < med[best]) best = c;
+    // the default stays unless something else is clearly (one per cent) better: a tuned value changes the
+    // rounding of the outputs, and noise should not
+    const int def = 2;
+    if (med[best] > 0.99f * med[def]) best = def;
+    p->skew_permille = kCand[best];
+    if (skew_permille_out) *skew_permille_out = kCand[best];
     return WGKV_OK;
 }
 

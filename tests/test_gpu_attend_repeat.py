@@ -2,7 +2,8 @@
 cross workgroups (and XCDs) inside the launch, the split of the work is a fixed function of the
 lengths and the fold runs in a fixed order.  Checked at one layer of the two large decode
 workloads (64 and 256 (sequence, kv head) units per launch, every share straddling units), together
-with parity of sampled sequences against the definition oracle."""
+with parity of sampled sequences against the definition oracle, before and after the split has been tuned to
+the machine (wgkv_tune_decode_attention)."""
 import math
 
 import numpy as np
@@ -63,11 +64,36 @@ def test_decode_attention_repeats_bit_for_bit(index, layer):
         assert torch.equal(outs[0], outs[r]), f"launch {r} differs from launch 0"
     o = outs[0].cpu().numpy()
     assert np.isfinite(o).all()
+    refs = {}
     for s in sampled:
         K = np.concatenate([hist[s][0], k1[s:s + 1].float().cpu().numpy()])
         V = np.concatenate([hist[s][1], v1[s:s + 1].float().cpu().numpy()])
         G = np.concatenate([hist[s][2], g1[s:s + 1].cpu().numpy()])
         t = K.shape[0]
-        ref = attend_definition(K, V, G, q1[s].float().cpu().numpy()[None], np.array([t - 1]), W, cfg.tau, scale)[0]
-        err = np.abs(o[s].astype(np.float64) - ref)
+        refs[s] = attend_definition(K, V, G, q1[s].float().cpu().numpy()[None], np.array([t - 1]), W, cfg.tau, scale)[0]
+        err = np.abs(o[s].astype(np.float64) - refs[s])
         assert err.max() <= MAX_ABS_TOL and err.mean() <= MEAN_ABS_TOL, (s, err.max(), err.mean())
+    # tuning the split to the machine: one of the candidates is kept, the cache is untouched, and with the
+    # kept value the launches repeat bit for bit again and stay within tolerance
+    meta_before = pool.meta_buf.cpu().numpy().copy()
+    scratch = torch.empty((B, Hq, d), dtype=torch.float32, device=dev)
+    kept = pool.tune_decode_attention(seqs, q1, scratch, scale)
+    assert kept in (0, 20, 40, 60, 80, 100, 120)
+    print(f"workload {index}: split correction kept by the tuning: {kept} per mille", flush=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(pool.meta_buf.cpu().numpy(), meta_before)
+    outs = []
+    for r in range(6):
+        out = torch.full((B, Hq, d), float("nan"), dtype=torch.float32, device=dev)
+        pool.attend(0, seqs, q1, out, scale)
+        outs.append(out)
+    torch.cuda.synchronize()
+    for r in range(1, 6):
+        assert torch.equal(outs[0], outs[r]), f"after tuning: launch {r} differs from launch 0"
+    o = outs[0].cpu().numpy()
+    for s in sampled:
+        err = np.abs(o[s].astype(np.float64) - refs[s])
+        assert err.max() <= MAX_ABS_TOL and err.mean() <= MEAN_ABS_TOL, (s, err.max(), err.mean())
+    with pytest.raises(wg.WgkvError) as e:
+        pool.tune_decode_attention(seqs + [B], q1, scratch, scale)   # no such sequence slot
+    assert e.value.code == -1
