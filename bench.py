@@ -114,7 +114,7 @@ def main():
                          "wgkv_decode_step then decides and moves its promotions itself)")
     ap.add_argument("--no-tune", action="store_true",
                     help="decode workloads: no wgkv_tune_decode_attention before the timed steps (the split of the "
-                         "tiles between the XCDs of a pair then keeps its default of 40 per mille)")
+                         "tiles between the XCDs of a pair then keeps its default of 50 per mille)")
     ap.add_argument("--graph", action="store_true",
                     help="decode workloads: capture one whole step (all layers) in a HIP graph and time replays "
                          "instead of direct calls (per-kernel events are then not available)")

@@ -318,11 +318,11 @@ int wgkv_attend(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *s
  * turn, and the odd XCD of each pair streams a few per cent slower than the even one, by an amount
  * that differs between machines.  This call runs the decode attention of every layer for the
  * given sequences (arguments as for wgkv_attend, the same queries for every layer; the cache is
- * not changed, out_dev is overwritten) with the correction set to 0, 2, 4, ... 12 per cent, five
- * timed passes over the layers each, and keeps the one with the lowest median for all later calls
- * on this pool (the default of 4 per cent unless another value is at least one per cent faster).
- * Call it once, on a cache of the size the pool will serve; it synchronises with the stream after
- * every launch (35 passes: tens of milliseconds).  The outputs of later calls differ between
+ * not changed, out_dev is overwritten) with the correction set to 0, 2.5, 5, ... 12.5 per cent,
+ * five timed passes over the layers each, and keeps the one with the lowest median for all later
+ * calls on this pool (the default of 5 per cent unless another value is at least one per cent
+ * faster).  Call it once, on a cache of the size the pool will serve; it synchronises with the
+ * stream after every launch (30 passes: tens of milliseconds).  The outputs of later calls differ between
  * settings by the order of the floating-point sums only; for one setting they repeat bit for bit.
  *   skew_permille_out : optional, the value kept, in thousandths
  * Errors: INVALID_ARG, WORKSPACE, HIP. */

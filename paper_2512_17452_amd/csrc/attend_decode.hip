@@ -38,7 +38,7 @@ constexpr int kUnitStartTiles = 12;
 // Blocks go to the XCDs round-robin, and in every launch measured the odd XCD of a pair streams
 // slower than the even one, by 4-5 % on some machines and by about twice that on others: the
 // waves of an odd block get a number of thousandths fewer tiles, those of the even block before
-// it as many more (AttendArgs::skew_permille; 40 unless the pool was tuned on its machine, see
+// it as many more (AttendArgs::skew_permille; 50 unless the pool was tuned on its machine, see
 // wgkv_tune_decode_attention).
 struct AttendArgs {
     int layer;

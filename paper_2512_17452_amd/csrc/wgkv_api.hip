@@ -81,7 +81,7 @@ namespace {
 constexpr int kPrefillBlkHost = 512;    // must match kPrefillBlk in admit.hip
 constexpr int kAttnGridMax = 2048;      // upper bound on the decode-attention grid (blocks of 4 waves)
 constexpr int kAttnMinTilesPerWave = 16;  // below that a share is shorter than the fold of its partial
-constexpr int kAttnDefaultSkewPermille = 40;  // see wgkv_tune_decode_attention
+constexpr int kAttnDefaultSkewPermille = 50;  // see wgkv_tune_decode_attention
 constexpr int kAttnStaticGridMax = 512;   // grid bound of the entry point that keeps its partials in the static array
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -830,7 +830,7 @@ int wgkv_tune_decode_attention(wgkv_pool *p, int32_t n_seqs, const int32_t *seq_
     if ((((uintptr_t)q_dev | (uintptr_t)out_dev | (uintptr_t)workspace_dev) & 15) != 0) return WGKV_ERR_INVALID_ARG;
     if (workspace_bytes < attend_decode_ws_bytes(p->view, n_seqs, kAttnGridMax)) return WGKV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    static const int kCand[] = {0, 20, 40, 60, 80, 100, 120};
+    static constexpr int kCand[] = {0, 25, 50, 75, 100, 125};
     constexpr int kNc = (int)(sizeof(kCand) / sizeof(kCand[0])), kReps = 5;
     const int L = p->cfg.n_layers;
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -869,6 +869,7 @@ int wgkv_tune_decode_attention(wgkv_pool *p, int32_t n_seqs, const int32_t *seq_
     // the default stays unless something else is clearly (one per cent) better: a tuned value changes the
     // rounding of the outputs, and noise should not
     const int def = 2;
+    static_assert(kCand[2] == kAttnDefaultSkewPermille, "the default is one of the candidates");
     if (med[best] > 0.99f * med[def]) best = def;
     p->skew_permille = kCand[best];
     if (skew_permille_out) *skew_permille_out = kCand[best];
