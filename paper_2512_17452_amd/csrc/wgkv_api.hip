@@ -840,7 +840,7 @@ int wgkv_tune_decode_attention(wgkv_pool *p, int32_t n_seqs, const int32_t *seq_
     bool ok = true;
     // One measurement of a candidate is a pass over all layers, as a decode step makes it (a layer that is
     // read again right away would come out of the memory-side cache in part); the candidates in turn, several
-    // rounds, round 0 to warm up.  Launches of one kernel on one state: only the split differs.
+    // times over, the first time to warm up.  Launches of one kernel on one state: only the split differs.
     for (int r = 0; r < kReps + 1 && ok; r++)
         for (int c = 0; c < kNc && ok; c++) {
             float sum = 0.f;
