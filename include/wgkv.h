@@ -26,7 +26,8 @@
  *   - All path calls (prefill_admit, decode_step, attend, gate_scores, free_seq)
  *     only enqueue kernels on the given stream (a hipStream_t passed as void*)
  *     and return; calls on one pool must be issued in stream order.  Small host
- *     arrays are read before the call returns.  Only wgkv_status synchronises.
+ *     arrays are read before the call returns.  Only wgkv_status and
+ *     wgkv_tune_decode_attention synchronise.
  *   - Return value: 0 = WGKV_OK, negative = error.  Argument errors and page
  *     exhaustion are detected on the host before anything is enqueued and leave
  *     all state untouched.
