@@ -97,3 +97,22 @@ def test_decode_attention_repeats_bit_for_bit(index, layer):
     with pytest.raises(wg.WgkvError) as e:
         pool.tune_decode_attention(seqs + [B], q1, scratch, scale)   # no such sequence slot
     assert e.value.code == -1
+
+
+def test_tuning_runs_over_every_layer_and_leaves_the_cache_alone():
+    from harness import Pair, rand_q, rand_tokens
+    L, Hq, Hk, d, P, W, B = 3, 8, 2, 128, 16, 32, 2
+    rng = np.random.default_rng(77)
+    pr = Pair(L, Hq, Hk, d, wg.BF16, P, W, B, 64, 2000, max_call_seqs=B, max_call_tokens=1024)
+    seqs = [1, 0]
+    for l in range(L):
+        k, v, g = rand_tokens(rng, 900, Hk, d, pr.tdt, rates=[0.5] * Hk)
+        pr.prefill(l, seqs, [500, 400], k, v, g, 0.5)
+    pr.check_state()
+    q = rand_q(rng, B, Hq, d, pr.tdt)
+    scratch = torch.empty((B, Hq, d), dtype=torch.float32, device=pr.dev)
+    kept = pr.pool.tune_decode_attention(seqs, q.to(pr.dev), scratch, 1.0 / math.sqrt(d))
+    assert kept in (0, 25, 50, 75, 100, 125)
+    pr.check_state()
+    for l in range(L):
+        pr.check_attend(l, seqs, rand_q(rng, B, Hq, d, pr.tdt))
