@@ -63,6 +63,9 @@ class Config:
 
 
 def library_path() -> str:
+    override = os.environ.get("WGKV_LIB")   # e.g. the build with a sanitized host side (see build.py)
+    if override:
+        return os.path.abspath(override)
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libwgkv.so")
 
 

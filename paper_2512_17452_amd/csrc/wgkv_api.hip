@@ -137,17 +137,18 @@ View make_view(const wgkv_config *c, void *pool, void *meta) {
     v.v_off = (uint32_t)(v.P * v.d * v.es);
     v.page_bytes = (uint64_t)2 * v.P * v.d * v.es;
     v.pool = (char *)pool;
-    char *m = (char *)meta;
-    v.seq_len = (int32_t *)(m + lay.seq_len);
-    v.global_len = (int32_t *)(m + lay.global_len);
-    v.local_pt = (int32_t *)(m + lay.local_pt);
-    v.global_pt = (int32_t *)(m + lay.global_pt);
-    v.ring_g = (float *)(m + lay.ring_g);
-    v.free_stack = (int32_t *)(m + lay.free_stack);
-    v.free_top = (int32_t *)(m + lay.free_top);
-    v.err_flag = (int32_t *)(m + lay.err_flag);
-    v.unit_counters = (int32_t *)(m + lay.unit_counters);
-    v.ahead = (int32_t *)(m + lay.ahead);
+    // a null base (the size query builds a view for its dimensions only) leaves every metadata pointer null
+    const auto at = [meta](size_t off) -> void * { return meta ? (char *)meta + off : nullptr; };
+    v.seq_len = (int32_t *)at(lay.seq_len);
+    v.global_len = (int32_t *)at(lay.global_len);
+    v.local_pt = (int32_t *)at(lay.local_pt);
+    v.global_pt = (int32_t *)at(lay.global_pt);
+    v.ring_g = (float *)at(lay.ring_g);
+    v.free_stack = (int32_t *)at(lay.free_stack);
+    v.free_top = (int32_t *)at(lay.free_top);
+    v.err_flag = (int32_t *)at(lay.err_flag);
+    v.unit_counters = (int32_t *)at(lay.unit_counters);
+    v.ahead = (int32_t *)at(lay.ahead);
     return v;
 }
 
