@@ -362,8 +362,11 @@ int wgkv_attend_decode_static(wgkv_pool *pool, int32_t layer, int32_t n_seqs, co
  * index first) are read, one selection per kv head; the local window is always read.
  *
  * Landmarks live in a caller-owned device buffer of wgkv_quest_landmark_bytes bytes,
- * zero-filled by the caller before its first use: per physical page the minimum and the
- * maximum row in the pool dtype, then one int32 per (slot, layer, kv head). */
+ * zero-filled by the caller before its first use: per (slot, layer, kv head), in that
+ * order, max_global_pages_per_head pages in cache order, each the minimum and the maximum
+ * row in the pool dtype (2 * head_dim elements); then one int32 per (slot, layer, kv head).
+ * The buffer grows with max_global_pages_per_head, not with the pool: 1 / page_size of
+ * the keys of a cache in which every head is full.  It must be 16-byte aligned. */
 int wgkv_quest_landmark_bytes(const wgkv_config *cfg, size_t *landmark_bytes);
 
 /* Brings the landmarks of the given sequences' heads (layer `layer`) up to date with
@@ -375,7 +378,7 @@ int wgkv_quest_update(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int3
                       void *landmarks_dev, size_t landmark_bytes, int32_t reset, wgkv_stream stream);
 
 /* Scores every page of every head for the decode queries and picks the pages to read.
- *   q_dev [n_seqs][n_q_heads][head_dim] of cfg.dtype
+ *   q_dev [n_seqs][n_q_heads][head_dim] of cfg.dtype, 16-byte aligned
  *   page_scores_out_dev float [n_seqs * n_kv_heads][score_stride]: U of pages [0, n_pages);
  *                       score_stride must cover the host's bound of every head's page count
  *   sel_pages_out_dev int32 [n_seqs * n_kv_heads][budget_pages]: ascending indices into the

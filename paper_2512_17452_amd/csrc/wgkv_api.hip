@@ -37,7 +37,7 @@ hipError_t launch_quest_update(const View &pv, const CallSeqs &cs, int layer, vo
                                hipStream_t st);
 hipError_t launch_quest_select(const View &pv, const CallSeqs &cs, int layer, const void *q, void *landmarks,
                                int budget_pages, float *scores, int64_t score_stride, int32_t *sel_pages,
-                               int32_t *sel_count, int64_t max_pages, hipStream_t st);
+                               int32_t *sel_count, const int32_t *len_ub, hipStream_t st);
 size_t attend_decode_ws_bytes(const View &pv, int n_seqs, int grid);
 hipError_t static_scratch_init();
 void *static_scratch();
@@ -706,7 +706,8 @@ int wgkv_quest_update(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t
     int64_t max_len;
     int rc = quest_seqs(p, layer, n_seqs, seq_ids_host, &cs, &max_len);
     if (rc) return rc;
-    if (!landmarks_dev || landmark_bytes < quest_landmark_bytes(p->view)) return WGKV_ERR_INVALID_ARG;
+    if (!landmarks_dev || landmark_bytes < quest_landmark_bytes(p->view) || ((uintptr_t)landmarks_dev & 15) != 0)
+        return WGKV_ERR_INVALID_ARG;
     return launch_quest_update(p->view, cs, layer, landmarks_dev, reset != 0, (hipStream_t)stream) == hipSuccess
                ? WGKV_OK
                : WGKV_ERR_HIP;
@@ -723,10 +724,16 @@ int wgkv_quest_select(wgkv_pool *p, int32_t layer, int32_t n_seqs, const int32_t
     const int P = p->cfg.page_size;
     const int64_t max_pages = (max_len + P - 1) / P;
     if (!q_dev || !landmarks_dev || landmark_bytes < quest_landmark_bytes(p->view) || budget_pages < 1 ||
-        !page_scores_out_dev || score_stride < max_pages || !sel_pages_out_dev || !sel_count_out_dev)
+        !page_scores_out_dev || score_stride < max_pages || !sel_pages_out_dev || !sel_count_out_dev ||
+        (((uintptr_t)q_dev | (uintptr_t)landmarks_dev) & 15) != 0)  // both are read 16 bytes per lane
         return WGKV_ERR_INVALID_ARG;
+    int32_t len_ub[WGKV_MAX_CALL_UNITS];  // the host's bounds of the heads' lengths, in the call's unit order
+    const int H = p->cfg.n_kv_heads;
+    for (int b = 0; b < n_seqs; b++)
+        for (int h = 0; h < H; h++)
+            len_ub[b * H + h] = p->g_ub[((size_t)seq_ids_host[b] * p->cfg.n_layers + layer) * H + h];
     return launch_quest_select(p->view, cs, layer, q_dev, landmarks_dev, budget_pages, page_scores_out_dev,
-                               score_stride, sel_pages_out_dev, sel_count_out_dev, max_pages,
+                               score_stride, sel_pages_out_dev, sel_count_out_dev, len_ub,
                                (hipStream_t)stream) == hipSuccess
                ? WGKV_OK
                : WGKV_ERR_HIP;

@@ -16,15 +16,18 @@ U_RTOL = 2e-5      # fp32 sum of head_dim products against fp64, relative to the
 
 
 def _landmarks_of(pair, lm, layer, s, h):
-    """(lo, hi) rows per page of one head, read back from the landmark buffer through its page table."""
+    """(lo, hi) rows per page of one head, read back from the landmark buffer: heads in (slot, layer, head) order,
+    each with max_global_pages_per_head pages of two rows, in cache order."""
     c = pair.cfg
     es = 4 if c.dtype == wg.F32 else 2
     n = pair.orc.global_len(s, layer, h)
     n_pg = -(-n // c.page_size)
-    gpt = pair.pool.meta()["global_pt"][s, layer, h].cpu().numpy()[:n_pg]
-    rows = lm[: c.n_pages * 2 * c.head_dim * es].view(torch.float32 if c.dtype == wg.F32 else torch.bfloat16)
-    rows = rows.view(c.n_pages, 2, c.head_dim).float().cpu().numpy()
-    return rows[gpt, 0], rows[gpt, 1]
+    um = (s * c.n_layers + layer) * c.n_kv_heads + h
+    per_head = c.max_global_pages_per_head * 2 * c.head_dim * es
+    rows = lm[um * per_head: um * per_head + n_pg * 2 * c.head_dim * es]
+    rows = rows.view(torch.float32 if c.dtype == wg.F32 else torch.bfloat16)
+    rows = rows.view(n_pg, 2, c.head_dim).float().cpu().numpy()
+    return rows[:, 0], rows[:, 1]
 
 
 def _check_scores(pair, lm, layer, seqs, q, budget):
@@ -81,8 +84,11 @@ def _check_attend_selected(pair, layer, seqs, q, sel, cnt, scale):
     (wg.BF16, 32, 8, 128, 16, 256, 6000, 128),      # the paper's budget: 2048 KVs = 128 pages of 16
     (wg.BF16, 4, 4, 64, 32, 64, 700, 5),            # pages larger than a tile, group of one
     (wg.F32, 8, 1, 128, 2, 4, 150, 1000),           # budget larger than the cache: everything is read
-    (wg.F32, 8, 2, 64, 1, 4, 3000, 40),             # more than 2048 pages per head: three turns of the block over the scores
-    (wg.BF16, 8, 2, 128, 4, 16, 7000, 33),          # between 1024 and 2048 pages per head: two turns
+    (wg.F32, 8, 2, 64, 1, 4, 3000, 40),             # thousands of pages per head, fp32 scoring kernel
+    (wg.BF16, 8, 2, 128, 4, 16, 7000, 33),
+    (wg.F32, 8, 2, 64, 1, 4, 6000, 40),             # more than 4096 pages in a head: a second stretch of the selection
+    (wg.BF16, 4, 2, 64, 1, 4, 50000, 700),          # 90K pages in the call: several turns per scoring block, a head with
+                                                    # more blocks than the plan can name, rows shorter than 16 lanes x 16 bytes
 ])
 def test_quest_select_and_attend(dtype, Hq, Hk, d, P, W, T, budget):
     rng = np.random.default_rng(T + budget)
@@ -163,6 +169,14 @@ def test_quest_rejects_bad_arguments():
         pair.pool.quest_select(0, [0], q, lm, 0, 64)                   # no budget
     with pytest.raises(wg.WgkvError):
         pair.pool.quest_select(0, [0], q, lm, 4, 2)                    # score rows shorter than the page count
+    q_off = torch.zeros(4 * 64 + 1, dtype=torch.float32, device=pair.dev)[1:].view(1, 4, 64)
+    with pytest.raises(wg.WgkvError):
+        pair.pool.quest_select(0, [0], q_off, lm, 4, 64)               # queries not 16-byte aligned
+    lm_off = torch.zeros(lm.numel() + 16, dtype=torch.uint8, device=pair.dev)[8:]
+    with pytest.raises(wg.WgkvError):
+        pair.pool.quest_update(0, [0], lm_off)                         # landmarks not 16-byte aligned
+    with pytest.raises(wg.WgkvError):
+        pair.pool.quest_select(0, [0], q, lm_off, 4, 64)
     # indices outside the table are clamped: garbage in, finite numbers out, nothing outside the pool is read
     sel = torch.tensor([[-5, 3, 10 ** 6], [0, 1, 2]], dtype=torch.int32, device=pair.dev)
     cnt = torch.tensor([3, 99], dtype=torch.int32, device=pair.dev)
