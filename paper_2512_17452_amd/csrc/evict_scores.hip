@@ -239,18 +239,22 @@ __global__ __launch_bounds__(512) void evict_stats_mfma_kernel(View pv, CallSeqs
         }
         // register 4j+i of a lane holds key 8j + 4*half + i of the tile
         float x[16], mt = -INFINITY;
-        const int k0 = t * kEmKT + 4 * half;
 #pragma unroll
-        for (int c = 0; c < 16; c++) {
-            x[c] = (k0 + 8 * (c >> 2) + (c & 3) < N) ? s[c] * a.scale_log2e : -INFINITY;
-            mt = fmaxf(mt, x[c]);
+        for (int c = 0; c < 16; c++) x[c] = s[c] * a.scale_log2e;
+        if (t == n_tiles - 1) {  // block-uniform: only the last tile can reach past the end of the cache
+            const int k0 = t * kEmKT + 4 * half;
+#pragma unroll
+            for (int c = 0; c < 16; c++) x[c] = (k0 + 8 * (c >> 2) + (c & 3) < N) ? x[c] : -INFINITY;
         }
+#pragma unroll
+        for (int c = 0; c < 16; c++) mt = fmaxf(mt, x[c]);
         const float mn = fmaxf(m, mt);
         const float ms = mn == -INFINITY ? 0.f : mn;  // this half may hold no valid key of the last tile
+        // the hardware exponential: one instruction, a relative error of about an ulp, 0 for -inf
         float ps = 0.f;
 #pragma unroll
-        for (int c = 0; c < 16; c++) ps += exp2f(x[c] - ms);
-        l = l * exp2f(m - ms) + ps;
+        for (int c = 0; c < 16; c++) ps += __builtin_amdgcn_exp2f(x[c] - ms);
+        l = l * __builtin_amdgcn_exp2f(m - ms) + ps;
         m = mn;
         if (t + 1 < n_tiles) *reinterpret_cast<uint4 *>(&s_k[buf ^ 1][ld_key * kEmRow + ld_c * 16]) = kreg;
         __syncthreads();
@@ -259,17 +263,25 @@ __global__ __launch_bounds__(512) void evict_stats_mfma_kernel(View pv, CallSeqs
     const float m2 = __shfl_xor(m, 32), l2 = __shfl_xor(l, 32);
     const float M = fmaxf(m, m2);  // finite: N > 0
     const float Lsum = l * exp2f(m - M) + l2 * exp2f(m2 - M);
+    // per unit: first n_cols values M + log2(L), what the weight sweep subtracts in the exponent
+    // (exp2(x - M) / L = exp2(x - (M + log2 L))), then the n_cols denominators
     if (half == 0 && col < n_cols) {
-        a.stats[((size_t)u * n_cols + col) * 2 + 0] = M;
-        a.stats[((size_t)u * n_cols + col) * 2 + 1] = Lsum;
+        a.stats[(size_t)u * n_cols * 2 + col] = M + log2f(Lsum);
+        a.stats[(size_t)u * n_cols * 2 + n_cols + col] = Lsum;
     }
 }
 
 constexpr int kEmKeys = 128;  // keys per block of the weight sweep (4 tiles)
 
-__global__ __launch_bounds__(512) void evict_weights_mfma_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
+// The weight sweep forms S = Q K^T, the other way round: rows = 32 query rows of a turn, columns = 32 keys.  A lane
+// then owns one key, and its 16 registers are four observation rows x the four heads of the group: the maximum
+// over the group is a maximum over four registers of the lane (no cross-lane step per weight), the sum over
+// the window a sum inside the lane, then over the two halves of the wave and over the waves, in a fixed order.
+// A block holds 128 keys as matrix operands in registers for all its turns (4 products per query operand
+// loaded); the four waves take the turns of 32 query rows in turn.  n_cols is a multiple of 32 (n_obs of 8).
+__global__ __launch_bounds__(256, 2) void evict_weights_mfma_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
     __shared__ __attribute__((aligned(16))) char s_k[kEmKeys * kEmRow];
-    __shared__ float s_acc[8][kEmKeys];
+    __shared__ float s_acc[4][kEmKeys];
     const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
     const int um = unit_meta(pv, cs.sid[b], a.layer, h);
     const int N = pv.global_len[um], n_cols = a.n_obs * 4;
@@ -277,66 +289,91 @@ __global__ __launch_bounds__(512) void evict_weights_mfma_kernel(View pv, CallSe
     if (key0 >= N) return;  // block-uniform
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, half = lane >> 5;
-    // the block's keys into LDS, zero rows past the end of the cache
-    for (int e = threadIdx.x; e < kEmKeys * 16; e += 512) {
-        const int key = key0 + (e >> 4), c = e & 15;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (key < N)
-            v = *reinterpret_cast<const uint4 *>(page_ptr(pv, pv.global_pt[(size_t)um * pv.maxgp + (key >> pv.logP)]) +
-                                                 (size_t)(key & (pv.P - 1)) * (kEmD * 2) + c * 16);
-        *reinterpret_cast<uint4 *>(&s_k[(e >> 4) * kEmRow + c * 16]) = v;
+    const float *off_u = a.stats + (size_t)u * n_cols * 2;
+    // the first turn's query rows, on their way while the keys are staged
+    es_bf16x8_t qv[8];
+    em_load_q(pv, a, b, h, wave * 32 + n, n_cols, half, qv);
+    // the block's keys into LDS, zero rows past the end of the cache: eight 16-byte pieces per thread, their page
+    // ids requested together and then the pieces together (keys past the end read the last key: no branch around a load)
+    {
+        static_assert(kEmKeys * 16 == 8 * 256, "eight pieces per thread");
+        int pg[8];
+        uint4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int key = min(key0 + ((int)threadIdx.x >> 4) + 16 * j, N - 1);
+            pg[j] = pv.global_pt[(size_t)um * pv.maxgp + (key >> pv.logP)];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int key = min(key0 + ((int)threadIdx.x >> 4) + 16 * j, N - 1);
+            v[j] = *reinterpret_cast<const uint4 *>(page_ptr(pv, pg[j]) + (size_t)(key & (pv.P - 1)) * (kEmD * 2) +
+                                                    (threadIdx.x & 15) * 16);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int kl = ((int)threadIdx.x >> 4) + 16 * j;
+            if (key0 + kl >= N) v[j] = make_uint4(0u, 0u, 0u, 0u);
+            *reinterpret_cast<uint4 *>(&s_k[kl * kEmRow + (threadIdx.x & 15) * 16]) = v[j];
+        }
     }
     __syncthreads();
-    float acc[4][16];
+    es_bf16x8_t kreg[4][8];
 #pragma unroll
     for (int kt = 0; kt < 4; kt++)
 #pragma unroll
-        for (int c = 0; c < 16; c++) acc[kt][c] = 0.f;
-    for (int col0 = wave * 32; col0 < n_cols; col0 += 256) {  // wave-uniform
-        const int col = col0 + n;
-        es_bf16x8_t qv[8];
-        em_load_q(pv, a, b, h, col, n_cols, half, qv);
-        const bool live = col < n_cols;
-        const float mr = a.stats[((size_t)u * n_cols + min(col, n_cols - 1)) * 2 + 0];
-        const float inv = live ? 1.0f / a.stats[((size_t)u * n_cols + min(col, n_cols - 1)) * 2 + 1] : 0.f;
+        for (int ks = 0; ks < 8; ks++)
+            kreg[kt][ks] = *reinterpret_cast<const es_bf16x8_t *>(&s_k[(kt * 32 + n) * kEmRow + (ks * 16 + half * 8) * 2]);
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const int n_turns = n_cols >> 5;
+    for (int qt = wave; qt < n_turns; qt += 4) {  // wave-uniform
+        // the exponent offsets of the turn's rows arrive while its products run
+        float4 off4[4];
 #pragma unroll
-        for (int kt = 0; kt < 4; kt++) {
-            es_f32x16_t s;
+        for (int j = 0; j < 4; j++) off4[j] = *reinterpret_cast<const float4 *>(off_u + qt * 32 + 8 * j + 4 * half);
+        // register 4j+i of a product: query row 8j + 4*half + i of the turn = observation row 2j + half, head i
+        auto weigh = [&](const es_f32x16_t &sc, float &sum) __attribute__((always_inline)) {
 #pragma unroll
-            for (int c = 0; c < 16; c++) s[c] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < 8; ks++) {
-                const es_bf16x8_t ka =
-                    *reinterpret_cast<const es_bf16x8_t *>(&s_k[(kt * 32 + n) * kEmRow + (ks * 16 + half * 8) * 2]);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qv[ks], s, 0, 0, 0);
+            for (int j = 0; j < 4; j++) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[4 * j], a.scale_log2e, -off4[j].x));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[4 * j + 1], a.scale_log2e, -off4[j].y));
+                const float p2 = __builtin_amdgcn_exp2f(fmaf(sc[4 * j + 2], a.scale_log2e, -off4[j].z));
+                const float p3 = __builtin_amdgcn_exp2f(fmaf(sc[4 * j + 3], a.scale_log2e, -off4[j].w));
+                sum += fmaxf(fmaxf(p0, p1), fmaxf(p2, p3));
             }
+        };
+        es_f32x16_t s0, s1;
 #pragma unroll
-            for (int c = 0; c < 16; c++) {
-                float p = exp2f(s[c] * a.scale_log2e - mr) * inv;     // weight of (query row, key)
-                p = fmaxf(p, dpp_f<kDppXor1>(p));                      // maximum over the four heads of the
-                p = fmaxf(p, dpp_f<kDppXor2>(p));                      // observation row: the lanes of a quad
-                acc[kt][c] += p;
-            }
-        }
+        for (int c = 0; c < 16; c++) { s0[c] = 0.f; s1[c] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qv[ks], kreg[0][ks], s0, 0, 0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qv[ks], kreg[1][ks], s1, 0, 0, 0);
+        weigh(s0, acc[0]);
+        es_f32x16_t s2, s3;
+#pragma unroll
+        for (int c = 0; c < 16; c++) { s2[c] = 0.f; s3[c] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qv[ks], kreg[2][ks], s2, 0, 0, 0);
+        weigh(s1, acc[1]);
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) s3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qv[ks], kreg[3][ks], s3, 0, 0, 0);
+        // the turn's products are issued: the next turn's query rows are requested into the same registers
+        // and arrive while the last weights of this turn are formed
+        if (qt + 4 < n_turns) em_load_q(pv, a, b, h, (qt + 4) * 32 + n, n_cols, half, qv);
+        weigh(s2, acc[2]);
+        weigh(s3, acc[3]);
     }
-    // every lane of a quad holds the quad's sum; add the eight quads of a half, then the waves
+    // the two halves of a wave hold different observation rows of the same key; then the waves
 #pragma unroll
-    for (int kt = 0; kt < 4; kt++)
-#pragma unroll
-        for (int c = 0; c < 16; c++) {
-            float v = acc[kt][c];
-            v += __shfl_xor(v, 4);
-            v += __shfl_xor(v, 8);
-            v += __shfl_xor(v, 16);
-            if (n == 0) s_acc[wave][kt * 32 + 8 * (c >> 2) + 4 * half + (c & 3)] = v;
-        }
+    for (int kt = 0; kt < 4; kt++) {
+        const float v = acc[kt] + __shfl_xor(acc[kt], 32);
+        if (half == 0) s_acc[wave][kt * 32 + n] = v;
+    }
     __syncthreads();
-    if (threadIdx.x < kEmKeys && key0 + threadIdx.x < N) {
-        float v = s_acc[0][threadIdx.x];
-#pragma unroll
-        for (int w = 1; w < 8; w++) v += s_acc[w][threadIdx.x];
-        a.raw[(size_t)u * a.stride + key0 + threadIdx.x] = v;
-    }
+    if (threadIdx.x < kEmKeys && key0 + threadIdx.x < N)
+        a.raw[(size_t)u * a.stride + key0 + threadIdx.x] =
+            ((s_acc[0][threadIdx.x] + s_acc[1][threadIdx.x]) + s_acc[2][threadIdx.x]) + s_acc[3][threadIdx.x];
 }
 
 __global__ __launch_bounds__(256) void evict_pool_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
@@ -378,7 +415,7 @@ hipError_t launch_evict_scores(const View &pv, const CallSeqs &cs, int layer, co
         const dim3 g_stats_m((n_rows + 255) / 256, n_units);
         const dim3 g_keys_m((unsigned)((max_len + kEmKeys - 1) / kEmKeys), n_units);
         hipLaunchKernelGGL(evict_stats_mfma_kernel, g_stats_m, dim3(512), 0, st, pv, cs, a);
-        hipLaunchKernelGGL(evict_weights_mfma_kernel, g_keys_m, dim3(512), 0, st, pv, cs, a);
+        hipLaunchKernelGGL(evict_weights_mfma_kernel, g_keys_m, dim3(256), 0, st, pv, cs, a);
     } else if (pv.dtype == WGKV_F32) {
         hipLaunchKernelGGL(evict_stats_kernel<WGKV_F32>, g_stats, dim3(256), 0, st, pv, cs, a);
         hipLaunchKernelGGL(evict_weights_kernel<WGKV_F32>, g_keys, dim3(256), 0, st, pv, cs, a);
