@@ -377,18 +377,26 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dq_kernel(SoftSeqs cs, Soft
         for (int ks = 0; ks < 8; ks++) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], dov[ks], dp, 0, 0, 0);
         // dS^T = P^T (dP^T - D_i), rounded to bf16 for the last product
         uint32_t db_[8];
+        const bool far = t * kSaT + kSaT - 1 <= q0 - a.W;  // every key outside every window of the block: no mask, one bias
 #pragma unroll
         for (int j = 0; j < 4; j++) {
             const float4 bo4 = *reinterpret_cast<const float4 *>(&s_bout[buf][8 * j + 4 * half]);
-            const float4 bi4 = *reinterpret_cast<const float4 *>(&s_bin[buf][8 * j + 4 * half]);
-            const float bo[4] = {bo4.x, bo4.y, bo4.z, bo4.w}, bi[4] = {bi4.x, bi4.y, bi4.z, bi4.w};
+            const float bo[4] = {bo4.x, bo4.y, bo4.z, bo4.w};
             float ds[4];
+            if (far) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const int jg = t * kSaT + 8 * j + 4 * half + i;
-                const float bias = (qi - jg < a.W) ? bi[i] : bo[i];
-                const float x = (jg <= qi) ? fmaf(s[4 * j + i], a.scale_log2e, bias) - lse2 : -INFINITY;
-                ds[i] = __builtin_amdgcn_exp2f(x) * (dp[4 * j + i] - Di);
+                for (int i = 0; i < 4; i++)
+                    ds[i] = __builtin_amdgcn_exp2f(fmaf(s[4 * j + i], a.scale_log2e, bo[i] - lse2)) * (dp[4 * j + i] - Di);
+            } else {
+                const float4 bi4 = *reinterpret_cast<const float4 *>(&s_bin[buf][8 * j + 4 * half]);
+                const float bi[4] = {bi4.x, bi4.y, bi4.z, bi4.w};
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const int jg = t * kSaT + 8 * j + 4 * half + i;
+                    const float bias = (qi - jg < a.W) ? bi[i] : bo[i];
+                    const float x = (jg <= qi) ? fmaf(s[4 * j + i], a.scale_log2e, bias) - lse2 : -INFINITY;
+                    ds[i] = __builtin_amdgcn_exp2f(x) * (dp[4 * j + i] - Di);
+                }
             }
             db_[2 * j] = sa_pack(ds[0], ds[1]);
             db_[2 * j + 1] = sa_pack(ds[2], ds[3]);
@@ -528,7 +536,23 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
             for (int ks = 0; ks < 8; ks++) x = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], own[ks], x, 0, 0, 0);
             // register c = 4j+i of a lane holds query i0 + 8j + 4*half + i
             uint32_t pk[8];
-            if (role == 0) {
+            // wave-uniform: every query of the tile follows every key of this wave by at least the window, so no
+            // pair is masked and every bias is the one outside the window (nearly all tiles of a long sequence)
+            const bool interior = i0 - (j0 + kb * 32 + 31) >= a.W;
+            if (role == 0 && interior) {
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    const float4 l4 = *reinterpret_cast<const float4 *>(&s_lse[it & 1][8 * j + 4 * half]);
+                    const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        x[4 * j + i] = __builtin_amdgcn_exp2f(fmaf(x[4 * j + i], a.scale_log2e, b_out - ls[i]));
+                        s_p[it & 1][kb][4 * j + i][lane] = x[4 * j + i];
+                    }
+                }
+#pragma unroll
+                for (int c = 0; c < 8; c++) pk[c] = sa_pack(x[2 * c], x[2 * c + 1]);
+            } else if (role == 0) {
                 // P = exp2(S * scale + bias - lse); a copy goes to the partner wave through LDS
 #pragma unroll
                 for (int j = 0; j < 4; j++) {
@@ -545,6 +569,22 @@ __global__ __launch_bounds__(512) void soft_attn_bwd_dkv_kernel(SoftSeqs cs, Sof
                 }
 #pragma unroll
                 for (int c = 0; c < 8; c++) pk[c] = sa_pack(x[2 * c], x[2 * c + 1]);
+            } else if (interior) {
+                float dsum = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    const float4 d4 = *reinterpret_cast<const float4 *>(&s_dd[b3p][8 * j + 4 * half]);
+                    const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
+                    float ds[4];
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        ds[i] = s_p[mine & 1][kb][4 * j + i][lane] * (x[4 * j + i] - dd[i]);
+                        dsum += ds[i];
+                    }
+                    pk[2 * j] = sa_pack(ds[0], ds[1]);
+                    pk[2 * j + 1] = sa_pack(ds[2], ds[3]);
+                }
+                dg_acc += follows_out ? dsum : 0.f;
             } else {
                 // dS = P (dP - D_i); the part of it where m_ij follows g_j adds up to dg_j (g_j + eps)
 #pragma unroll
