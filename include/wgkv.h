@@ -380,7 +380,10 @@ int wgkv_quest_update(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int3
 /* Scores every page of every head for the decode queries and picks the pages to read.
  *   q_dev [n_seqs][n_q_heads][head_dim] of cfg.dtype, 16-byte aligned
  *   page_scores_out_dev float [n_seqs * n_kv_heads][score_stride]: U of pages [0, n_pages);
- *                       score_stride must cover the host's bound of every head's page count
+ *                       score_stride must cover the host's bound of every head's page count;
+ *                       where the cache on the device is longer than the host knows (decode
+ *                       steps replayed in a graph since the last wgkv_status), pages from
+ *                       score_stride on are neither scored nor selected
  *   sel_pages_out_dev int32 [n_seqs * n_kv_heads][budget_pages]: ascending indices into the
  *                       head's global page table; sel_count_out_dev int32 [n_seqs * n_kv_heads]
  * fp32 arithmetic.  Errors: INVALID_ARG, HIP. */

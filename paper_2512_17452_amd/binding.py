@@ -334,11 +334,15 @@ class Pool:
         _check(self.L.wgkv_quest_update(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(landmarks), landmarks.numel(),
                                         1 if reset else 0, _stream()), "wgkv_quest_update")
 
-    def quest_select(self, layer, seq_ids, q, landmarks, budget_pages, score_stride):
-        """Returns (page_scores [n_units, score_stride], sel_pages int32 [n_units, budget_pages], sel_count [n_units])."""
+    def quest_select(self, layer, seq_ids, q, landmarks, budget_pages, score_stride, scores=None):
+        """Returns (page_scores [n_units, score_stride], sel_pages int32 [n_units, budget_pages], sel_count [n_units]).
+        scores: the caller's own contiguous float32 buffer of n_units * score_stride elements, else a new one."""
         import torch
         n_units = len(seq_ids) * self.cfg.n_kv_heads
-        scores = torch.zeros((n_units, score_stride), dtype=torch.float32, device=self.device)
+        if scores is None:
+            scores = torch.zeros((n_units, score_stride), dtype=torch.float32, device=self.device)
+        assert scores.is_cuda and scores.is_contiguous() and scores.dtype == torch.float32
+        assert scores.numel() == n_units * score_stride
         sel = torch.full((n_units, budget_pages), -1, dtype=torch.int32, device=self.device)
         cnt = torch.zeros((n_units,), dtype=torch.int32, device=self.device)
         _check(self.L.wgkv_quest_select(self.h, layer, len(seq_ids), _ids(seq_ids), _ptr(q), _ptr(landmarks),

@@ -153,7 +153,8 @@ __global__ __launch_bounds__(256) void quest_score_kernel(View pv, CallSeqs cs, 
     for (int j = 0; j < 4; j++)
         if (j * 256 + (int)threadIdx.x < G * pv.d) s_q[j * 256 + threadIdx.x] = qx[j];
     __syncthreads();
-    const int n_pages = (N + pv.P - 1) >> pv.logP;
+    // never past the caller's score row, whatever the device's length is (the host sized the row from its own bound)
+    const int n_pages = (int)min((long long)((N + pv.P - 1) >> pv.logP), a.score_stride);
     const int n_iter = (n_pages + stride - 1) / stride;  // the same for every lane: no divergence
     for (int it0 = 0; it0 < n_iter; it0 += PF) {
         float acc[G][PF];
@@ -253,7 +254,8 @@ __global__ __launch_bounds__(256) void quest_score_bf16_kernel(View pv, CallSeqs
             qw[g][i] = w;
             qm[g][i] = ((w & 0x8000u) ? 0u : 0xffffu) | ((w & 0x80000000u) ? 0u : 0xffff0000u);  // all ones where q >= 0
         }
-    const int n_pages = (N + pv.P - 1) >> pv.logP;
+    // never past the caller's score row, whatever the device's length is (the host sized the row from its own bound)
+    const int n_pages = (int)min((long long)((N + pv.P - 1) >> pv.logP), a.score_stride);
     for (int it = 0; (int)blockIdx.x * 64 + it * stride < n_pages; it++) {  // block-uniform
         uint32_t lw[PF][4], hw[PF][4];
 #pragma unroll
@@ -342,7 +344,7 @@ __global__ __launch_bounds__(kSelThreads) void quest_select_kernel(View pv, Call
 #pragma unroll
     for (int i = 0; i < kSelOwn; i++)  // clamped, not skipped: no branch around a load, the sixteen are in flight together
         kreg[i] = quest_key(sc[min((long long)(own0 + i), a.score_stride - 1)]);
-    const int n_pages = (N + pv.P - 1) >> pv.logP;
+    const int n_pages = (int)min((long long)((N + pv.P - 1) >> pv.logP), a.score_stride);  // what was scored
     int32_t *sel = a.sel_pages + (size_t)u * a.budget_pages;
     if (n_pages <= a.budget_pages) {  // block-uniform: everything fits the budget
         for (int p = threadIdx.x; p < n_pages; p += kSelThreads) sel[p] = p;

@@ -184,3 +184,59 @@ def test_quest_rejects_bad_arguments():
     pair.pool.attend_selected(0, [0], q, sel, cnt, out, 0.1)
     assert torch.isfinite(out).all()
     pair.check_state()
+
+
+def test_quest_after_replayed_decode_steps_the_host_has_not_seen():
+    """Decode steps replayed in a graph grow the caches without the host's bounds moving; scoring sizes its blocks
+    from those bounds and must still reach the device's last page (more turns per block), and never write past
+    the caller's score row."""
+    rng = np.random.default_rng(29)
+    Hq, Hk, d, P, W, B, T = 4, 2, 64, 1, 4, 2, 120
+    max_gp = T + 400
+    pair = Pair(1, Hq, Hk, d, wg.BF16, P, W, B, max_gp, B * Hk * (max_gp + W) + 8, max_call_seqs=B, max_call_tokens=B * T)
+    dev, seqs = pair.dev, [0, 1]
+    k, v, g = rand_tokens(rng, 2 * T, Hk, d, pair.tdt, rates=[0.7, 0.5])
+    pair.prefill(0, seqs, [T, T], k, v, g, 0.5)
+    k1, v1, g1 = rand_tokens(rng, B, Hk, d, pair.tdt, rates=[0.9] * Hk)
+    pair.decode(0, seqs, k1, v1, g1, 0.5)                    # one eager step: everything is warm before the capture
+    pair.pool.status()
+    kb = torch.zeros((B, Hk, d), dtype=torch.bfloat16, device=dev)
+    vb = torch.zeros_like(kb)
+    gb = torch.zeros((B, Hk), dtype=torch.float32, device=dev)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            pair.pool.decode_step(0, seqs, kb, vb, gb, tau=0.5)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(300):                                      # ~270 more pages per head than the host counts
+        k1, v1, g1 = rand_tokens(rng, B, Hk, d, pair.tdt, rates=[0.9] * Hk)
+        kb.copy_(k1); vb.copy_(v1); gb.copy_(g1)
+        graph.replay()
+        torch.cuda.synchronize()
+        pair.orc.push_tokens(0, seqs, [1] * B, k1.float().numpy(), v1.float().numpy(), g1.numpy(), 0.5)
+    lm = pair.pool.quest_landmarks()
+    pair.pool.quest_update(0, seqs, lm)
+    q = torch.from_numpy(rng.standard_normal((B, Hq, d)).astype(np.float32)).to(pair.tdt)
+    n_pg = [pair.orc.global_len(s, 0, h) for s in seqs for h in range(Hk)]      # P = 1: a page per entry
+    assert min(n_pg) > 300
+    stride = max(n_pg) + 3
+    scores, sel, cnt = pair.pool.quest_select(0, seqs, q.to(dev), lm, 20, stride)
+    scores, sel, cnt = scores.cpu().numpy(), sel.cpu().numpy(), cnt.cpu().numpy()
+    for b, s in enumerate(seqs):
+        for h in range(Hk):
+            u = b * Hk + h
+            ref = pair.orc.quest_page_scores(0, s, h, q[b].float().numpy())
+            assert np.abs(scores[u, :n_pg[u]] - ref).max() <= U_RTOL * max(1.0, float(np.abs(ref).max()))
+            assert np.all(scores[u, n_pg[u]:] == 0)
+            assert cnt[u] == 20 and np.array_equal(sel[u, :20], quest_select(scores[u, :n_pg[u]], 20))
+    # a score row shorter than the device's page count: filled to its end and no further, the selection stays inside it
+    short = min(n_pg) - 50
+    big = torch.full((B * Hk * short + 64,), 7.0, dtype=torch.float32, device=dev)    # 64 guard values behind the rows
+    rows = big[:B * Hk * short].view(B * Hk, short)
+    sc2, sel2, cnt2 = pair.pool.quest_select(0, seqs, q.to(dev), lm, 20, short, scores=rows)
+    assert np.all(big[B * Hk * short:].cpu().numpy() == 7.0)
+    assert np.array_equal(sc2.cpu().numpy(), scores[:, :short])       # no row ran over into the next one either
+    assert int(sel2.max()) < short and np.all(cnt2.cpu().numpy() == 20)
+    pair.check_state()
