@@ -435,7 +435,10 @@ int wgkv_evict_scores(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int3
  * table index.  When to call it (the memory budget) is the caller's policy.
  *   scores_dev : float [n_seqs * n_kv_heads][stride], entry j of the head at
  *                [(b * n_kv_heads + h) * stride + j]; stride must cover the host's
- *                upper bound of every head's length (wgkv_status makes it exact)
+ *                upper bound of every head's length (wgkv_status makes it exact); a head
+ *                whose cache on the device is longer than stride (decode steps replayed
+ *                in a graph since the last wgkv_status) is left as it is, and
+ *                wgkv_evict_scores writes no score past the end of a row
  *   n_evicted_out_dev : optional int32 [n_seqs * n_kv_heads]
  * Errors: INVALID_ARG, WORKSPACE, HIP. */
 int wgkv_evict_apply(wgkv_pool *pool, int32_t layer, int32_t n_seqs, const int32_t *seq_ids_host,

@@ -36,7 +36,8 @@ __global__ __launch_bounds__(kEvictThreads) void evict_compact_kernel(View pv, C
     const int u = blockIdx.x, b = u / pv.Hkv, h = u % pv.Hkv;
     const int um = unit_meta(pv, cs.sid[b], a.layer, h);
     const int N = pv.global_len[um];
-    const int n_e = (int)floor((double)a.frac * (double)N);
+    // a cache longer than the caller's score row (the host's bound was stale): the head is left alone
+    const int n_e = N <= a.stride ? (int)floor((double)a.frac * (double)N) : 0;
     if (threadIdx.x == 0) {
         if (a.n_evicted) a.n_evicted[u] = n_e;
         if (n_e == 0) a.released[u] = 0;

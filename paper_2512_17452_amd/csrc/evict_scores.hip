@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256) void evict_weights_kernel(View pv, CallSeqs cs
     }
     s_part[part][kj] = sum;
     __syncthreads();
-    if (part == 0 && key0 + kj < N)
+    if (part == 0 && key0 + kj < N && key0 + kj < a.stride)  // never past the caller's row, whatever the device's length
         a.raw[(size_t)u * a.stride + key0 + kj] = ((s_part[0][kj] + s_part[1][kj]) + s_part[2][kj]) + s_part[3][kj];
 }
 
@@ -371,14 +371,15 @@ __global__ __launch_bounds__(256, 2) void evict_weights_mfma_kernel(View pv, Cal
         if (half == 0) s_acc[wave][kt * 32 + n] = v;
     }
     __syncthreads();
-    if (threadIdx.x < kEmKeys && key0 + threadIdx.x < N)
+    if (threadIdx.x < kEmKeys && key0 + threadIdx.x < N && key0 + threadIdx.x < a.stride)  // never past the caller's row
         a.raw[(size_t)u * a.stride + key0 + threadIdx.x] =
             ((s_acc[0][threadIdx.x] + s_acc[1][threadIdx.x]) + s_acc[2][threadIdx.x]) + s_acc[3][threadIdx.x];
 }
 
 __global__ __launch_bounds__(256) void evict_pool_kernel(View pv, CallSeqs cs, EvictScoreArgs a) {
     const int u = blockIdx.y, b = u / pv.Hkv, h = u % pv.Hkv;
-    const int N = pv.global_len[unit_meta(pv, cs.sid[b], a.layer, h)];
+    // the part of the cache that fits the caller's rows (all of it unless the host's bound is stale)
+    const int N = (int)min((long long)pv.global_len[unit_meta(pv, cs.sid[b], a.layer, h)], (long long)a.stride);
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= N) return;
     const float *raw = a.raw + (size_t)u * a.stride;
