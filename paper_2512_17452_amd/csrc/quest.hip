@@ -110,6 +110,7 @@ __global__ __launch_bounds__(256) void quest_update_kernel(View pv, CallSeqs cs,
     if (threadIdx.x == 0) a.lm_len[um] = N;
 }
 
+// The general form, launched for fp32 pools (bf16 pools take quest_score_bf16_kernel below).
 // Sixteen lanes per page, four pages per wave at a time and four such turns in flight; a lane reads 16 bytes
 // of the minimum row and of the maximum row of a page, once for the whole group of query heads, whose queries sit
 // in LDS as floats.  The launch is small (1/P of the keys), so its time is what stands in front of its stream:
