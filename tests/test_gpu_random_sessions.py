@@ -1,0 +1,125 @@
+"""Seeded random sessions on one pool: prompts fed in chunks of random lengths to random subsets of the slots in
+random order, decode steps with and without the promotion done ahead, eviction with random scores, slots freed
+and used again, page scoring and selection now and then.  After every few calls the whole cache state (tables,
+free stack, rows) must equal the oracle's bit for bit and the decode attention must match it; shapes, window,
+page size and dtype come from the seed.  Every call is a valid one: the pool is sized for the dense cache."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_17452_amd as wg
+from harness import Pair, rand_q, rand_tokens
+from oracle import quest_select
+
+pytestmark = pytest.mark.gpu
+
+N_CALLS = 24
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_session(seed):
+    rng = np.random.default_rng(9000 + seed)
+    L = int(rng.integers(1, 3))
+    Hk = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    if Hk * G > 32:
+        G = 32 // Hk
+    Hq = Hk * G
+    d = int(rng.choice([64, 128]))
+    dtype = wg.BF16 if rng.random() < 0.6 else wg.F32
+    P = int(rng.choice([1, 2, 4, 8, 16, 32]))
+    W = int(rng.integers(1, 71))
+    S = int(rng.integers(1, 4))
+    max_chunk = 150
+    cap = 900                                             # tokens a slot may see before it is freed
+    max_gp = cap // P + 2
+    nlp = -(-W // P)
+    pair = Pair(L, Hq, Hk, d, dtype, P, W, S, max_gp, S * L * Hk * (max_gp + nlp) + 4, max_call_seqs=S,
+                max_call_tokens=S * max_chunk)
+    scale = 1.0 / math.sqrt(d)
+    seen = [0] * S                                        # tokens fed to each slot (all layers alike)
+    lm = None                                             # landmark buffer once page scoring has been used
+    stale = {(s, l) for s in range(S) for l in range(L)}  # (slot, layer) whose landmarks need a full rebuild
+
+    def some_slots():
+        k = int(rng.integers(1, S + 1))
+        return [int(s) for s in rng.permutation(S)[:k]]
+
+    for call in range(N_CALLS):
+        op = rng.choice(["prefill", "decode", "decode", "evict", "free", "quest"], p=[0.3, 0.2, 0.2, 0.1, 0.1, 0.1])
+        if op == "prefill":
+            seqs = [s for s in some_slots() if seen[s] + max_chunk <= cap]
+            if not seqs:
+                continue
+            lens = [int(rng.integers(0, max_chunk + 1)) for _ in seqs]
+            if sum(lens) == 0:
+                lens[0] = 1
+            rates = list(rng.uniform(0.05, 0.95, Hk))
+            for l in range(L):
+                k, v, g = rand_tokens(rng, max(sum(lens), 1), Hk, d, pair.tdt, rates=rates)
+                pair.prefill(l, seqs, lens, k[:sum(lens)], v[:sum(lens)], g[:sum(lens)], 0.5)
+            for s, n in zip(seqs, lens):
+                seen[s] += n
+        elif op == "decode":
+            seqs = [s for s in some_slots() if 0 < seen[s] < cap - 8]
+            if not seqs:
+                continue
+            for step in range(int(rng.integers(1, 6))):
+                ahead = rng.random() < 0.5
+                if ahead:
+                    pair.pool.decode_promote(seqs, tau=0.5)
+                for l in range(L):
+                    k, v, g = rand_tokens(rng, len(seqs), Hk, d, pair.tdt, rates=[0.7] * Hk)
+                    pair.decode(l, seqs, k, v, g, 0.5)
+                for s in seqs:
+                    seen[s] += 1
+        elif op == "evict":
+            seqs = [s for s in some_slots() if seen[s] > 0]
+            if not seqs:
+                continue
+            pair.pool.status()                            # the host's bounds of the lengths become exact
+            l = int(rng.integers(0, L))
+            n_max = max(pair.orc.global_len(s, l, h) for s in seqs for h in range(Hk))
+            scores = rng.random((len(seqs) * Hk, n_max + 2)).astype(np.float32)
+            scores[rng.random(scores.shape) < 0.2] = 0.25  # ties
+            pair.evict(l, seqs, scores, float(rng.choice([0.0, 0.1, 0.5, 1.0])))
+            stale.update((s, l) for s in seqs)            # entries moved between pages
+        elif op == "free":
+            s = int(rng.integers(0, S))
+            pair.pool.free_seq(s)
+            pair.orc.free_seq(s)
+            seen[s] = 0
+            stale.update((s, l) for l in range(L))        # the slot's next owner starts from nothing
+        else:
+            seqs = [s for s in some_slots() if seen[s] > 0]
+            if not seqs:
+                continue
+            pair.pool.status()
+            if lm is None:
+                lm = pair.pool.quest_landmarks()
+            l = int(rng.integers(0, L))
+            # after an eviction or a freed slot the landmarks are rebuilt from scratch, else only what was appended
+            pair.pool.quest_update(l, seqs, lm, reset=any((s, l) in stale for s in seqs))
+            stale.difference_update((s, l) for s in seqs)
+            q = rand_q(rng, len(seqs), Hq, d, pair.tdt)
+            n_pg = [-(-pair.orc.global_len(s, l, h) // P) for s in seqs for h in range(Hk)]
+            budget = int(rng.integers(1, 12))
+            scores, sel, cnt = pair.pool.quest_select(l, seqs, q.to(pair.dev), lm, budget, max(n_pg) + 1)
+            scores, sel, cnt = scores.cpu().numpy(), sel.cpu().numpy(), cnt.cpu().numpy()
+            for b, s in enumerate(seqs):
+                for h in range(Hk):
+                    u = b * Hk + h
+                    ref = pair.orc.quest_page_scores(l, s, h, q[b].float().numpy())
+                    if n_pg[u]:
+                        assert np.abs(scores[u, :n_pg[u]] - ref).max() <= 2e-5 * max(1.0, float(np.abs(ref).max()))
+                    # the selection is checked against the kernel's own scores: no near-tie can flip it
+                    want = quest_select(scores[u, :n_pg[u]], budget)
+                    assert cnt[u] == len(want) and np.array_equal(sel[u, :cnt[u]], want)
+        if call % 3 == 2 or call == N_CALLS - 1:
+            pair.check_state()
+            live = [s for s in range(S) if seen[s] > 0]
+            if live:
+                for l in range(L):
+                    pair.check_attend(l, live, rand_q(rng, len(live), Hq, d, pair.tdt), scale)
