@@ -85,6 +85,10 @@ CASES = [
     (5, [513], 1, 100, 1e-6, "ends"),        # window not a multiple of the tile, keys far outside it
     (6, [64, 128], 1, 1, 1e-6, "law"),       # window of one: only the token itself is unweighted
     (9, [200], 1, 16, 0.0, "ends"),          # eps = 0: a score of exactly 0 removes the key outside the window
+    # windows one off a tile of 32 keys: where the backward kernels' paths without mask tests begin
+    (11, [257], 1, 33, 1e-6, "ends"),
+    (12, [420, 130], 1, 63, 1e-6, "law"),
+    (13, [257], 1, 96, 1e-6, "law"),
 ]
 
 
