@@ -11,6 +11,7 @@ import torch
 import paper_2512_17452_amd as wg
 from harness import Pair, rand_q, rand_tokens
 from oracle import quest_select
+from test_gpu_prefill_chunks import _flow
 
 pytestmark = pytest.mark.gpu
 
@@ -66,6 +67,16 @@ def test_128_sequences_and_1024_units_in_every_call():
     pair.decode(0, seqs, k, v, g, 0.5)
     pair.check_attend(0, seqs, rand_q(rng, B, Hq, d, pair.tdt), 1.0 / math.sqrt(d))
     pair.check_state()
+
+
+@pytest.mark.parametrize("shape", [(32, 8, 128, wg.BF16),   # matrix-core kernel
+                                   (8, 8, 64, wg.F32)])     # plain kernel
+def test_chunked_prefill_of_128_sequences(shape):
+    """Gate-free flow (scores given): prefill-form attention of every chunk row against the definition, admission
+    state against the oracle, 128 sequences of ragged lengths = 1024 units per call."""
+    rng = np.random.default_rng(1024)
+    lens = [int(x) for x in rng.integers(1, 40, 128)]
+    _flow(128, lens, 16, 8, 4, 64, 77, use_gate=False, shape=shape)
 
 
 def test_one_more_sequence_or_unit_than_a_call_takes_is_refused():
