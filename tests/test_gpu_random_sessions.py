@@ -2,7 +2,8 @@
 random order, decode steps with and without the promotion done ahead, eviction with random scores, slots freed
 and used again, page scoring and selection now and then.  After every few calls the whole cache state (tables,
 free stack, rows) must equal the oracle's bit for bit and the decode attention must match it; shapes, window,
-page size and dtype come from the seed.  Every call is a valid one: the pool is sized for the dense cache."""
+page size and dtype come from the seed (every fifth seed: pages of up to 1024 tokens, windows of 1 to 2500).  Every
+call is a valid one: the pool is sized for the dense cache."""
 import math
 
 import numpy as np
@@ -34,6 +35,10 @@ def test_random_session(seed):
     S = int(rng.integers(1, 4))
     max_chunk = 150
     cap = 900                                             # tokens a slot may see before it is freed
+    if seed % 5 == 4:                                     # pages larger than anything cached, windows of one or of thousands
+        P = int(rng.choice([64, 256, 1024]))
+        W = int(rng.choice([1, 333, 2500]))
+        max_chunk, cap = 700, 3000
     max_gp = cap // P + 2
     nlp = -(-W // P)
     pair = Pair(L, Hq, Hk, d, dtype, P, W, S, max_gp, S * L * Hk * (max_gp + nlp) + 4, max_call_seqs=S,
