@@ -337,13 +337,45 @@ __global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs 
     // The ring slots of this block's leaving tokens that sat in the ring (leaving index < t0 - lo): every row and
     // score the block takes from them has arrived (the stores above used them), for all its threads behind the
     // barrier.  The slot of position p gets the last position of the call that is congruent to p modulo W.
-    const int i_hi = min((int)(blockIdx.x + 1) * kPrefillBlk, min(n_leave, t0 - lo));
-    if ((int)blockIdx.x * kPrefillBlk >= i_hi) return;  // block-uniform
+    // Like the copy above, not a chain of round trips per row: the page ids of the ring go to LDS once (s_gp is free
+    // behind the barrier) and a thread requests kScatterBatch pieces of 16 bytes of K and of V before it stores any.
+    const int i_lo = (int)blockIdx.x * kPrefillBlk;
+    const int i_hi = min(i_lo + kPrefillBlk, min(n_leave, t0 - lo));
+    if (i_lo >= i_hi) return;  // block-uniform
     __syncthreads();
-    for (int i = blockIdx.x * kPrefillBlk + threadIdx.x / lpr; i < i_hi; i += rows_per_pass) {
-        const int pos = lo + i;
-        const int q = pos + pv.W * ((t0 + T - 1 - pos) / pv.W);
-        ring_put(pv, a, um, h, base, t0, q - t0, sub);
+    const bool pt_in_lds = pv.nlp <= kPrefillBlk;  // block-uniform
+    if (pt_in_lds) {
+        for (int i = threadIdx.x; i < pv.nlp; i += 256) s_gp[i] = pv.local_pt[(size_t)um * pv.nlp + i];
+        __syncthreads();
+    }
+    const int n_items = (i_hi - i_lo) * lpr;
+    for (int c0 = 0; c0 < n_items; c0 += 256 * kScatterBatch) {
+        uint4 kk[kScatterBatch], vv[kScatterBatch];
+        float gg[kScatterBatch];
+        char *dst[kScatterBatch];
+        int slot[kScatterBatch];
+#pragma unroll
+        for (int j = 0; j < kScatterBatch; j++) {
+            const int c = min(c0 + j * 256 + (int)threadIdx.x, n_items - 1);  // a piece past the end: the last one again, not stored
+            const int pos = lo + i_lo + c / lpr, sb = c % lpr;
+            const int q = pos + pv.W * ((t0 + T - 1 - pos) / pv.W);
+            const size_t row = (size_t)(base + q - t0) * pv.Hkv + h;
+            kk[j] = *reinterpret_cast<const uint4 *>(a.k + row * pv.row_bytes + sb * 16);
+            vv[j] = *reinterpret_cast<const uint4 *>(a.v + row * pv.row_bytes + sb * 16);
+            gg[j] = a.g[row];
+            slot[j] = pos % pv.W;
+            const int pg = pt_in_lds ? s_gp[slot[j] >> pv.logP] : pv.local_pt[(size_t)um * pv.nlp + (slot[j] >> pv.logP)];
+            dst[j] = page_ptr(pv, pg) + (size_t)(slot[j] & (pv.P - 1)) * pv.row_bytes + sb * 16;
+        }
+#pragma unroll
+        for (int j = 0; j < kScatterBatch; j++) {
+            const int c = c0 + j * 256 + (int)threadIdx.x;
+            if (c < n_items) {
+                *reinterpret_cast<uint4 *>(dst[j]) = kk[j];
+                *reinterpret_cast<uint4 *>(dst[j] + pv.v_off) = vv[j];
+                if (c % lpr == 0) pv.ring_g[(size_t)um * pv.W + slot[j]] = gg[j];
+            }
+        }
     }
 }
 
