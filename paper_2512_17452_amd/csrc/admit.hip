@@ -338,7 +338,7 @@ __global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs 
     // score the block takes from them has arrived (the stores above used them), for all its threads behind the
     // barrier.  The slot of position p gets the last position of the call that is congruent to p modulo W.
     // Like the copy above, not a chain of round trips per row: the page ids of the ring go to LDS once (s_gp is free
-    // behind the barrier) and a thread requests kScatterBatch pieces of 16 bytes of K and of V before it stores any.
+    // behind the barrier) and a thread requests four pieces of 16 bytes of K and of V before it stores any.
     const int i_lo = (int)blockIdx.x * kPrefillBlk;
     const int i_hi = min(i_lo + kPrefillBlk, min(n_leave, t0 - lo));
     if (i_lo >= i_hi) return;  // block-uniform
@@ -349,33 +349,37 @@ __global__ __launch_bounds__(256) void prefill_scatter_kernel(View pv, CallSeqs 
         __syncthreads();
     }
     const int n_items = (i_hi - i_lo) * lpr;
-    for (int c0 = 0; c0 < n_items; c0 += 256 * kScatterBatch) {
-        uint4 kk[kScatterBatch], vv[kScatterBatch];
-        float gg[kScatterBatch];
-        char *dst[kScatterBatch];
-        int slot[kScatterBatch];
-#pragma unroll
-        for (int j = 0; j < kScatterBatch; j++) {
-            const int c = min(c0 + j * 256 + (int)threadIdx.x, n_items - 1);  // a piece past the end: the last one again, not stored
-            const int pos = lo + i_lo + c / lpr, sb = c % lpr;
-            const int q = pos + pv.W * ((t0 + T - 1 - pos) / pv.W);
-            const size_t row = (size_t)(base + q - t0) * pv.Hkv + h;
-            kk[j] = *reinterpret_cast<const uint4 *>(a.k + row * pv.row_bytes + sb * 16);
-            vv[j] = *reinterpret_cast<const uint4 *>(a.v + row * pv.row_bytes + sb * 16);
-            gg[j] = a.g[row];
-            slot[j] = pos % pv.W;
-            const int pg = pt_in_lds ? s_gp[slot[j] >> pv.logP] : pv.local_pt[(size_t)um * pv.nlp + (slot[j] >> pv.logP)];
-            dst[j] = page_ptr(pv, pg) + (size_t)(slot[j] & (pv.P - 1)) * pv.row_bytes + sb * 16;
+    // one piece: 16 bytes of K and of V of the token that takes the slot of leaving position lo + i_lo + c / lpr
+    // (the last position of the call congruent to it modulo W), its score, the slot and the slot's page; a piece
+    // past the end asks for the last one again and is not stored.  Plain variables, written out: an array of
+    // them ends up in scratch memory.
+    auto ask = [&](int c, uint4 &kk, uint4 &vv, float &gg, int &slot, int &pg) __attribute__((always_inline)) {
+        c = min(c, n_items - 1);
+        const int pos = lo + i_lo + c / lpr, sb = c % lpr;
+        const int q = pos + pv.W * ((t0 + T - 1 - pos) / pv.W);
+        const size_t row = (size_t)(base + q - t0) * pv.Hkv + h;
+        kk = *reinterpret_cast<const uint4 *>(a.k + row * pv.row_bytes + sb * 16);
+        vv = *reinterpret_cast<const uint4 *>(a.v + row * pv.row_bytes + sb * 16);
+        gg = a.g[row];
+        slot = pos % pv.W;
+        pg = pt_in_lds ? s_gp[slot >> pv.logP] : pv.local_pt[(size_t)um * pv.nlp + (slot >> pv.logP)];
+    };
+    auto place = [&](int c, const uint4 &kk, const uint4 &vv, float gg, int slot, int pg) __attribute__((always_inline)) {
+        if (c < n_items) {
+            char *dst = page_ptr(pv, pg) + (size_t)(slot & (pv.P - 1)) * pv.row_bytes + (c % lpr) * 16;
+            *reinterpret_cast<uint4 *>(dst) = kk;
+            *reinterpret_cast<uint4 *>(dst + pv.v_off) = vv;
+            if (c % lpr == 0) pv.ring_g[(size_t)um * pv.W + slot] = gg;
         }
-#pragma unroll
-        for (int j = 0; j < kScatterBatch; j++) {
-            const int c = c0 + j * 256 + (int)threadIdx.x;
-            if (c < n_items) {
-                *reinterpret_cast<uint4 *>(dst[j]) = kk[j];
-                *reinterpret_cast<uint4 *>(dst[j] + pv.v_off) = vv[j];
-                if (c % lpr == 0) pv.ring_g[(size_t)um * pv.W + slot[j]] = gg[j];
-            }
-        }
+    };
+    for (int c0 = threadIdx.x; c0 < n_items; c0 += 256 * 4) {
+        uint4 ka, kb, kc, kd, va, vb, vc, vd;
+        float ga, gb, gc, gd;
+        int sa, sb_, sc, sd, pa, pb, pc, pd;
+        ask(c0, ka, va, ga, sa, pa); ask(c0 + 256, kb, vb, gb, sb_, pb);
+        ask(c0 + 512, kc, vc, gc, sc, pc); ask(c0 + 768, kd, vd, gd, sd, pd);
+        place(c0, ka, va, ga, sa, pa); place(c0 + 256, kb, vb, gb, sb_, pb);
+        place(c0 + 512, kc, vc, gc, sc, pc); place(c0 + 768, kd, vd, gd, sd, pd);
     }
 }
 
